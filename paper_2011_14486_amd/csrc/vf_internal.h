@@ -1,0 +1,92 @@
+// Internal declarations of libvf (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "vf.h"
+
+// candidates per partial-argmin slot (one slot per scoring workgroup)
+#define VF_PART 128
+
+struct vf_packed_model {
+  // fp32 path: the caller's blob copied as is
+  float *w_f32 = nullptr;
+  size_t n_floats = 0;
+  // bf16 path: matrices repacked into MFMA A-fragment order, biases and the last
+  // layer's vector as fp32
+  uint16_t *w_pack = nullptr;      // all packed matrices back to back
+  size_t pack_off[8] = {0};        // element offset of each matrix in w_pack
+  float *aux = nullptr;            // biases / head vector, fp32
+  size_t aux_off[8] = {0};         // element offset of each layer's bias in aux
+};
+
+struct vf_ctx {
+  int device = 0;
+  hipStream_t stream = nullptr;
+  int last_hip = 0;
+
+  bool has_space = false, has_pipeline = false, has_model = false;
+  vf_space space;
+  int64_t M = 0, Mpad = 0;
+  int S = 0, B = 0;
+  int n_sched = 0;
+
+  // device tables, all int32 unless noted
+  int32_t *d_space = nullptr;   // [65]
+  int32_t *d_stages = nullptr;  // [B][S][16]
+  int32_t *d_intr = nullptr;    // [B][S][16] intrinsic block of every stage
+  int32_t *d_suffix = nullptr;  // [B][S][2]  sums of macs / points over later stages
+  int32_t *d_states = nullptr;  // [B][S][16]
+  int32_t *d_cf = nullptr;      // [B][S][64] committed core features
+  int32_t *d_prefix = nullptr;  // [B][S+1][2] sums of total_macs / bytes_written over committed stages
+  int32_t *d_cids = nullptr;    // [B][S]
+  float *d_vals = nullptr;      // [B][S]
+  int32_t *d_alive = nullptr;   // [B] 0 once a stage of the problem found no winner
+  int32_t *d_err = nullptr;     // [1] set by a forced commit of an invalid candidate
+  int32_t *d_forced = nullptr;  // [B][S] staging for vf_set_state
+
+  vf_model model;
+  vf_packed_model pm;
+
+  // scratch, grown on demand
+  int32_t *d_feat = nullptr; size_t feat_elems = 0;
+  float *d_act[2] = {nullptr, nullptr}; size_t act_elems = 0;
+  float *d_pval = nullptr; int32_t *d_pidx = nullptr; size_t part_elems = 0;
+
+  hipEvent_t ev0 = nullptr, ev1 = nullptr;
+};
+
+#define VF_HIP(ctx, call)                          \
+  do {                                             \
+    hipError_t e_ = (call);                        \
+    if (e_ != hipSuccess) {                        \
+      (ctx)->last_hip = (int)e_;                   \
+      return VF_EHIP;                              \
+    }                                              \
+  } while (0)
+
+// ---- vf_sched.hip: enumeration, featurization, commit ----
+int vfk_setup_tables(vf_ctx *c);
+int vfk_reset_state(vf_ctx *c);
+int vfk_enumerate(vf_ctx *c, int stage, uint32_t *dec, uint8_t *valid, int32_t *n_valid);
+int vfk_featurize(vf_ctx *c, int stage, int32_t *feat);
+// reduce the per-workgroup partial minima of every problem, report and optionally commit
+int vfk_commit_from_partials(vf_ctx *c, int stage, int nparts, int commit, int32_t *best_cid,
+                             float *best_val);
+int vfk_commit_forced(vf_ctx *c, int stage);
+
+// ---- vf_score.hip: value networks and argmin ----
+int vfk_pack_model(vf_ctx *c, const float *weights_dev);
+void vfk_free_model(vf_ctx *c);
+// Scores nprob problems of M candidates each: x + p*prob_stride is [F][ld].
+// use_valid_row: row 16 of x is the validity flag (invalid -> +inf).
+// Writes scores (nullable, [nprob][ld_scores]) and the partial minima
+// (ctx->d_pval / d_pidx, [nprob][nparts], ids local to the problem).
+int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
+                  int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out);
+int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores, int *nparts_out);
+int vfk_argmin_groups(vf_ctx *c, int64_t M, int nparts, int parts_per_group, int ngroups,
+                      int32_t *best_idx, float *best_val);
+int vfk_ensure_parts(vf_ctx *c, size_t n);

@@ -1,0 +1,698 @@
+// Value networks V(s) and the argmin scan of Algorithm 1 (gfx950).
+//
+// Inputs are raw integer features, candidate-contiguous ([feature][candidate]); they
+// are normalised on load with a piecewise-linear log2 (Sec. 3.2: the network is fed
+// normalised feature values).  Three scorers:
+//   - fp32 MLP: plain FMA kernels, one layer per launch (small models);
+//   - bf16 MLP: the whole layer chain in one kernel per tile of candidates.  The
+//     tile's activations live in LDS as bf16 [candidate][feature]; weights are the
+//     MFMA A operand (output feature = row), activations the B operand (candidate =
+//     column), so the 32x32 accumulator of a lane holds 4x4 consecutive features of
+//     one candidate and goes back to LDS with 8-byte writes.  Weights are repacked
+//     once into A-fragment order and stream from L2 straight into registers;
+//   - bf16 LSTM (Sec. 3.2): per timestep one [4H] x [F+H] contraction per candidate
+//     tile, gates and cell state in fp32 registers, h_t fed back through LDS as
+//     bf16, the per-timestep linear prediction accumulated on the fly.
+// Every scoring workgroup also reduces its candidates to one (value, id) pair: the
+// inner loop "if V(s) < v_i" of Algorithm 1 keeps the first strict minimum, so the
+// reduction orders by value, then by id, and NaN never wins.
+#include "vf_internal.h"
+
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float plog2_dev(int32_t x) {
+  if (x <= 0) return 0.0f;
+  float xf = (float)x;  // round to nearest even
+  uint32_t u = __float_as_uint(xf);
+  int e = (int)(u >> 23) - 127;
+  float frac = __uint_as_float((u & 0x007fffffu) | 0x3f800000u) - 1.0f;  // exact
+  return (float)e + frac;
+}
+
+// float -> bfloat16 bits, round to nearest, ties to even
+__device__ __forceinline__ uint32_t bf16_bits(float v) {
+  uint32_t u = __float_as_uint(v);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return u >> 16;
+}
+__device__ __forceinline__ float bf16_val(float v) { return __uint_as_float(bf16_bits(v) << 16); }
+__device__ __forceinline__ float relu_keep_nan(float v) { return v < 0.0f ? 0.0f : v; }
+
+// (value, id) ordering of the scan: smaller value first, then smaller id; id < 0 = none
+__device__ __forceinline__ void take_min(float &v, int32_t &c, float ov, int32_t oc) {
+  if (oc >= 0 && (ov < v || (ov == v && (c < 0 || oc < c)))) { v = ov; c = oc; }
+}
+__device__ __forceinline__ void wave_min(float &v, int32_t &c) {
+  for (int off = 32; off > 0; off >>= 1) {
+    float ov = __shfl_down(v, off);
+    int32_t oc = __shfl_down(c, off);
+    take_min(v, c, ov, oc);
+  }
+}
+
+// --------------------------------------------------------------- fp32 MLP
+
+// out[o][n] = act(b[o] + sum_k W[o][k] * in[k][n]); one thread per candidate, 16
+// outputs per thread; W and b are uniform across the wave.
+template <bool FIRST>
+__global__ __launch_bounds__(256) void k_mlp_f32_layer(const void *in_, int64_t in_stride, int64_t ld_in,
+                                                       const float *W, const float *bias, float *out,
+                                                       int64_t out_stride, int64_t ld_out, int K, int N,
+                                                       int64_t M, int relu) {
+  const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int o0 = blockIdx.y * 16;
+  const int p = blockIdx.z;
+  if (n >= M) return;
+  float acc[16];
+#pragma unroll
+  for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
+  const int32_t *xi = (const int32_t *)in_ + (size_t)p * in_stride;
+  const float *xf = (const float *)in_ + (size_t)p * in_stride;
+  for (int k = 0; k < K; ++k) {
+    float a = FIRST ? plog2_dev(xi[(size_t)k * ld_in + n]) : xf[(size_t)k * ld_in + n];
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+      if (o0 + j < N) acc[j] = fmaf(W[(size_t)(o0 + j) * K + k], a, acc[j]);
+  }
+#pragma unroll
+  for (int j = 0; j < 16; ++j)
+    if (o0 + j < N) {
+      float v = acc[j] + bias[o0 + j];
+      if (relu) v = relu_keep_nan(v);
+      out[(size_t)p * out_stride + (size_t)(o0 + j) * ld_out + n] = v;
+    }
+}
+
+// One (value, id) pair per block of VF_PART candidates of each problem.
+__global__ __launch_bounds__(VF_PART) void k_argmin_parts(const float *scores, int64_t score_stride,
+                                                          const int32_t *valid_row, int64_t valid_stride,
+                                                          int64_t M, int nparts, float *pval, int32_t *pidx) {
+  __shared__ float sv[VF_PART / 64];
+  __shared__ int32_t sc[VF_PART / 64];
+  const int p = blockIdx.y;
+  const int64_t n = (int64_t)blockIdx.x * VF_PART + threadIdx.x;
+  float v = __builtin_inff();
+  int32_t c = -1;
+  if (n < M) {
+    float s = scores[(size_t)p * score_stride + n];
+    bool ok = valid_row ? valid_row[(size_t)p * valid_stride + n] != 0 : true;
+    if (ok && s < v) { v = s; c = (int32_t)n; }
+  }
+  wave_min(v, c);
+  if ((threadIdx.x & 63) == 0) { sv[threadIdx.x >> 6] = v; sc[threadIdx.x >> 6] = c; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < VF_PART / 64; ++w) take_min(v, c, sv[w], sc[w]);
+    pval[(size_t)p * nparts + blockIdx.x] = v;
+    pidx[(size_t)p * nparts + blockIdx.x] = c;
+  }
+}
+
+// Final scan per group of candidates over the partial minima.
+__global__ __launch_bounds__(64) void k_argmin_groups(const float *pval, const int32_t *pidx, int nparts,
+                                                      int parts_per_group, int32_t *best_idx, float *best_val) {
+  const int g = blockIdx.x;
+  const int lo = g * parts_per_group;
+  int hi = lo + parts_per_group;
+  if (hi > nparts) hi = nparts;
+  float v = __builtin_inff();
+  int32_t c = -1;
+  for (int p = lo + (int)threadIdx.x; p < hi; p += 64) take_min(v, c, pval[p], pidx[p]);
+  wave_min(v, c);
+  if (threadIdx.x == 0) {
+    if (best_idx) best_idx[g] = c;
+    if (best_val) best_val[g] = v;
+  }
+}
+
+// --------------------------------------------------------------- bf16 MLP
+
+struct MlpDev {
+  int L;                 // weight layers; layer L-1 maps to the scalar value
+  int dims[8];
+  const uint16_t *w_pack;
+  size_t pack_off[8];
+  const float *aux;      // biases of every layer, then the last layer's vector
+  size_t bias_off[8];
+  size_t wl_off;
+};
+
+// Repack W[N][K] (fp32, row-major) into MFMA A-fragment order, rounded to bf16:
+// out[tile][kstep][lane][e] = W[tile*32 + lane%32][kstep*16 + 8*(lane/32) + e].
+__global__ __launch_bounds__(256) void k_pack_a(const float *W, int N, int K, uint16_t *out) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)N * K) return;
+  int e = (int)(i & 7), lane = (int)((i >> 3) & 63);
+  size_t rest = i >> 9;
+  int ksteps = K / 16;
+  int s = (int)(rest % ksteps), tile = (int)(rest / ksteps);
+  int row = tile * 32 + (lane & 31), k = s * 16 + 8 * (lane >> 5) + e;
+  out[i] = (uint16_t)bf16_bits(W[(size_t)row * K + k]);
+}
+
+__global__ __launch_bounds__(256) void k_copy_f32(const float *src, float *dst, size_t n, int round_bf16) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) dst[i] = round_bf16 ? bf16_val(src[i]) : src[i];
+}
+
+// The whole MLP for a tile of NC candidates.  8 waves; wave w owns the output
+// row tiles w, w+8, ... (at most RT of them) of every hidden layer and all NC/32
+// candidate column tiles.
+template <int NC, int RT>
+__global__ __launch_bounds__(512) void k_mlp_bf16(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
+                                                  int use_valid_row, MlpDev md, int ks, float *scores,
+                                                  int64_t ld_scores, float *pval, int32_t *pidx, int nparts) {
+  constexpr int CT = NC / 32;
+  constexpr int SEGS = 512 / NC;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t *act = reinterpret_cast<uint16_t *>(smem);                   // [NC][ks]
+  float *red = reinterpret_cast<float *>(smem + (size_t)NC * ks * 2);   // [SEGS][NC]
+  int32_t *okf = reinterpret_cast<int32_t *>(red + SEGS * NC);          // [NC]
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int p = blockIdx.y;
+  const int64_t n0 = (int64_t)blockIdx.x * NC;
+  const int32_t *xp = x + (size_t)p * prob_stride;
+
+  // ---- load: raw int32 [k][n] -> plog2 -> bf16 -> act[n][k]
+  {
+    const int F = md.dims[0];
+    const int n = tid % NC;
+    const bool inb = (n0 + n) < M;
+    for (int k8 = tid / NC; k8 < F / 8; k8 += SEGS) {
+      uint32_t h[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        int32_t raw = inb ? xp[(size_t)(k8 * 8 + e) * ld + n0 + n] : 0;
+        h[e] = bf16_bits(plog2_dev(raw));
+        if (k8 == 2 && e == 0) okf[n] = inb && (!use_valid_row || raw != 0);
+      }
+      uint4 q;
+      q.x = h[0] | h[1] << 16; q.y = h[2] | h[3] << 16; q.z = h[4] | h[5] << 16; q.w = h[6] | h[7] << 16;
+      *reinterpret_cast<uint4 *>(act + (size_t)n * ks + k8 * 8) = q;
+    }
+  }
+  __syncthreads();
+
+  // ---- hidden layers
+  for (int l = 0; l < md.L - 1; ++l) {
+    const int K = md.dims[l], N = md.dims[l + 1];
+    const int ntiles = N / 32, ksteps = K / 16;
+    const uint4 *Wp = reinterpret_cast<const uint4 *>(md.w_pack + md.pack_off[l]);
+    floatx16 acc[RT][CT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[r][c][j] = 0.0f;
+    int mine = 0;
+#pragma unroll
+    for (int r = 0; r < RT; ++r) mine += (w + r * 8 < ntiles);
+    if (mine > 0) {
+      const uint16_t *brow = act + (size_t)(lane & 31) * ks + 8 * (lane >> 5);
+#pragma unroll 2
+      for (int s = 0; s < ksteps; ++s) {
+        uint4 a[RT], b[CT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+          if (r < mine) a[r] = Wp[((size_t)(w + r * 8) * ksteps + s) * 64 + lane];
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+          b[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ks + s * 16);
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+          if (r < mine) {
+#pragma unroll
+            for (int c = 0; c < CT; ++c)
+              acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                  __builtin_bit_cast(bf16x8, a[r]), __builtin_bit_cast(bf16x8, b[c]), acc[r][c], 0, 0, 0);
+          }
+      }
+    }
+    __syncthreads();  // every wave has read the layer's input: it can be overwritten
+    const float *bias = md.aux + md.bias_off[l];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+      if (r < mine) {
+        const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
+#pragma unroll
+          for (int c = 0; c < CT; ++c) {
+            uint32_t h0 = bf16_bits(relu_keep_nan(acc[r][c][4 * g + 0] + bv.x));
+            uint32_t h1 = bf16_bits(relu_keep_nan(acc[r][c][4 * g + 1] + bv.y));
+            uint32_t h2 = bf16_bits(relu_keep_nan(acc[r][c][4 * g + 2] + bv.z));
+            uint32_t h3 = bf16_bits(relu_keep_nan(acc[r][c][4 * g + 3] + bv.w));
+            uint2 q;
+            q.x = h0 | h1 << 16; q.y = h2 | h3 << 16;
+            *reinterpret_cast<uint2 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + mbase + 8 * g) = q;
+          }
+        }
+      }
+    __syncthreads();
+  }
+
+  // ---- last layer: v = w_L . h + b_L, from LDS, in a fixed summation order
+  {
+    const int K = md.dims[md.L - 1];
+    const float *wl = md.aux + md.wl_off;
+    const int n = tid % NC, seg = tid / NC;
+    const int klen = K / SEGS;  // K is a multiple of 32, SEGS of 4 or 8
+    float sum = 0.0f;
+    const uint16_t *row = act + (size_t)n * ks + seg * klen;
+    for (int k = 0; k < klen; k += 4) {
+      uint2 q = *reinterpret_cast<const uint2 *>(row + k);
+      const float4 wv = *reinterpret_cast<const float4 *>(wl + seg * klen + k);
+      sum = fmaf(__uint_as_float(q.x << 16), wv.x, sum);
+      sum = fmaf(__uint_as_float(q.x & 0xffff0000u), wv.y, sum);
+      sum = fmaf(__uint_as_float(q.y << 16), wv.z, sum);
+      sum = fmaf(__uint_as_float(q.y & 0xffff0000u), wv.w, sum);
+    }
+    red[seg * NC + n] = sum;
+  }
+  __syncthreads();
+  {
+    float v = __builtin_inff();
+    int32_t c = -1;
+    if (tid < NC) {
+      float s = md.aux[md.bias_off[md.L - 1]];
+#pragma unroll
+      for (int g = 0; g < SEGS; ++g) s += red[g * NC + tid];
+      if (scores && (n0 + tid) < M) scores[(size_t)p * ld_scores + n0 + tid] = s;
+      if (okf[tid] != 0 && s < v) { v = s; c = (int32_t)(n0 + tid); }
+      wave_min(v, c);
+    }
+    if (NC > 64) {
+      __shared__ float sv[NC / 64];
+      __shared__ int32_t sc[NC / 64];
+      if (tid < NC && lane == 0) { sv[w] = v; sc[w] = c; }
+      __syncthreads();
+      if (tid == 0) {
+        for (int k = 1; k < NC / 64; ++k) take_min(v, c, sv[k], sc[k]);
+        pval[(size_t)p * nparts + blockIdx.x] = v;
+        pidx[(size_t)p * nparts + blockIdx.x] = c;
+      }
+    } else if (tid == 0) {
+      pval[(size_t)p * nparts + blockIdx.x] = v;
+      pidx[(size_t)p * nparts + blockIdx.x] = c;
+    }
+  }
+}
+
+// --------------------------------------------------------------- bf16 LSTM
+
+struct LstmDev {
+  int F, H;
+  const uint16_t *w_pack;  // [unit tile][gate][kstep][lane][8]
+  const float *aux;        // b_ih + b_hh [4H], head vector [H], head bias [1]
+};
+
+// [W_ih | W_hh] as one [4H][F+H] matrix in A-fragment order, grouped so that the four
+// gate row tiles of a tile of 32 hidden units are adjacent.
+__global__ __launch_bounds__(256) void k_pack_lstm(const float *Wih, const float *Whh, int F, int H,
+                                                   uint16_t *out) {
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)4 * H * (F + H)) return;
+  int e = (int)(i & 7), lane = (int)((i >> 3) & 63);
+  size_t rest = i >> 9;
+  int ksteps = (F + H) / 16;
+  int s = (int)(rest % ksteps); rest /= ksteps;
+  int g = (int)(rest % 4), u = (int)(rest / 4);
+  int row = g * H + u * 32 + (lane & 31), k = s * 16 + 8 * (lane >> 5) + e;
+  float v = k < F ? Wih[(size_t)row * F + k] : Whh[(size_t)row * H + (k - F)];
+  out[i] = (uint16_t)bf16_bits(v);
+}
+
+__global__ __launch_bounds__(256) void k_lstm_aux(const float *bih, const float *bhh, const float *wh,
+                                                  const float *bh, int H, float *aux) {
+  int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < 4 * H) aux[i] = bih[i] + bhh[i];
+  else if (i < 5 * H) aux[i] = bf16_val(wh[i - 4 * H]);
+  else if (i == 5 * H) aux[i] = bh[0];
+}
+
+__device__ __forceinline__ float sigmoid_dev(float z) { return __fdividef(1.0f, 1.0f + __expf(-z)); }
+__device__ __forceinline__ float tanh_dev(float z) { return 2.0f * sigmoid_dev(2.0f * z) - 1.0f; }
+
+// One workgroup walks NC sequences through all T steps.  Wave w owns hidden units
+// 32w..32w+31: the four gate row tiles of those units for every candidate column.
+template <int NC, int XPT>
+__global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M, int T, LstmDev md, int xld,
+                                                   int hld, float *scores, float *pval, int32_t *pidx) {
+  constexpr int CT = NC / 32;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t *xs = reinterpret_cast<uint16_t *>(smem);           // [2][NC][xld]
+  uint16_t *hs = xs + (size_t)2 * NC * xld;                    // [NC][hld]
+  float *red = reinterpret_cast<float *>(hs + (size_t)NC * hld);  // [8][NC]
+
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int F = md.F, H = md.H;
+  const int64_t n0 = (int64_t)blockIdx.x * NC;
+  const int cpr = F / 8;                 // 16-byte chunks per sequence row
+  const int nchunks = NC * cpr;          // <= 512 * XPT
+  const int ksx = F / 16, ksteps = (F + H) / 16;
+  const bool active = w < H / 32;
+  const uint4 *Wp = reinterpret_cast<const uint4 *>(md.w_pack) + (size_t)w * 4 * ksteps * 64;
+  const float *bias = md.aux, *wh = md.aux + 4 * H;
+
+  for (int i = tid; i < NC * hld / 2; i += 512) reinterpret_cast<uint32_t *>(hs)[i] = 0u;
+  for (int i = tid; i < 8 * NC; i += 512) red[i] = 0.0f;
+
+  uint4 xr[XPT];
+  auto fetch = [&](int t) {
+#pragma unroll
+    for (int q = 0; q < XPT; ++q) {
+      int ch = tid + q * 512;
+      uint4 v = make_uint4(0u, 0u, 0u, 0u);
+      if (ch < nchunks) {
+        int n = ch / cpr, kc = ch % cpr;
+        if (n0 + n < M) v = *reinterpret_cast<const uint4 *>(x + ((size_t)(n0 + n) * T + t) * F + kc * 8);
+      }
+      xr[q] = v;
+    }
+  };
+  auto stash = [&](int buf) {
+#pragma unroll
+    for (int q = 0; q < XPT; ++q) {
+      int ch = tid + q * 512;
+      if (ch < nchunks) {
+        int n = ch / cpr, kc = ch % cpr;
+        *reinterpret_cast<uint4 *>(xs + ((size_t)buf * NC + n) * xld + kc * 8) = xr[q];
+      }
+    }
+  };
+
+  floatx16 cst[CT];
+  float vsum[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) {
+    vsum[c] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) cst[c][j] = 0.0f;
+  }
+  if (T > 0) { fetch(0); stash(0); }
+  __syncthreads();
+
+  for (int t = 0; t < T; ++t) {
+    if (t + 1 < T) fetch(t + 1);
+    floatx16 acc[4][CT];
+    float hn[CT][16];
+    if (active) {
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+#pragma unroll
+          for (int j = 0; j < 16; ++j) acc[g][c][j] = 0.0f;
+      const uint16_t *xrow = xs + ((size_t)(t & 1) * NC + (lane & 31)) * xld + 8 * (lane >> 5);
+      const uint16_t *hrow = hs + (size_t)(lane & 31) * hld + 8 * (lane >> 5);
+#pragma unroll 2
+      for (int s = 0; s < ksteps; ++s) {
+        uint4 a[4], b[CT];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) a[g] = Wp[((size_t)g * ksteps + s) * 64 + lane];
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+          b[c] = s < ksx ? *reinterpret_cast<const uint4 *>(xrow + (size_t)c * 32 * xld + s * 16)
+                         : *reinterpret_cast<const uint4 *>(hrow + (size_t)c * 32 * hld + (s - ksx) * 16);
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+#pragma unroll
+          for (int c = 0; c < CT; ++c)
+            acc[g][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, a[g]), __builtin_bit_cast(bf16x8, b[c]), acc[g][c], 0, 0, 0);
+      }
+#pragma unroll
+      for (int j = 0; j < 16; ++j) {
+        const int m = w * 32 + 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3);
+        const float bi = bias[m], bf = bias[H + m], bg = bias[2 * H + m], bo = bias[3 * H + m];
+        const float whm = wh[m];
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+          float ig = sigmoid_dev(acc[0][c][j] + bi);
+          float fg = sigmoid_dev(acc[1][c][j] + bf);
+          float gg = tanh_dev(acc[2][c][j] + bg);
+          float og = sigmoid_dev(acc[3][c][j] + bo);
+          float cn = fg * cst[c][j] + ig * gg;
+          cst[c][j] = cn;
+          float h = og * tanh_dev(cn);
+          hn[c][j] = h;
+          vsum[c] = fmaf(whm, h, vsum[c]);
+        }
+      }
+    }
+    __syncthreads();  // h_{t-1} and x_t have been read by every wave
+    if (active) {
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          uint2 q;
+          q.x = bf16_bits(hn[c][4 * g + 0]) | bf16_bits(hn[c][4 * g + 1]) << 16;
+          q.y = bf16_bits(hn[c][4 * g + 2]) | bf16_bits(hn[c][4 * g + 3]) << 16;
+          *reinterpret_cast<uint2 *>(hs + (size_t)(c * 32 + (lane & 31)) * hld + w * 32 + 8 * g + 4 * (lane >> 5)) = q;
+        }
+    }
+    if (t + 1 < T) stash((t + 1) & 1);
+    __syncthreads();
+  }
+
+  // v = sum_t (w . h_t + b): add the two lane halves, then the waves in order
+#pragma unroll
+  for (int c = 0; c < CT; ++c) {
+    float v = vsum[c] + __shfl_xor(vsum[c], 32);
+    if (lane < 32) red[w * NC + c * 32 + lane] = v;
+  }
+  __syncthreads();
+  {
+    float v = __builtin_inff();
+    int32_t cbest = -1;
+    if (tid < NC) {
+      float s = (float)T * md.aux[5 * H];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) s += red[k * NC + tid];
+      const bool inb = (n0 + tid) < M;
+      if (scores && inb) scores[n0 + tid] = s;
+      if (inb && s < v) { v = s; cbest = (int32_t)(n0 + tid); }
+      wave_min(v, cbest);
+    }
+    if (NC > 64) {
+      __shared__ float sv[NC / 64];
+      __shared__ int32_t sc[NC / 64];
+      if (tid < NC && lane == 0) { sv[w] = v; sc[w] = cbest; }
+      __syncthreads();
+      if (tid == 0) {
+        for (int k = 1; k < NC / 64; ++k) take_min(v, cbest, sv[k], sc[k]);
+        pval[blockIdx.x] = v; pidx[blockIdx.x] = cbest;
+      }
+    } else if (tid == 0) {
+      pval[blockIdx.x] = v; pidx[blockIdx.x] = cbest;
+    }
+  }
+}
+
+template <typename T>
+int grow(vf_ctx *c, T *&p, size_t &have, size_t want) {
+  if (want <= have) return VF_OK;
+  if (p) { VF_HIP(c, hipStreamSynchronize(c->stream)); VF_HIP(c, hipFree(p)); p = nullptr; have = 0; }
+  void *q = nullptr;
+  if (hipMalloc(&q, want * sizeof(T)) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
+  p = (T *)q; have = want;
+  return VF_OK;
+}
+
+}  // namespace
+
+int vfk_ensure_parts(vf_ctx *c, size_t n) {
+  if (n <= c->part_elems) return VF_OK;
+  size_t h1 = c->part_elems, h2 = c->part_elems;
+  int rc = grow(c, c->d_pval, h1, n);
+  if (rc != VF_OK) return rc;
+  rc = grow(c, c->d_pidx, h2, n);
+  if (rc != VF_OK) return rc;
+  c->part_elems = n;
+  return VF_OK;
+}
+
+void vfk_free_model(vf_ctx *c) {
+  if (c->pm.w_f32) (void)hipFree(c->pm.w_f32);
+  if (c->pm.w_pack) (void)hipFree(c->pm.w_pack);
+  if (c->pm.aux) (void)hipFree(c->pm.aux);
+  c->pm = vf_packed_model();
+}
+
+int vfk_pack_model(vf_ctx *c, const float *wdev) {
+  const vf_model &m = c->model;
+  vf_packed_model &pm = c->pm;
+  hipStream_t st = c->stream;
+  auto blocks = [](size_t n) { return dim3((unsigned)((n + 255) / 256)); };
+  if (m.kind == VF_MLP && m.dtype == VF_FP32) {
+    size_t n = 0;
+    for (int l = 0; l < m.n_layers; ++l) n += (size_t)m.dims[l] * m.dims[l + 1] + m.dims[l + 1];
+    VF_HIP(c, hipMalloc((void **)&pm.w_f32, n * sizeof(float)));
+    pm.n_floats = n;
+    hipLaunchKernelGGL(k_copy_f32, blocks(n), dim3(256), 0, st, wdev, pm.w_f32, n, 0);
+    VF_HIP(c, hipGetLastError());
+    return VF_OK;
+  }
+  if (m.kind == VF_MLP) {
+    const int L = m.n_layers;
+    size_t npack = 0, naux = 0;
+    for (int l = 0; l < L; ++l) {
+      if (l < L - 1) { pm.pack_off[l] = npack; npack += (size_t)m.dims[l] * m.dims[l + 1]; }
+      pm.aux_off[l] = naux; naux += m.dims[l + 1];
+    }
+    naux = (naux + 3) / 4 * 4;  // keep the last layer's vector 16-byte aligned
+    size_t wl_off = naux;
+    naux += m.dims[L - 1];
+    pm.aux_off[7] = wl_off;
+    if (npack) VF_HIP(c, hipMalloc((void **)&pm.w_pack, npack * sizeof(uint16_t)));
+    VF_HIP(c, hipMalloc((void **)&pm.aux, naux * sizeof(float)));
+    size_t off = 0;
+    for (int l = 0; l < L; ++l) {
+      const int K = m.dims[l], N = m.dims[l + 1];
+      const float *W = wdev + off, *b = W + (size_t)K * N;
+      if (l < L - 1) {
+        hipLaunchKernelGGL(k_pack_a, blocks((size_t)K * N), dim3(256), 0, st, W, N, K, pm.w_pack + pm.pack_off[l]);
+      } else {
+        hipLaunchKernelGGL(k_copy_f32, blocks((size_t)K), dim3(256), 0, st, W, pm.aux + wl_off, (size_t)K, 1);
+      }
+      VF_HIP(c, hipGetLastError());
+      hipLaunchKernelGGL(k_copy_f32, blocks((size_t)N), dim3(256), 0, st, b, pm.aux + pm.aux_off[l], (size_t)N, 0);
+      VF_HIP(c, hipGetLastError());
+      off += (size_t)K * N + N;
+    }
+    return VF_OK;
+  }
+  // LSTM, bf16
+  const int F = m.dims[0], H = m.dims[1];
+  size_t npack = (size_t)4 * H * (F + H);
+  VF_HIP(c, hipMalloc((void **)&pm.w_pack, npack * sizeof(uint16_t)));
+  VF_HIP(c, hipMalloc((void **)&pm.aux, (size_t)(5 * H + 1) * sizeof(float)));
+  const float *Wih = wdev, *Whh = Wih + (size_t)4 * H * F, *bih = Whh + (size_t)4 * H * H;
+  const float *bhh = bih + 4 * H, *wh = bhh + 4 * H, *bh = wh + H;
+  hipLaunchKernelGGL(k_pack_lstm, blocks(npack), dim3(256), 0, st, Wih, Whh, F, H, pm.w_pack);
+  VF_HIP(c, hipGetLastError());
+  hipLaunchKernelGGL(k_lstm_aux, blocks((size_t)5 * H + 1), dim3(256), 0, st, bih, bhh, wh, bh, H, pm.aux);
+  VF_HIP(c, hipGetLastError());
+  return VF_OK;
+}
+
+int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
+                  int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out) {
+  const vf_model &m = c->model;
+  const int L = m.n_layers;
+  hipStream_t st = c->stream;
+  if (m.dtype == VF_FP32) {
+    int maxh = 1;
+    for (int l = 1; l <= L; ++l) if (m.dims[l] > maxh) maxh = m.dims[l];
+    const size_t per_prob = (size_t)maxh * ld;
+    size_t h0 = c->act_elems, h1 = c->act_elems;
+    int rc = grow(c, c->d_act[0], h0, per_prob * nprob);
+    if (rc == VF_OK) rc = grow(c, c->d_act[1], h1, per_prob * nprob);
+    if (rc != VF_OK) return rc;
+    c->act_elems = h0 < h1 ? h0 : h1;
+    const int nparts = (int)((M + VF_PART - 1) / VF_PART);
+    rc = vfk_ensure_parts(c, (size_t)nparts * nprob);
+    if (rc != VF_OK) return rc;
+    const float *wp = c->pm.w_f32;
+    const void *in = x;
+    int64_t in_stride = prob_stride, ld_in = ld;
+    const float *final_scores = nullptr;
+    int64_t final_stride = 0;
+    for (int l = 0; l < L; ++l) {
+      const int K = m.dims[l], N = m.dims[l + 1];
+      const float *W = wp, *b = wp + (size_t)K * N;
+      float *out = c->d_act[l & 1];
+      int64_t out_stride = (int64_t)per_prob, ld_out = ld;
+      if (l == L - 1) {
+        if (scores) { out = scores; out_stride = ld_scores; ld_out = ld_scores; }
+        final_scores = out; final_stride = out_stride;
+      }
+      dim3 grid((unsigned)((M + 255) / 256), (unsigned)((N + 15) / 16), (unsigned)nprob);
+      if (M > 0) {
+        if (l == 0)
+          hipLaunchKernelGGL(k_mlp_f32_layer<true>, grid, dim3(256), 0, st, in, in_stride, ld_in, W, b, out,
+                             out_stride, ld_out, K, N, M, (int)(l < L - 1));
+        else
+          hipLaunchKernelGGL(k_mlp_f32_layer<false>, grid, dim3(256), 0, st, in, in_stride, ld_in, W, b, out,
+                             out_stride, ld_out, K, N, M, (int)(l < L - 1));
+        VF_HIP(c, hipGetLastError());
+      }
+      in = out; in_stride = out_stride; ld_in = ld_out;
+      wp = b + N;
+    }
+    if (nparts > 0) {
+      hipLaunchKernelGGL(k_argmin_parts, dim3((unsigned)nparts, (unsigned)nprob), dim3(VF_PART), 0, st,
+                         final_scores, final_stride, use_valid_row ? x + (size_t)16 * ld : (const int32_t *)nullptr,
+                         prob_stride, M, nparts, c->d_pval, c->d_pidx);
+      VF_HIP(c, hipGetLastError());
+    }
+    *nparts_out = nparts;
+    return VF_OK;
+  }
+  // bf16: one fused kernel
+  int maxw = 0;
+  for (int l = 0; l < L; ++l) if (m.dims[l] > maxw) maxw = m.dims[l];
+  MlpDev md;
+  md.L = L;
+  for (int l = 0; l < 8; ++l) { md.dims[l] = m.dims[l]; md.pack_off[l] = c->pm.pack_off[l]; md.bias_off[l] = c->pm.aux_off[l]; }
+  md.w_pack = c->pm.w_pack; md.aux = c->pm.aux; md.wl_off = c->pm.aux_off[7];
+  const int ks = maxw + 8;
+  const bool wide = maxw > 512;
+  const int NC = wide ? 64 : 128;
+  const int nparts = (int)((M + NC - 1) / NC);
+  int rc = vfk_ensure_parts(c, (size_t)(nparts > 0 ? nparts : 1) * nprob);
+  if (rc != VF_OK) return rc;
+  const size_t smem = (size_t)NC * ks * 2 + (size_t)(512 / NC) * NC * 4 + (size_t)NC * 4;
+  if (nparts > 0) {
+    dim3 grid((unsigned)nparts, (unsigned)nprob);
+    if (wide) {
+      VF_HIP(c, hipFuncSetAttribute((const void *)k_mlp_bf16<64, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      hipLaunchKernelGGL((k_mlp_bf16<64, 4>), grid, dim3(512), smem, st, x, prob_stride, M, ld, use_valid_row, md, ks,
+                         scores, ld_scores, c->d_pval, c->d_pidx, nparts);
+    } else {
+      VF_HIP(c, hipFuncSetAttribute((const void *)k_mlp_bf16<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+      hipLaunchKernelGGL((k_mlp_bf16<128, 2>), grid, dim3(512), smem, st, x, prob_stride, M, ld, use_valid_row, md, ks,
+                         scores, ld_scores, c->d_pval, c->d_pidx, nparts);
+    }
+    VF_HIP(c, hipGetLastError());
+  }
+  *nparts_out = nparts;
+  return VF_OK;
+}
+
+int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores, int *nparts_out) {
+  const vf_model &m = c->model;
+  constexpr int NC = 64;
+  LstmDev md;
+  md.F = m.dims[0]; md.H = m.dims[1]; md.w_pack = c->pm.w_pack; md.aux = c->pm.aux;
+  const int xld = md.F + 8, hld = md.H + 8;
+  const int nparts = (int)((M + NC - 1) / NC);
+  int rc = vfk_ensure_parts(c, (size_t)(nparts > 0 ? nparts : 1));
+  if (rc != VF_OK) return rc;
+  const size_t smem = (size_t)2 * NC * xld * 2 + (size_t)NC * hld * 2 + (size_t)8 * NC * 4;
+  if (nparts > 0) {
+    VF_HIP(c, hipFuncSetAttribute((const void *)k_lstm_bf16<NC, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    hipLaunchKernelGGL((k_lstm_bf16<NC, 4>), dim3((unsigned)nparts), dim3(512), smem, c->stream, x, M, T, md, xld, hld,
+                       scores, c->d_pval, c->d_pidx);
+    VF_HIP(c, hipGetLastError());
+  }
+  *nparts_out = nparts;
+  return VF_OK;
+}
+
+int vfk_argmin_groups(vf_ctx *c, int64_t M, int nparts, int parts_per_group, int ngroups, int32_t *best_idx,
+                      float *best_val) {
+  (void)M;
+  hipLaunchKernelGGL(k_argmin_groups, dim3((unsigned)ngroups), dim3(64), 0, c->stream, c->d_pval, c->d_pidx, nparts,
+                     parts_per_group, best_idx, best_val);
+  VF_HIP(c, hipGetLastError());
+  return VF_OK;
+}

@@ -1,0 +1,150 @@
+"""GPU parity: V(s) scores and the argmin scan against the CPU checker."""
+import numpy as np
+import pytest
+
+from paper_2011_14486_amd import inputs as I
+from tests.util import TOL, check_argmin, score_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vf():
+    import paper_2011_14486_amd as pkg
+    return pkg.load()
+
+
+def raw(F, M, seed, max_log2=20.0):
+    rng = np.random.default_rng(seed)
+    x = np.floor(np.exp2(rng.random((F, M)) * max_log2)).astype(np.int32)
+    x[:, : min(M, 3)] = 0
+    return x
+
+
+def run_mlp(vf, ovf, dims, dtype, M, group, seed, bias_std=0.2, ld=None):
+    import torch
+    ld = M if ld is None else ld
+    x = raw(dims[0], ld, seed)
+    w = I.mlp_weights(dims, seed=seed, bias_std=bias_std)
+    model = I.model_record(I.MLP, dims, dtype)
+    ctx = vf.vf_create(0)
+    vf.vf_set_model(ctx, model, w)
+    xd = torch.from_numpy(x).cuda()
+    scores, bi, bv = vf.vf_score(ctx, xd, vf.VF_X_RAW_I32, M=M, group=group)
+    only_min = vf.vf_score(ctx, xd, vf.VF_X_RAW_I32, M=M, group=group, want_scores=False)
+    torch.cuda.synchronize()
+    scores = scores.cpu().numpy(); bi = bi.cpu().numpy(); bv = bv.cpu().numpy()
+    assert np.array_equal(only_min[1].cpu().numpy(), bi) and np.array_equal(only_min[2].cpu().numpy(), bv)
+    vf.vf_destroy(ctx)
+    ref = ovf.score_mlp(model, w, x, M=M)
+    err = score_err(scores, ref)
+    assert err <= TOL[dtype], f"score error {err}"
+    g = group if group else max(M, 1)
+    for k in range(len(bi)):
+        lo, hi = k * g, min((k + 1) * g, M)
+        check_argmin(int(bi[k]), float(bv[k]), ref[lo:hi], None, TOL[dtype], lo=lo)
+        if bi[k] >= 0:
+            assert bv[k] == scores[bi[k]]
+            # and it is exactly the first minimum of the GPU's own scores
+            blk = scores[lo:hi]
+            assert bi[k] - lo == int(np.argmin(np.where(np.isnan(blk), np.inf, blk)))
+    return err
+
+
+@pytest.mark.parametrize("dims,M,group", [([64, 128, 128, 1], 6000, 0), ([64, 16, 1], 777, 256),
+                                          ([64, 1], 130, 0), ([256, 40, 24, 1], 1000, 128)])
+def test_mlp_fp32(vf, ovf, dims, M, group):
+    run_mlp(vf, ovf, dims, I.FP32, M, group, seed=1)
+
+
+@pytest.mark.parametrize("dims,M,group", [([256, 512, 512, 1], 4096, 0), ([256, 512, 512, 1], 1000, 128),
+                                          ([64, 32, 1], 300, 0), ([64, 128, 128, 1], 6000, 0),
+                                          ([256, 1], 256, 128), ([256, 1024, 1024, 1024, 1], 2048, 1024),
+                                          ([64, 96, 1024, 32, 1], 200, 0), ([256, 512, 512, 1], 1, 0)])
+def test_mlp_bf16(vf, ovf, dims, M, group):
+    run_mlp(vf, ovf, dims, I.BF16, M, group, seed=2)
+
+
+def test_mlp_padded_leading_dimension(vf, ovf):
+    run_mlp(vf, ovf, [64, 64, 1], I.BF16, 333, 0, seed=3, ld=512)
+    run_mlp(vf, ovf, [64, 64, 1], I.FP32, 333, 0, seed=3, ld=512)
+
+
+def test_raw_scoring_workload_sample(vf, ovf):
+    """The 1,048,576-vector scoring workload at full size on the GPU; the checker scores a
+    sample of groups (the first 2 and 2 drawn with a seed) column by column."""
+    import torch
+    dims = [256, 1024, 1024, 1024, 1]
+    G, group = 256, 4096
+    w = I.mlp_weights(dims, 0)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    x = I.raw_feature_matrix(G, 256, group, seed=3)
+    ctx = vf.vf_create(0)
+    vf.vf_set_model(ctx, model, w)
+    xd = torch.from_numpy(x).cuda()
+    scores, bi, bv = vf.vf_score(ctx, xd, vf.VF_X_RAW_I32, group=group)
+    torch.cuda.synchronize()
+    scores = scores.cpu().numpy(); bi = bi.cpu().numpy(); bv = bv.cpu().numpy()
+    vf.vf_destroy(ctx)
+    rng = np.random.default_rng(3)
+    sample = [0, 1] + sorted(rng.choice(np.arange(2, G), 2, replace=False).tolist())
+    for g in sample:
+        blk = I.raw_feature_group(g, 256, group, seed=3)
+        assert np.array_equal(blk, x[:, g * group:(g + 1) * group])
+        ref = ovf.score_mlp(model, w, blk)
+        assert score_err(scores[g * group:(g + 1) * group], ref) <= TOL[1]
+        check_argmin(int(bi[g]), float(bv[g]), ref, None, TOL[1], lo=g * group)
+    # properties that hold for every group at full size
+    sc = scores.reshape(G, group)
+    assert np.isfinite(sc).all()
+    assert np.array_equal(bi, np.arange(G) * group + sc.argmin(1)) and np.array_equal(bv, sc.min(1))
+
+
+def test_score_edge_cases(vf, ovf):
+    import torch
+    dims = [64, 32, 1]
+    ctx = vf.vf_create(0)
+    with pytest.raises(vf.VfError) as e:
+        vf.vf_score(ctx, torch.zeros((64, 8), dtype=torch.int32, device="cuda"))
+    assert e.value.code == vf.VF_ESTATE                       # no model yet
+    for dtype in (I.FP32, I.BF16):
+        w = I.mlp_weights(dims, seed=4)
+        vf.vf_set_model(ctx, I.model_record(I.MLP, dims, dtype), w)
+        x = torch.from_numpy(raw(64, 256, 5)).cuda()
+        s, bi, bv = vf.vf_score(ctx, x, M=0)                   # empty candidate set
+        assert s.numel() == 0 and bi.cpu().tolist() == [-1] and np.isinf(bv.cpu().numpy()[0])
+        with pytest.raises(vf.VfError):
+            vf.vf_score(ctx, x, group=100)                     # group not a multiple of 128
+        wn = w.copy(); wn[:] = np.nan
+        vf.vf_set_model(ctx, I.model_record(I.MLP, dims, dtype), wn)
+        s, bi, bv = vf.vf_score(ctx, x, group=128)
+        assert np.isnan(s.cpu().numpy()).all()                 # NaN scores, and NaN never wins
+        assert bi.cpu().tolist() == [-1, -1] and np.isinf(bv.cpu().numpy()).all()
+        # ties: zero weights make every score equal to the bias; the first id must win
+        wz = np.zeros_like(w); wz[-1] = 1.5
+        vf.vf_set_model(ctx, I.model_record(I.MLP, dims, dtype), wz)
+        s, bi, bv = vf.vf_score(ctx, x, group=128)
+        assert bi.cpu().tolist() == [0, 128] and bv.cpu().tolist() == [1.5, 1.5]
+    with pytest.raises(vf.VfError) as e:
+        vf.vf_set_model(ctx, I.model_record(I.MLP, [64, 30, 1], I.BF16), I.mlp_weights([64, 30, 1]))
+    assert e.value.code == vf.VF_EINVAL                        # bf16 widths must be multiples of 32
+    vf.vf_destroy(ctx)
+
+
+@pytest.mark.parametrize("F,H,T,B", [(128, 256, 50, 256), (32, 32, 3, 100), (64, 96, 1, 64), (128, 256, 7, 1)])
+def test_lstm_bf16(vf, ovf, F, H, T, B):
+    import torch
+    w = I.lstm_weights(F, H, seed=6, bias_std=0.1)
+    model = I.model_record(I.LSTM, [F, H, 1], I.BF16)
+    nseq = (B + 255) // 256 * 256
+    xb = I.feature_sequences(0, nseq, T=T, F=F, seed=4)[:B]
+    ctx = vf.vf_create(0)
+    vf.vf_set_model(ctx, model, w)
+    xd = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
+    s, bi, bv = vf.vf_score(ctx, xd, vf.VF_X_SEQ_BF16)
+    torch.cuda.synchronize()
+    s = s.cpu().numpy()
+    vf.vf_destroy(ctx)
+    ref = ovf.score_lstm(model, w, xb)
+    assert score_err(s, ref) <= TOL[1]
+    check_argmin(int(bi.cpu()[0]), float(bv.cpu()[0]), ref, None, TOL[1])
