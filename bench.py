@@ -1,0 +1,153 @@
+"""Benchmark of the whole hot path on one MI355X.
+
+A step is one complete pass of Algorithm 1 (enumerate, featurize, V(s), argmin, commit
+for every layer) over one batch of synthetic scheduling problems.  Default workload:
+a batch of ResNet-18-shaped 20-stage pipelines, 4096 candidates per decision, 256
+features, MLP 256-512-512-1 in bf16 with fp32 accumulation.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+
+
+def mlp_flops(dims):
+    return 2 * sum(dims[k] * dims[k + 1] for k in range(len(dims) - 1))
+
+
+def cpu_baseline(I, pipe, space, model, w, dims):
+    """The CPU checker, as it stands, on one pipeline of the batch (bounded sample)."""
+    from oracle import ovf
+    S = len(pipe)
+    M = ovf.dense_count(space)
+    t0 = time.perf_counter()
+    ovf.greedy(pipe, space, model, w)
+    dt = time.perf_counter() - t0
+    return {"value": S * M / dt, "unit": "candidates/s", "cores": ovf.num_threads(), "kind": "oracle",
+            "sample": f"one pipeline of the batch (problem 0: {S} decisions x {M} candidate ids, "
+                      f"features + V(s) for the valid ones + argmin), {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--batch", type=int, default=256, help="independent pipelines per step")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-latency", action="store_true", help="skip the single-pipeline latency measurement")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import paper_2011_14486_amd as pkg
+    from paper_2011_14486_amd import inputs as I
+    vf = pkg.load()
+
+    B = args.batch
+    dims = [256, 512, 512, 1]
+    pipes = I.resnet18_batch(B, seed=2)
+    space = I.resnet18_space()
+    S, M = pipes.shape[1], I.space_dense_count(space)
+    w = I.mlp_weights(dims, 0)
+    model = I.model_record(I.MLP, dims, I.BF16)
+
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, space)
+    vf.vf_set_pipeline(ctx, pipes)
+    vf.vf_set_model(ctx, model, w)
+    out = (ctx.empty((B, S, 16), torch.int32), ctx.empty((B, S), torch.int32), ctx.empty((B, S), torch.float32))
+
+    def step():
+        vf.vf_reset_state(ctx)
+        vf.vf_greedy_schedule(ctx, 0, S - 1, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    vf.vf_profile_enable(ctx, True)
+    for k in (0, 1, 2):
+        vf.vf_profile_read(ctx, k)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    vf.vf_profile_enable(ctx, False)
+    ms_feat, n_feat = vf.vf_profile_read(ctx, vf.VF_PROF_FEATURIZE)
+    ms_score, n_score = vf.vf_profile_read(ctx, vf.VF_PROF_SCORE)
+    ms_commit, n_commit = vf.vf_profile_read(ctx, vf.VF_PROF_COMMIT)
+    cids = out[1].cpu().numpy()
+    assert (cids >= 0).all(), "a schedule ended early"
+
+    cand_per_step = B * S * M
+    value = cand_per_step * args.steps / dt
+
+    # dominant kernel: the fused MLP scorer (dense contraction -> MFMA roofline)
+    flops_per_launch = mlp_flops(dims) * B * M
+    score_ms = ms_score / max(n_score, 1)
+    achieved = flops_per_launch / (score_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "k_mlp_bf16", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "launch_ms": score_ms, "launches": n_score}
+    feat_bytes = 4 * 256 * B * M
+    feat_ms = ms_feat / max(n_feat, 1)
+    feat_gbs = feat_bytes / (feat_ms * 1e-3) / 1e9
+    roofline_feat = {"bound": "hbm", "kernel": "k_featurize", "achieved": feat_gbs, "peak": PEAK_HBM_GBS,
+                     "unit": "GB/s", "frac": feat_gbs / PEAK_HBM_GBS, "traffic": None,
+                     "launch_ms": feat_ms, "launches": n_feat}
+
+    # latency of one pipeline alone (the single-network case of Algorithm 1)
+    single_ms = None
+    if not args.no_latency:
+        ctx1 = vf.vf_create(0)
+        vf.vf_set_space(ctx1, space); vf.vf_set_pipeline(ctx1, pipes[0]); vf.vf_set_model(ctx1, model, w)
+        for _ in range(3):
+            vf.vf_reset_state(ctx1); vf.vf_greedy_schedule(ctx1)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        reps = 10
+        for _ in range(reps):
+            vf.vf_reset_state(ctx1); vf.vf_greedy_schedule(ctx1)
+        torch.cuda.synchronize()
+        single_ms = (time.perf_counter() - t1) / reps * 1e3
+        vf.vf_destroy(ctx1)
+
+    line = {
+        "metric": "candidate schedules scored/sec (V(s) eval) + end-to-end greedy schedule ms",
+        "value": value, "unit": "candidates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"ResNet-18-shaped pipelines, {S} stages, {M} candidates per decision, F=256, "
+                               f"MLP 256-512-512-1 bf16 weights/activations with fp32 accumulation; batch of {B} "
+                               "independent pipelines per step (problem 0 has the standard shapes, the others "
+                               "seeded width/resolution variants)",
+                   "batch": B, "stages": S, "candidates_per_decision": M, "candidates_per_step": cand_per_step},
+        "greedy_ms_single_pipeline": single_ms,
+        "kernel_ms_per_step": {"featurize": ms_feat / args.steps, "score": ms_score / args.steps,
+                               "commit": ms_commit / args.steps},
+        "roofline": roofline,
+        "roofline_featurize": roofline_feat,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(I, pipes[0], space, model, w, dims)
+    vf.vf_destroy(ctx)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -110,8 +110,9 @@ int vf_set_pipeline(vf_ctx *ctx, const vf_stage *stages_host, int n_stages, int 
  * LSTM  W_ih[4H][F], W_hh[4H][H], b_ih[4H], b_hh[4H], w_head[H], b_head[1] with the
  * four gate blocks in the order i, f, g, o.  With VF_BF16 the library rounds the
  * matrices (and w_head) to bfloat16, ties to even; biases stay fp32.
- * VF_BF16 needs every MLP width except the last to be a multiple of 32 (LSTM: F a
- * multiple of 32, H a multiple of 64).  VF_LSTM supports VF_BF16 only. */
+ * VF_BF16 needs every MLP width except the last to be a multiple of 32 and at most
+ * 1024 (LSTM: F and H multiples of 32, at most 256).  VF_LSTM supports VF_BF16 only.
+ * Anything else is VF_EINVAL. */
 int vf_set_model(vf_ctx *ctx, const vf_model *model_host, const float *weights_dev, size_t n_floats);
 
 /* s_0 = InitialState of Algorithm 1: nothing scheduled. */
@@ -188,6 +189,14 @@ int vf_last_hip_error(const vf_ctx *ctx);
 int vf_timer_start(vf_ctx *ctx);
 int vf_timer_stop(vf_ctx *ctx);
 int vf_timer_elapsed_ms(vf_ctx *ctx, float *ms_host);
+/* Per-kernel timing for benchmarks.  While enabled, vf_featurize, vf_score,
+ * vf_argmin_step and vf_greedy_schedule bracket each launch of their featurize
+ * (which = 0), scoring (1) and commit (2) kernels with HIP events on the context's
+ * stream.  vf_profile_read synchronises, returns the summed duration and the number
+ * of launches of one kind since the last read of that kind, and clears them. */
+enum { VF_PROF_FEATURIZE = 0, VF_PROF_SCORE = 1, VF_PROF_COMMIT = 2 };
+int vf_profile_enable(vf_ctx *ctx, int enable);
+int vf_profile_read(vf_ctx *ctx, int which, double *total_ms_host, int64_t *launches_host);
 
 #ifdef __cplusplus
 }

@@ -24,6 +24,7 @@ EXPORTS = [
     "vf_set_state", "vf_n_scheduled", "vf_dense_count", "vf_padded_count", "vf_enumerate",
     "vf_featurize", "vf_score", "vf_argmin_step", "vf_greedy_schedule", "vf_strerror",
     "vf_last_hip_error", "vf_timer_start", "vf_timer_stop", "vf_timer_elapsed_ms",
+    "vf_profile_enable", "vf_profile_read",
 ]
 
 _lib = None
@@ -76,6 +77,8 @@ def lib():
         L.vf_timer_start.argtypes = [vp]
         L.vf_timer_stop.argtypes = [vp]
         L.vf_timer_elapsed_ms.argtypes = [vp, C.POINTER(C.c_float)]
+        L.vf_profile_enable.argtypes = [vp, C.c_int]
+        L.vf_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
         _lib = L
     return _lib
 
@@ -260,3 +263,17 @@ def vf_timer_elapsed_ms(ctx):
     ms = C.c_float()
     _check(ctx, lib().vf_timer_elapsed_ms(ctx.handle, C.byref(ms)))
     return float(ms.value)
+
+
+VF_PROF_FEATURIZE, VF_PROF_SCORE, VF_PROF_COMMIT = 0, 1, 2
+
+
+def vf_profile_enable(ctx, enable=True):
+    _check(ctx, lib().vf_profile_enable(ctx.handle, 1 if enable else 0))
+
+
+def vf_profile_read(ctx, which):
+    """Returns (total milliseconds, launches) of one kernel kind since the last read."""
+    ms, n = C.c_double(), C.c_int64()
+    _check(ctx, lib().vf_profile_read(ctx.handle, which, C.byref(ms), C.byref(n)))
+    return float(ms.value), int(n.value)

@@ -177,6 +177,9 @@ void vf_destroy(vf_ctx *c) {
     if (p) (void)hipFree(p);
   if (c->ev0) (void)hipEventDestroy(c->ev0);
   if (c->ev1) (void)hipEventDestroy(c->ev1);
+  for (auto &v : c->prof_pairs)
+    for (hipEvent_t e : v) (void)hipEventDestroy(e);
+  for (hipEvent_t e : c->prof_free) (void)hipEventDestroy(e);
   delete c;
 }
 
@@ -399,6 +402,30 @@ int vf_timer_elapsed_ms(vf_ctx *c, float *ms) {
   DeviceGuard g(c->device);
   VF_HIP(c, hipEventSynchronize(c->ev1));
   VF_HIP(c, hipEventElapsedTime(ms, c->ev0, c->ev1));
+  return VF_OK;
+}
+
+int vf_profile_enable(vf_ctx *c, int enable) {
+  if (!c) return VF_EINVAL;
+  c->profiling = enable != 0;
+  return VF_OK;
+}
+
+int vf_profile_read(vf_ctx *c, int which, double *total_ms, int64_t *launches) {
+  if (!c || which < 0 || which > 2) return VF_EINVAL;
+  DeviceGuard g(c->device);
+  auto &v = c->prof_pairs[which];
+  double sum = 0.0;
+  for (size_t k = 0; k + 1 < v.size(); k += 2) {
+    VF_HIP(c, hipEventSynchronize(v[k + 1]));
+    float ms = 0.0f;
+    VF_HIP(c, hipEventElapsedTime(&ms, v[k], v[k + 1]));
+    sum += ms;
+  }
+  if (total_ms) *total_ms = sum;
+  if (launches) *launches = (int64_t)(v.size() / 2);
+  for (hipEvent_t e : v) c->prof_free.push_back(e);
+  v.clear();
   return VF_OK;
 }
 

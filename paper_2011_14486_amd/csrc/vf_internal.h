@@ -5,6 +5,8 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <vector>
+
 #include "vf.h"
 
 // candidates per partial-argmin slot (one slot per scoring workgroup)
@@ -56,6 +58,40 @@ struct vf_ctx {
   float *d_pval = nullptr; int32_t *d_pidx = nullptr; size_t part_elems = 0;
 
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
+
+  // per-kernel timing (benchmarks): event pairs recorded around launches
+  bool profiling = false;
+  std::vector<hipEvent_t> prof_pairs[3];  // begin, end, begin, end, ...
+  std::vector<hipEvent_t> prof_free;
+};
+
+// Brackets one kernel launch with events when profiling is on.
+struct vf_prof_scope {
+  vf_ctx *c;
+  int which;
+  hipEvent_t e1 = nullptr;
+  vf_prof_scope(vf_ctx *ctx, int w) : c(ctx), which(w) {
+    if (!c->profiling) return;
+    hipEvent_t e0 = take();
+    e1 = take();
+    if (!e0 || !e1) { e1 = nullptr; return; }
+    (void)hipEventRecord(e0, c->stream);
+    c->prof_pairs[which].push_back(e0);
+    c->prof_pairs[which].push_back(e1);
+  }
+  ~vf_prof_scope() {
+    if (e1) (void)hipEventRecord(e1, c->stream);
+  }
+  hipEvent_t take() {
+    if (!c->prof_free.empty()) {
+      hipEvent_t e = c->prof_free.back();
+      c->prof_free.pop_back();
+      return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+  }
 };
 
 #define VF_HIP(ctx, call)                          \

@@ -458,6 +458,7 @@ int vfk_enumerate(vf_ctx *c, int stage, uint32_t *dec, uint8_t *valid, int32_t *
 }
 
 int vfk_featurize(vf_ctx *c, int stage, int32_t *feat) {
+  vf_prof_scope prof(c, VF_PROF_FEATURIZE);
   dim3 grid((unsigned)(c->Mpad / 256), (unsigned)c->B);
   hipLaunchKernelGGL(k_featurize, grid, dim3(256), 0, c->stream, tables_of(c), stage, (uint32_t)c->M,
                      (uint32_t)c->Mpad, (int)c->space.F, feat);
@@ -466,6 +467,7 @@ int vfk_featurize(vf_ctx *c, int stage, int32_t *feat) {
 }
 
 int vfk_commit_from_partials(vf_ctx *c, int stage, int nparts, int commit, int32_t *best_cid, float *best_val) {
+  vf_prof_scope prof(c, VF_PROF_COMMIT);
   hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), stage, nparts, c->d_pval,
                      c->d_pidx, (const int32_t *)nullptr, commit, (uint32_t)c->M, best_cid, best_val);
   VF_HIP(c, hipGetLastError());

@@ -652,6 +652,7 @@ int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, i
   if (rc != VF_OK) return rc;
   const size_t smem = (size_t)NC * ks * 2 + (size_t)(512 / NC) * NC * 4 + (size_t)NC * 4;
   if (nparts > 0) {
+    vf_prof_scope prof(c, VF_PROF_SCORE);
     dim3 grid((unsigned)nparts, (unsigned)nprob);
     if (wide) {
       VF_HIP(c, hipFuncSetAttribute((const void *)k_mlp_bf16<64, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
@@ -679,6 +680,7 @@ int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores
   if (rc != VF_OK) return rc;
   const size_t smem = (size_t)2 * NC * xld * 2 + (size_t)NC * hld * 2 + (size_t)8 * NC * 4;
   if (nparts > 0) {
+    vf_prof_scope prof(c, VF_PROF_SCORE);
     VF_HIP(c, hipFuncSetAttribute((const void *)k_lstm_bf16<NC, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     hipLaunchKernelGGL((k_lstm_bf16<NC, 4>), dim3((unsigned)nparts), dim3(512), smem, c->stream, x, M, T, md, xld, hld,
                        scores, c->d_pval, c->d_pidx);
