@@ -22,6 +22,12 @@ struct vf_packed_model {
   size_t pack_off[8] = {0};        // element offset of each matrix in w_pack
   float *aux = nullptr;            // biases / head vector, fp32
   size_t aux_off[8] = {0};         // element offset of each layer's bias in aux
+  // bf16 MLPs whose hidden layers all have 512 (fast_rt = 2) or 1024 (fast_rt = 4)
+  // units: the same matrices once more, ordered as one contiguous fragment stream
+  // per wave over all hidden layers
+  uint16_t *w_stream = nullptr;
+  size_t wave_stride = 0;          // 16-byte units between the streams of two waves
+  int fast_rt = 0;
 };
 
 struct vf_ctx {

@@ -16,6 +16,8 @@
 // Every scoring workgroup also reduces its candidates to one (value, id) pair: the
 // inner loop "if V(s) < v_i" of Algorithm 1 keeps the first strict minimum, so the
 // reduction orders by value, then by id, and NaN never wins.
+#include <stdlib.h>
+
 #include "vf_internal.h"
 
 namespace {
@@ -159,10 +161,28 @@ __global__ __launch_bounds__(256) void k_copy_f32(const float *src, float *dst, 
   if (i < n) dst[i] = round_bf16 ? bf16_val(src[i]) : src[i];
 }
 
-// The whole MLP for a tile of NC candidates.  8 waves; wave w owns the output
-// row tiles w, w+8, ... (at most RT of them) of every hidden layer and all NC/32
-// candidate column tiles.
-template <int NC, int RT>
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
+
+// two floats -> packed bfloat16 pair (round to nearest even, v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  floatx2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+// ReLU on the bit pattern: negative values (sign bit set, including -0) become +0,
+// everything else, NaN included, is kept
+__device__ __forceinline__ float relu_bits(float v) {
+  int32_t i = __float_as_int(v);
+  return __int_as_float(i < 0 ? 0 : i);
+}
+
+// The whole MLP for a tile of NC candidates.  8 waves; wave w owns the output row
+// tiles w, w+8, ... (at most RT of them) of every hidden layer and all NC/32 candidate
+// column tiles.  The weight fragments of a wave form one stream over all layers; a
+// ring of PD k-steps of them is kept in flight so that L2 latency is hidden, also
+// across the layer boundaries and behind the feature load.  The last hidden layer is
+// never written back: its epilogue multiplies with the output vector directly.
+template <int NC, int RT, int PD>
 __global__ __launch_bounds__(512) void k_mlp_bf16(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
                                                   int use_valid_row, MlpDev md, int ks, float *scores,
                                                   int64_t ld_scores, float *pval, int32_t *pidx, int nparts) {
@@ -170,13 +190,30 @@ __global__ __launch_bounds__(512) void k_mlp_bf16(const int32_t *x, int64_t prob
   constexpr int SEGS = 512 / NC;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t *act = reinterpret_cast<uint16_t *>(smem);                   // [NC][ks]
-  float *red = reinterpret_cast<float *>(smem + (size_t)NC * ks * 2);   // [SEGS][NC]
-  int32_t *okf = reinterpret_cast<int32_t *>(red + SEGS * NC);          // [NC]
+  float *red = reinterpret_cast<float *>(smem + (size_t)NC * ks * 2);   // [8][NC]
+  int32_t *okf = reinterpret_cast<int32_t *>(red + 8 * NC);             // [NC]
 
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   const int p = blockIdx.y;
   const int64_t n0 = (int64_t)blockIdx.x * NC;
   const int32_t *xp = x + (size_t)p * prob_stride;
+  const int NH = md.L - 1;  // hidden layers
+
+  // ---- weight stream: prefetch cursor (layer, k-step) runs PD steps ahead
+  uint4 ring[PD][RT];
+  int pf_l = 0, pf_s = 0;
+  auto prefetch = [&](int j) {
+    if (pf_l < NH) {
+      const int ksteps = md.dims[pf_l] / 16, ntiles = md.dims[pf_l + 1] / 32;
+      const uint4 *Wp = reinterpret_cast<const uint4 *>(md.w_pack + md.pack_off[pf_l]);
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+        if (w + r * 8 < ntiles) ring[j][r] = Wp[((size_t)(w + r * 8) * ksteps + pf_s) * 64 + lane];
+      if (++pf_s == ksteps) { pf_s = 0; ++pf_l; }
+    }
+  };
+#pragma unroll
+  for (int j = 0; j < PD; ++j) prefetch(j);
 
   // ---- load: raw int32 [k][n] -> plog2 -> bf16 -> act[n][k]
   {
@@ -184,25 +221,28 @@ __global__ __launch_bounds__(512) void k_mlp_bf16(const int32_t *x, int64_t prob
     const int n = tid % NC;
     const bool inb = (n0 + n) < M;
     for (int k8 = tid / NC; k8 < F / 8; k8 += SEGS) {
-      uint32_t h[8];
+      float h[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         int32_t raw = inb ? xp[(size_t)(k8 * 8 + e) * ld + n0 + n] : 0;
-        h[e] = bf16_bits(plog2_dev(raw));
+        h[e] = plog2_dev(raw);
         if (k8 == 2 && e == 0) okf[n] = inb && (!use_valid_row || raw != 0);
       }
       uint4 q;
-      q.x = h[0] | h[1] << 16; q.y = h[2] | h[3] << 16; q.z = h[4] | h[5] << 16; q.w = h[6] | h[7] << 16;
+      q.x = pack_bf16(h[0], h[1]); q.y = pack_bf16(h[2], h[3]);
+      q.z = pack_bf16(h[4], h[5]); q.w = pack_bf16(h[6], h[7]);
       *reinterpret_cast<uint4 *>(act + (size_t)n * ks + k8 * 8) = q;
     }
   }
   __syncthreads();
 
   // ---- hidden layers
-  for (int l = 0; l < md.L - 1; ++l) {
+  float dot[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
+  for (int l = 0; l < NH; ++l) {
     const int K = md.dims[l], N = md.dims[l + 1];
     const int ntiles = N / 32, ksteps = K / 16;
-    const uint4 *Wp = reinterpret_cast<const uint4 *>(md.w_pack + md.pack_off[l]);
     floatx16 acc[RT][CT];
 #pragma unroll
     for (int r = 0; r < RT; ++r)
@@ -213,57 +253,89 @@ __global__ __launch_bounds__(512) void k_mlp_bf16(const int32_t *x, int64_t prob
     int mine = 0;
 #pragma unroll
     for (int r = 0; r < RT; ++r) mine += (w + r * 8 < ntiles);
-    if (mine > 0) {
-      const uint16_t *brow = act + (size_t)(lane & 31) * ks + 8 * (lane >> 5);
-#pragma unroll 2
-      for (int s = 0; s < ksteps; ++s) {
+    const uint16_t *brow = act + (size_t)(lane & 31) * ks + 8 * (lane >> 5);
+    for (int s0 = 0; s0 < ksteps; s0 += PD) {  // ksteps is a multiple of PD (host checks)
+#pragma unroll
+      for (int j = 0; j < PD; ++j) {
         uint4 a[RT], b[CT];
 #pragma unroll
-        for (int r = 0; r < RT; ++r)
-          if (r < mine) a[r] = Wp[((size_t)(w + r * 8) * ksteps + s) * 64 + lane];
+        for (int r = 0; r < RT; ++r) a[r] = ring[j][r];
+        prefetch(j);
+        if (mine > 0) {
 #pragma unroll
-        for (int c = 0; c < CT; ++c)
-          b[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ks + s * 16);
+          for (int c = 0; c < CT; ++c)
+            b[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ks + (s0 + j) * 16);
 #pragma unroll
-        for (int r = 0; r < RT; ++r)
-          if (r < mine) {
+          for (int r = 0; r < RT; ++r)
+            if (r < mine) {
 #pragma unroll
-            for (int c = 0; c < CT; ++c)
-              acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                  __builtin_bit_cast(bf16x8, a[r]), __builtin_bit_cast(bf16x8, b[c]), acc[r][c], 0, 0, 0);
-          }
-      }
-    }
-    __syncthreads();  // every wave has read the layer's input: it can be overwritten
-    const float *bias = md.aux + md.bias_off[l];
-#pragma unroll
-    for (int r = 0; r < RT; ++r)
-      if (r < mine) {
-        const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
-#pragma unroll
-          for (int c = 0; c < CT; ++c) {
-            uint32_t h0 = bf16_bits(relu_keep_nan(acc[r][c][4 * g + 0] + bv.x));
-            uint32_t h1 = bf16_bits(relu_keep_nan(acc[r][c][4 * g + 1] + bv.y));
-            uint32_t h2 = bf16_bits(relu_keep_nan(acc[r][c][4 * g + 2] + bv.z));
-            uint32_t h3 = bf16_bits(relu_keep_nan(acc[r][c][4 * g + 3] + bv.w));
-            uint2 q;
-            q.x = h0 | h1 << 16; q.y = h2 | h3 << 16;
-            *reinterpret_cast<uint2 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + mbase + 8 * g) = q;
-          }
+              for (int c = 0; c < CT; ++c)
+                acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, a[r]), __builtin_bit_cast(bf16x8, b[c]), acc[r][c], 0, 0, 0);
+            }
         }
       }
-    __syncthreads();
+    }
+    const float *bias = md.aux + md.bias_off[l];
+    if (l < NH - 1) {
+      __syncthreads();  // every wave has read the layer's input: it can be overwritten
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+        if (r < mine) {
+          const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+              uint2 q;
+              q.x = pack_bf16(relu_bits(acc[r][c][4 * g + 0] + bv.x), relu_bits(acc[r][c][4 * g + 1] + bv.y));
+              q.y = pack_bf16(relu_bits(acc[r][c][4 * g + 2] + bv.z), relu_bits(acc[r][c][4 * g + 3] + bv.w));
+              *reinterpret_cast<uint2 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + mbase + 8 * g) = q;
+            }
+          }
+        }
+      __syncthreads();
+    } else {
+      // last hidden layer: round to bf16 and multiply with the output vector at once
+      const float *wl = md.aux + md.wl_off;
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+        if (r < mine) {
+          const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
+            const float4 wv = *reinterpret_cast<const float4 *>(wl + mbase + 8 * g);
+#pragma unroll
+            for (int c = 0; c < CT; ++c) {
+              uint32_t q0 = pack_bf16(relu_bits(acc[r][c][4 * g + 0] + bv.x), relu_bits(acc[r][c][4 * g + 1] + bv.y));
+              uint32_t q1 = pack_bf16(relu_bits(acc[r][c][4 * g + 2] + bv.z), relu_bits(acc[r][c][4 * g + 3] + bv.w));
+              float d = dot[c];
+              d = fmaf(__uint_as_float(q0 << 16), wv.x, d);
+              d = fmaf(__uint_as_float(q0 & 0xffff0000u), wv.y, d);
+              d = fmaf(__uint_as_float(q1 << 16), wv.z, d);
+              d = fmaf(__uint_as_float(q1 & 0xffff0000u), wv.w, d);
+              dot[c] = d;
+            }
+          }
+        }
+    }
   }
 
-  // ---- last layer: v = w_L . h + b_L, from LDS, in a fixed summation order
-  {
-    const int K = md.dims[md.L - 1];
+  // ---- value: sum the partial dots of the two lane halves, then of the waves in order
+  if (NH > 0) {
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+      float v = dot[c] + __shfl_xor(dot[c], 32);
+      if (lane < 32) red[w * NC + c * 32 + lane] = v;
+    }
+  } else {
+    // no hidden layer: v = w_L . x + b_L straight from the input tile
+    const int K = md.dims[0];
     const float *wl = md.aux + md.wl_off;
     const int n = tid % NC, seg = tid / NC;
-    const int klen = K / SEGS;  // K is a multiple of 32, SEGS of 4 or 8
+    const int klen = K / SEGS;  // K is a multiple of 32, SEGS is 4 or 8
     float sum = 0.0f;
     const uint16_t *row = act + (size_t)n * ks + seg * klen;
     for (int k = 0; k < klen; k += 4) {
@@ -275,6 +347,7 @@ __global__ __launch_bounds__(512) void k_mlp_bf16(const int32_t *x, int64_t prob
       sum = fmaf(__uint_as_float(q.y & 0xffff0000u), wv.w, sum);
     }
     red[seg * NC + n] = sum;
+    for (int g = SEGS + seg; g < 8; g += SEGS) red[g * NC + n] = 0.0f;
   }
   __syncthreads();
   {
@@ -283,7 +356,232 @@ __global__ __launch_bounds__(512) void k_mlp_bf16(const int32_t *x, int64_t prob
     if (tid < NC) {
       float s = md.aux[md.bias_off[md.L - 1]];
 #pragma unroll
-      for (int g = 0; g < SEGS; ++g) s += red[g * NC + tid];
+      for (int g = 0; g < 8; ++g) s += red[g * NC + tid];
+      if (scores && (n0 + tid) < M) scores[(size_t)p * ld_scores + n0 + tid] = s;
+      if (okf[tid] != 0 && s < v) { v = s; c = (int32_t)(n0 + tid); }
+      wave_min(v, c);
+    }
+    if (NC > 64) {
+      __shared__ float sv[NC / 64];
+      __shared__ int32_t sc[NC / 64];
+      if (tid < NC && lane == 0) { sv[w] = v; sc[w] = c; }
+      __syncthreads();
+      if (tid == 0) {
+        for (int k = 1; k < NC / 64; ++k) take_min(v, c, sv[k], sc[k]);
+        pval[(size_t)p * nparts + blockIdx.x] = v;
+        pidx[(size_t)p * nparts + blockIdx.x] = c;
+      }
+    } else if (tid == 0) {
+      pval[(size_t)p * nparts + blockIdx.x] = v;
+      pidx[(size_t)p * nparts + blockIdx.x] = c;
+    }
+  }
+}
+
+// ------------------------------------------------- bf16 MLP, uniform hidden width
+
+struct FastDev {
+  int L;
+  int dims[8];
+  const uint4 *w_stream;   // per wave: [layer][k step][row tile r][lane] fragments
+  size_t wave_stride;      // in uint4
+  const float *aux;
+  size_t bias_off[8];
+  size_t wl_off;
+};
+
+// Stream order for k_mlp_fast: wave w's fragments of all hidden layers back to back,
+// out[w][step][r][lane][e] with step running over (layer, k step) and row tile
+// w + 8 r; `pad` zero steps follow so that the prefetch never leaves the buffer.
+__global__ __launch_bounds__(256) void k_pack_stream(const float *blob, FastDev md, int RT, int steps_total,
+                                                     int pad, uint16_t *out) {
+  const size_t per_wave = (size_t)(steps_total + pad) * RT * 512;
+  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= per_wave * 8) return;
+  const int w = (int)(i / per_wave);
+  size_t q = i % per_wave;
+  const int e = (int)(q & 7), lane = (int)((q >> 3) & 63);
+  q >>= 9;
+  const int r = (int)(q % RT);
+  int step = (int)(q / RT);
+  uint16_t v = 0;
+  if (step < steps_total) {
+    size_t off = 0;
+    for (int l = 0; l < md.L - 1; ++l) {
+      const int K = md.dims[l], N = md.dims[l + 1], ksteps = K / 16;
+      if (step < ksteps) {
+        const int row = (w + 8 * r) * 32 + (lane & 31), k = step * 16 + 8 * (lane >> 5) + e;
+        v = (uint16_t)bf16_bits(blob[off + (size_t)row * K + k]);
+        break;
+      }
+      step -= ksteps;
+      off += (size_t)K * N + N;
+    }
+  }
+  out[i] = v;
+}
+
+// Fused MLP for hidden layers of exactly 256*RT units: every wave owns RT row tiles
+// of every layer, so the main loop has no per-wave conditions; the weight stream of a
+// wave is contiguous over all layers and is prefetched PD k-steps ahead without any
+// branch; the activation fragments are read one k-step ahead.
+template <int NC, int RT, int PD>
+__global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
+                                                  int use_valid_row, FastDev md, int ks, float *scores,
+                                                  int64_t ld_scores, float *pval, int32_t *pidx, int nparts) {
+  constexpr int CT = NC / 32;
+  constexpr int SEGS = 512 / NC;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t *act = reinterpret_cast<uint16_t *>(smem);                   // [NC][ks]
+  float *red = reinterpret_cast<float *>(smem + (size_t)NC * ks * 2);   // [8][NC]
+  int32_t *okf = reinterpret_cast<int32_t *>(red + 8 * NC);             // [NC]
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int p = blockIdx.y;
+  const int64_t n0 = (int64_t)blockIdx.x * NC;
+  const int32_t *xp = x + (size_t)p * prob_stride;
+  const int NH = md.L - 1;
+
+  const uint4 *wp = md.w_stream + (size_t)w * md.wave_stride + lane;
+  uint4 ring[PD][RT];
+#pragma unroll
+  for (int j = 0; j < PD; ++j)
+#pragma unroll
+    for (int r = 0; r < RT; ++r) ring[j][r] = wp[(j * RT + r) * 64];
+  wp += PD * RT * 64;
+
+  // ---- load: raw int32 [k][n] -> plog2 -> bf16 -> act[n][k]; all loads of a pass
+  // are issued before the first conversion
+  {
+    const int F = md.dims[0];
+    const int n = tid % NC;
+    const bool inb = (n0 + n) < M;
+    const int32_t *col = xp + n0 + n;
+    constexpr int G = 4;  // groups of 8 features per pass
+    for (int k8 = tid / NC; k8 < F / 8; k8 += SEGS * G) {
+      int32_t raw[G][8];
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int k = (k8 + g * SEGS) * 8 + e;
+          raw[g][e] = (inb && k < F) ? col[(size_t)k * ld] : 0;
+        }
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const int kk = k8 + g * SEGS;
+        if (kk < F / 8) {
+          if (kk == 2) okf[n] = inb && (!use_valid_row || raw[g][0] != 0);
+          uint4 q;
+          q.x = pack_bf16(plog2_dev(raw[g][0]), plog2_dev(raw[g][1]));
+          q.y = pack_bf16(plog2_dev(raw[g][2]), plog2_dev(raw[g][3]));
+          q.z = pack_bf16(plog2_dev(raw[g][4]), plog2_dev(raw[g][5]));
+          q.w = pack_bf16(plog2_dev(raw[g][6]), plog2_dev(raw[g][7]));
+          *reinterpret_cast<uint4 *>(act + (size_t)n * ks + kk * 8) = q;
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  float dot[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
+  const uint16_t *brow = act + (size_t)(lane & 31) * ks + 8 * (lane >> 5);
+  for (int l = 0; l < NH; ++l) {
+    const int ksteps = md.dims[l] / 16;
+    floatx16 acc[RT][CT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+      for (int c = 0; c < CT; ++c)
+#pragma unroll
+        for (int j = 0; j < 16; ++j) acc[r][c][j] = 0.0f;
+    uint4 bcur[CT];
+#pragma unroll
+    for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ks);
+    for (int s0 = 0; s0 < ksteps; s0 += PD) {
+#pragma unroll
+      for (int j = 0; j < PD; ++j) {
+        uint4 a[RT], bnext[CT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+          a[r] = ring[j][r];
+          ring[j][r] = wp[r * 64];
+        }
+        wp += RT * 64;
+        // fragments of the next k-step (one step past the end stays inside the tile's LDS)
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+          bnext[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ks + (s0 + j + 1) * 16);
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+#pragma unroll
+          for (int c = 0; c < CT; ++c)
+            acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, a[r]), __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
+#pragma unroll
+        for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
+      }
+    }
+    const float *bias = md.aux + md.bias_off[l];
+    if (l < NH - 1) {
+      __syncthreads();  // every wave has read the layer's input: it can be overwritten
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+        const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
+#pragma unroll
+          for (int c = 0; c < CT; ++c) {
+            uint2 q;
+            q.x = pack_bf16(relu_bits(acc[r][c][4 * g + 0] + bv.x), relu_bits(acc[r][c][4 * g + 1] + bv.y));
+            q.y = pack_bf16(relu_bits(acc[r][c][4 * g + 2] + bv.z), relu_bits(acc[r][c][4 * g + 3] + bv.w));
+            *reinterpret_cast<uint2 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + mbase + 8 * g) = q;
+          }
+        }
+      }
+      __syncthreads();
+    } else {
+      const float *wl = md.aux + md.wl_off;
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+        const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
+          const float4 wv = *reinterpret_cast<const float4 *>(wl + mbase + 8 * g);
+#pragma unroll
+          for (int c = 0; c < CT; ++c) {
+            uint32_t q0 = pack_bf16(relu_bits(acc[r][c][4 * g + 0] + bv.x), relu_bits(acc[r][c][4 * g + 1] + bv.y));
+            uint32_t q1 = pack_bf16(relu_bits(acc[r][c][4 * g + 2] + bv.z), relu_bits(acc[r][c][4 * g + 3] + bv.w));
+            float d = dot[c];
+            d = fmaf(__uint_as_float(q0 << 16), wv.x, d);
+            d = fmaf(__uint_as_float(q0 & 0xffff0000u), wv.y, d);
+            d = fmaf(__uint_as_float(q1 << 16), wv.z, d);
+            d = fmaf(__uint_as_float(q1 & 0xffff0000u), wv.w, d);
+            dot[c] = d;
+          }
+        }
+      }
+    }
+  }
+
+#pragma unroll
+  for (int c = 0; c < CT; ++c) {
+    float v = dot[c] + __shfl_xor(dot[c], 32);
+    if (lane < 32) red[w * NC + c * 32 + lane] = v;
+  }
+  __syncthreads();
+  {
+    float v = __builtin_inff();
+    int32_t c = -1;
+    if (tid < NC) {
+      float s = md.aux[md.bias_off[md.L - 1]];
+#pragma unroll
+      for (int g = 0; g < 8; ++g) s += red[g * NC + tid];
       if (scores && (n0 + tid) < M) scores[(size_t)p * ld_scores + n0 + tid] = s;
       if (okf[tid] != 0 && s < v) { v = s; c = (int32_t)(n0 + tid); }
       wave_min(v, c);
@@ -523,6 +821,7 @@ int vfk_ensure_parts(vf_ctx *c, size_t n) {
 void vfk_free_model(vf_ctx *c) {
   if (c->pm.w_f32) (void)hipFree(c->pm.w_f32);
   if (c->pm.w_pack) (void)hipFree(c->pm.w_pack);
+  if (c->pm.w_stream) (void)hipFree(c->pm.w_stream);
   if (c->pm.aux) (void)hipFree(c->pm.aux);
   c->pm = vf_packed_model();
 }
@@ -567,6 +866,29 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
       hipLaunchKernelGGL(k_copy_f32, blocks((size_t)N), dim3(256), 0, st, b, pm.aux + pm.aux_off[l], (size_t)N, 0);
       VF_HIP(c, hipGetLastError());
       off += (size_t)K * N + N;
+    }
+    // uniform hidden width 512 or 1024 with k-step counts that are multiples of 8:
+    // pack the per-wave fragment stream for k_mlp_fast as well
+    int rt = 0;
+    if (L >= 2) {
+      rt = m.dims[1] / 256;
+      if (rt != 2 && rt != 4) rt = 0;
+      for (int l = 1; l < L; ++l) if (m.dims[l] != 256 * rt) rt = 0;
+      for (int l = 0; l < L - 1; ++l) if ((m.dims[l] / 16) % 8 != 0) rt = 0;
+    }
+    if (rt) {
+      int steps = 0;
+      for (int l = 0; l < L - 1; ++l) steps += m.dims[l] / 16;
+      const int pad = 8;
+      const size_t per_wave = (size_t)(steps + pad) * rt * 512;
+      VF_HIP(c, hipMalloc((void **)&pm.w_stream, per_wave * 8 * sizeof(uint16_t)));
+      FastDev fd;
+      fd.L = L;
+      for (int l = 0; l < 8; ++l) fd.dims[l] = m.dims[l];
+      hipLaunchKernelGGL(k_pack_stream, blocks(per_wave * 8), dim3(256), 0, st, wdev, fd, rt, steps, pad, pm.w_stream);
+      VF_HIP(c, hipGetLastError());
+      pm.wave_stride = per_wave / 8;
+      pm.fast_rt = rt;
     }
     return VF_OK;
   }
@@ -650,19 +972,31 @@ int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, i
   const int nparts = (int)((M + NC - 1) / NC);
   int rc = vfk_ensure_parts(c, (size_t)(nparts > 0 ? nparts : 1) * nprob);
   if (rc != VF_OK) return rc;
-  const size_t smem = (size_t)NC * ks * 2 + (size_t)(512 / NC) * NC * 4 + (size_t)NC * 4;
-  if (nparts > 0) {
+  const size_t smem = (size_t)NC * ks * 2 + (size_t)8 * NC * 4 + (size_t)NC * 4;
+  if (nparts > 0 && c->pm.fast_rt) {
+    vf_prof_scope prof(c, VF_PROF_SCORE);
+    FastDev fd;
+    fd.L = L;
+    for (int l = 0; l < 8; ++l) { fd.dims[l] = m.dims[l]; fd.bias_off[l] = c->pm.aux_off[l]; }
+    fd.w_stream = reinterpret_cast<const uint4 *>(c->pm.w_stream);
+    fd.wave_stride = c->pm.wave_stride; fd.aux = c->pm.aux; fd.wl_off = c->pm.aux_off[7];
+    dim3 grid((unsigned)nparts, (unsigned)nprob);
+    void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, FastDev, int, float *, int64_t, float *, int32_t *, int);
+    if (wide) kern = k_mlp_fast<64, 4, 2>;
+    else kern = getenv("VF_PD8") ? k_mlp_fast<128, 2, 8> : k_mlp_fast<128, 2, 4>;
+    VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, x, prob_stride, M, ld, use_valid_row, fd, ks, scores,
+                       ld_scores, c->d_pval, c->d_pidx, nparts);
+    VF_HIP(c, hipGetLastError());
+  } else if (nparts > 0) {
     vf_prof_scope prof(c, VF_PROF_SCORE);
     dim3 grid((unsigned)nparts, (unsigned)nprob);
-    if (wide) {
-      VF_HIP(c, hipFuncSetAttribute((const void *)k_mlp_bf16<64, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-      hipLaunchKernelGGL((k_mlp_bf16<64, 4>), grid, dim3(512), smem, st, x, prob_stride, M, ld, use_valid_row, md, ks,
-                         scores, ld_scores, c->d_pval, c->d_pidx, nparts);
-    } else {
-      VF_HIP(c, hipFuncSetAttribute((const void *)k_mlp_bf16<128, 2>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-      hipLaunchKernelGGL((k_mlp_bf16<128, 2>), grid, dim3(512), smem, st, x, prob_stride, M, ld, use_valid_row, md, ks,
-                         scores, ld_scores, c->d_pval, c->d_pidx, nparts);
-    }
+    void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, MlpDev, int, float *, int64_t, float *, int32_t *, int);
+    if (wide) kern = k_mlp_bf16<64, 4, 2>;
+    else kern = k_mlp_bf16<128, 2, 2>;
+    VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, x, prob_stride, M, ld, use_valid_row, md, ks, scores,
+                       ld_scores, c->d_pval, c->d_pidx, nparts);
     VF_HIP(c, hipGetLastError());
   }
   *nparts_out = nparts;
