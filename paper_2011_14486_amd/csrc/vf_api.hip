@@ -118,6 +118,13 @@ int ensure_feat(vf_ctx *c) {
 
 // enumerate + featurize + score + argmin (+ commit) for one stage, all problems
 int step(vf_ctx *c, int stage, int commit, int32_t *best_cid, float *best_val) {
+  if (vfk_can_fuse_step(c)) {
+    // features are produced and consumed inside one kernel and never reach HBM
+    int nparts = 0;
+    int rc = vfk_step_fused(c, stage, &nparts);
+    if (rc != VF_OK) return rc;
+    return vfk_commit_from_partials(c, stage, nparts, commit, best_cid, best_val);
+  }
   int rc = ensure_feat(c);
   if (rc != VF_OK) return rc;
   rc = vfk_featurize(c, stage, c->d_feat);

@@ -128,6 +128,10 @@ void vfk_free_model(vf_ctx *c);
 // (ctx->d_pval / d_pidx, [nprob][nparts], ids local to the problem).
 int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
                   int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out);
+// Enumerate + featurize + score + partial argmin of one stage in a single kernel (bf16
+// MLPs of uniform hidden width whose input width is the space's F).
+bool vfk_can_fuse_step(const vf_ctx *c);
+int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out);
 int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores, int *nparts_out);
 int vfk_argmin_groups(vf_ctx *c, int64_t M, int nparts, int parts_per_group, int ngroups,
                       int32_t *best_idx, float *best_val);

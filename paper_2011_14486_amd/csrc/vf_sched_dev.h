@@ -1,0 +1,261 @@
+// Device-side candidate model shared by the featurize kernels and the fused scorer:
+// saturating integer helpers, the per-decision context (what all candidates of one
+// decision have in common) and the evaluation of one candidate state (Table 1 digits,
+// validity under the committed loop structure of Sec. 2, the 64 core features of
+// Sec. 3.2).  Include inside an anonymous namespace of a HIP translation unit.
+#pragma once
+
+constexpr uint32_t SATMAX = 2147483647u;
+
+__device__ __forceinline__ uint32_t smul(uint32_t a, uint32_t b) {
+  uint64_t p = (uint64_t)a * (uint64_t)b;
+  return p > (uint64_t)SATMAX ? SATMAX : (uint32_t)p;
+}
+__device__ __forceinline__ uint32_t sadd(uint32_t a, uint32_t b) {
+  uint32_t s = a + b;  // both <= 2^31-1: no wrap
+  return s > SATMAX ? SATMAX : s;
+}
+__device__ __forceinline__ uint32_t cdiv(uint32_t a, uint32_t b) { return (a + b - 1u) / b; }
+// 16 * num / den in fixed point; the numerator saturates before the division
+__device__ __forceinline__ uint32_t ratio16(uint32_t num, uint32_t den) {
+  uint32_t n16 = num > (SATMAX >> 4) ? SATMAX : (num << 4);
+  return n16 / (den ? den : 1u);
+}
+__device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
+
+struct Tables {
+  const int32_t *space, *stages, *intr, *suffix;
+  int32_t *states, *cf, *prefix, *cids, *alive, *err;
+  float *vals;
+  int S;
+};
+
+// What is common to every candidate of one decision (one problem, one stage).
+struct Dec {
+  int32_t srec[16];
+  int32_t intr[16];
+  uint32_t E[3][3];   // region per instance when computed at ROOT, L1, L2
+  uint32_t inst[3];   // number of instances at ROOT, L1, L2
+  uint32_t inl_inst;  // number of evaluations when inlined into the anchor
+  int32_t lvl_ok[4];  // compute_at level offered by the committed loop structure
+  int32_t a_tp, a_nt, a_cat, a_perm, anchored;
+  int32_t pm, pb, sm, spt;
+  int32_t nb[192];    // rows 64..255 of the 256-feature layout
+};
+
+// Intrinsic block of one stage record (schedule-invariant, Sec. 3.2).
+__device__ void intrinsic_of(const int32_t *w, int j, int S, int32_t *a) {
+  uint32_t kind = w[0], W = w[1], H = w[2], C = w[3], RC = w[4], KH = w[5], KW = w[6];
+  uint32_t stride = w[7], eb = w[12];
+  uint32_t R = smul(smul(RC, KH), KW);
+  uint32_t points = smul(smul(W, H), C);
+  bool conv_like = (kind == VF_CONV || kind == VF_DWCONV);
+  uint32_t macs = conv_like ? smul(points, R) : points;
+  uint32_t cin = (kind == VF_CONV) ? RC : C;
+  uint32_t in_elems = smul(smul(smul(W, stride), smul(H, stride)), cin);
+  if (kind == VF_ADD) in_elems = smul(in_elems, 2u);
+  uint32_t w_elems = 0;
+  if (kind == VF_CONV) w_elems = smul(smul(smul(C, RC), KH), KW);
+  else if (kind == VF_DWCONV) w_elems = smul(smul(C, KH), KW);
+  a[0] = kind; a[1] = W; a[2] = H; a[3] = C;
+  a[4] = R; a[5] = smul(KH, KW); a[6] = stride;
+  a[7] = points; a[8] = macs; a[9] = in_elems; a[10] = w_elems;
+  a[11] = smul(points, eb);
+  a[12] = ratio16(macs, sadd(sadd(in_elems, w_elems), points));
+  a[13] = w[9]; a[14] = j; a[15] = S - 1 - j;
+}
+
+// Region of the producer needed by a consumer box, clipped to the producer's extents.
+__device__ void needed(const int32_t *srec, const int32_t *arec, const uint32_t box[3], uint32_t E[3]) {
+  uint32_t sa = arec[7], kh = arec[5], kw = arec[6];
+  E[0] = umin((uint32_t)srec[1], sadd(smul(box[0] - 1u, sa), kw));
+  E[1] = umin((uint32_t)srec[2], sadd(smul(box[1] - 1u, sa), kh));
+  E[2] = (arec[0] == VF_CONV) ? (uint32_t)srec[3] : umin((uint32_t)srec[3], box[2]);
+}
+
+// Cooperative set-up of the decision context for problem b, stage `stage`.
+__device__ void build_dec(Dec &d, vf_space &sp, const Tables &t, int b, int stage) {
+  const int tid = threadIdx.x, nt = blockDim.x, S = t.S;
+  const size_t row = (size_t)b * S;
+  for (int i = tid; i < (int)(sizeof(vf_space) / 4); i += nt) ((int32_t *)&sp)[i] = t.space[i];
+  if (tid < 16) {
+    d.srec[tid] = t.stages[(row + stage) * 16 + tid];
+    d.intr[tid] = t.intr[(row + stage) * 16 + tid];
+  }
+  for (int i = tid; i < 192; i += nt) {
+    int32_t v = 0;
+    if (i < 144) {
+      int k = i / 48 + 1, f = i % 48;
+      if (stage - k >= 0) v = t.cf[(row + stage - k) * 64 + f];
+    } else {
+      int k = (i - 144) / 16 + 1, f = (i - 144) % 16;
+      if (stage + k < S) v = t.intr[(row + stage + k) * 16 + f];
+    }
+    d.nb[i] = v;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    const int alive = t.alive[b];
+    const int a = d.srec[8], kind = d.srec[0];
+    d.E[0][0] = d.srec[1]; d.E[0][1] = d.srec[2]; d.E[0][2] = d.srec[3];
+    d.inst[0] = 1;
+    for (int l = 1; l < 3; ++l) {
+      d.E[l][0] = d.E[0][0]; d.E[l][1] = d.E[0][1]; d.E[l][2] = d.E[0][2];
+      d.inst[l] = 1;
+    }
+    d.inl_inst = 1;
+    d.lvl_ok[0] = alive; d.lvl_ok[1] = 0; d.lvl_ok[2] = 0; d.lvl_ok[3] = 0;
+    d.a_tp = d.a_nt = d.a_cat = d.a_perm = 0;
+    bool anchored = (a >= 0 && a < stage && t.states[(row + a) * 16 + 15] == 1);
+    d.anchored = anchored;
+    if (anchored) {
+      const int32_t *ast = t.states + (row + a) * 16;
+      const int32_t *arec = t.stages + (row + a) * 16;
+      const int32_t *acf = t.cf + (row + a) * 64;
+      uint32_t fa[3] = {(uint32_t)ast[0], (uint32_t)ast[1], (uint32_t)ast[2]};
+      uint32_t Ea[3] = {(uint32_t)ast[8], (uint32_t)ast[9], (uint32_t)ast[10]};
+      uint32_t Oa[3] = {(uint32_t)ast[12], (uint32_t)ast[13], (uint32_t)ast[14]};
+      uint32_t inst_a = ast[11];
+      int d0 = sp.perm[ast[3]][0];
+      uint32_t box[3] = {Ea[0], Ea[1], Ea[2]};
+      box[d0] = fa[d0];
+      needed(d.srec, arec, box, d.E[1]);
+      d.inst[1] = smul(inst_a, Oa[d0]);
+      needed(d.srec, arec, fa, d.E[2]);
+      uint32_t tiles_a = smul(smul(Oa[0], Oa[1]), Oa[2]);
+      d.inst[2] = smul(inst_a, tiles_a);
+      uint32_t pp = 1;
+      for (int k = 0; k < 3; ++k) pp = smul(smul(pp, Oa[k]), fa[k]);
+      uint32_t Ra = smul(smul((uint32_t)arec[4], (uint32_t)arec[5]), (uint32_t)arec[6]);
+      d.inl_inst = smul(smul(inst_a, pp), Ra);
+      bool single = (d.srec[9] == 1) && alive;
+      bool loops = (ast[6] != VF_INLINE);
+      d.lvl_ok[1] = single && loops && Oa[d0] > 1u;
+      d.lvl_ok[2] = single && loops && tiles_a > 1u;
+      d.lvl_ok[3] = single && (kind == VF_POINTWISE || kind == VF_ADD);
+      d.a_tp = acf[42]; d.a_nt = acf[54]; d.a_cat = acf[32]; d.a_perm = acf[23];
+    }
+    d.pm = t.prefix[((size_t)b * (S + 1) + stage) * 2 + 0];
+    d.pb = t.prefix[((size_t)b * (S + 1) + stage) * 2 + 1];
+    d.sm = t.suffix[(row + stage) * 2 + 0];
+    d.spt = t.suffix[(row + stage) * 2 + 1];
+  }
+  __syncthreads();
+}
+
+// One candidate state: digits, validity and (FEATS) the 64 core features.
+// Rows 0..15 are always the stage's intrinsic block; rows 16..63 are zero when the
+// candidate is not valid.
+template <bool FEATS>
+__device__ __forceinline__ bool eval_candidate(const Dec &d, const vf_space &sp, uint32_t cid,
+                                               uint32_t &dec, int32_t *core) {
+  // Table 1 digits, least significant first
+  uint32_t r = cid;
+  uint32_t ix = r % (uint32_t)sp.nf[0]; r /= (uint32_t)sp.nf[0];
+  uint32_t iy = r % (uint32_t)sp.nf[1]; r /= (uint32_t)sp.nf[1];
+  uint32_t ic = r % (uint32_t)sp.nf[2]; r /= (uint32_t)sp.nf[2];
+  uint32_t ip = r % (uint32_t)sp.nperm; r /= (uint32_t)sp.nperm;
+  uint32_t vec = r % (uint32_t)sp.nvec; r /= (uint32_t)sp.nvec;
+  uint32_t par = r % (uint32_t)sp.npar; r /= (uint32_t)sp.npar;
+  uint32_t icat = r % (uint32_t)sp.ncat; r /= (uint32_t)sp.ncat;
+  uint32_t isat = r;
+  dec = ix | iy << 4 | ic << 8 | ip << 12 | vec << 16 | par << 20 | icat << 24 | isat << 28;
+
+  const int cat = sp.cat[icat];
+  const uint32_t hoist = isat;
+  uint32_t f[3] = {(uint32_t)sp.fac[0][ix], (uint32_t)sp.fac[1][iy], (uint32_t)sp.fac[2][ic]};
+  uint32_t E[3] = {1u, 1u, 1u};
+  uint32_t inst;
+
+  bool valid = d.lvl_ok[cat] != 0;
+  if (cat == VF_INLINE) {
+    valid = valid && ((ix | iy | ic | ip | vec | par | isat) == 0u);
+    f[0] = f[1] = f[2] = 1u;
+    inst = d.inl_inst;
+  } else {
+    E[0] = d.E[cat][0]; E[1] = d.E[cat][1]; E[2] = d.E[cat][2];
+    inst = d.inst[cat];
+    valid = valid && hoist <= (uint32_t)cat && f[0] <= E[0] && f[1] <= E[1] && f[2] <= E[2];
+  }
+  if (!FEATS) return valid;
+
+#pragma unroll
+  for (int k = 0; k < 16; ++k) core[k] = d.intr[k];
+  if (!valid) {
+#pragma unroll
+    for (int k = 16; k < 64; ++k) core[k] = 0;
+    return false;
+  }
+
+  const int p0 = sp.perm[ip][0], p2 = sp.perm[ip][2];
+  const uint32_t kind = d.srec[0], RC = d.srec[4], KH = d.srec[5], KW = d.srec[6];
+  const uint32_t stride = d.srec[7], eb = d.srec[12];
+  const uint32_t R = d.intr[4], points = d.intr[7];
+  uint32_t O[3] = {cdiv(E[0], f[0]), cdiv(E[1], f[1]), cdiv(E[2], f[2])};
+
+  core[16] = 1;
+  core[17] = f[0]; core[18] = f[1]; core[19] = f[2];
+  core[20] = O[0]; core[21] = O[1]; core[22] = O[2];
+  core[23] = ip; core[24] = p2; core[25] = p0;
+  core[26] = vec;
+  const uint32_t fin = p2 == 0 ? f[0] : (p2 == 1 ? f[1] : f[2]);
+  core[27] = vec ? umin(fin, (uint32_t)sp.vlen) : 1u;
+  core[28] = vec ? ratio16(fin, smul(cdiv(fin, (uint32_t)sp.vlen), (uint32_t)sp.vlen)) : 16u;
+  core[29] = par;
+  const uint32_t Oout = p0 == 0 ? O[0] : (p0 == 1 ? O[1] : O[2]);
+  const uint32_t tasks = par ? Oout : 1u;
+  core[30] = tasks;
+  core[31] = ratio16(tasks, smul(cdiv(tasks, (uint32_t)sp.ncores), (uint32_t)sp.ncores));
+  core[32] = cat; core[33] = hoist;
+  core[34] = E[0]; core[35] = E[1]; core[36] = E[2];
+  core[37] = inst;
+  uint32_t padded = smul(smul(smul(smul(smul(O[0], f[0]), O[1]), f[1]), O[2]), f[2]);
+  core[38] = padded;
+  uint32_t total_points = smul(inst, padded);
+  core[39] = total_points;
+  core[40] = smul(total_points, R);
+  core[41] = ratio16(total_points, points);
+  uint32_t tile_points = smul(smul(f[0], f[1]), f[2]);
+  core[42] = tile_points;
+  uint32_t tin = smul(sadd(smul(f[0] - 1u, stride), KW), sadd(smul(f[1] - 1u, stride), KH));
+  tin = smul(tin, kind == VF_CONV ? RC : f[2]);
+  if (kind == VF_ADD) tin = smul(tin, 2u);
+  core[43] = tin;
+  uint32_t tw = 0;
+  if (kind == VF_CONV) tw = smul(smul(smul(f[2], RC), KH), KW);
+  else if (kind == VF_DWCONV) tw = smul(smul(f[2], KH), KW);
+  core[44] = tw;
+  uint32_t ws = sadd(sadd(tile_points, tin), tw);
+  core[45] = ws;
+  uint32_t ws_bytes = smul(ws, eb);
+  core[46] = ws_bytes <= (uint32_t)sp.l1_bytes;
+  core[47] = ws_bytes <= (uint32_t)sp.l2_bytes;
+  if (cat == VF_INLINE) {
+    core[48] = 0; core[49] = 0; core[50] = 0;
+  } else {
+    const int lvl = cat - (int)hoist;  // where the buffer lives
+    core[48] = smul(smul(d.E[lvl][0], d.E[lvl][1]), d.E[lvl][2]);
+    core[49] = d.inst[lvl];
+    core[50] = smul(total_points, eb);
+  }
+  uint32_t ntiles = smul(smul(O[0], O[1]), O[2]);
+  core[51] = smul(smul(inst, ntiles), smul(sadd(tin, tw), eb));
+  core[52] = p2 == 0 ? f[0] : 1u;
+  core[53] = ratio16(smul(tile_points, R), sadd(tin, tw));
+  core[54] = ntiles;
+  core[55] = (O[0] * f[0] == E[0]) && (O[1] * f[1] == E[1]) && (O[2] * f[2] == E[2]);
+  core[56] = d.a_tp; core[57] = d.a_nt; core[58] = d.a_cat;
+  core[59] = d.anchored ? (int32_t)((int32_t)ip == d.a_perm) : 0;
+  core[60] = d.pm; core[61] = d.pb; core[62] = d.sm; core[63] = d.spt;
+  return true;
+}
+
+
+// Table pointers of a context.
+inline Tables tables_of(const vf_ctx *c) {
+  Tables t;
+  t.space = c->d_space; t.stages = c->d_stages; t.intr = c->d_intr; t.suffix = c->d_suffix;
+  t.states = c->d_states; t.cf = c->d_cf; t.prefix = c->d_prefix; t.cids = c->d_cids;
+  t.alive = c->d_alive; t.err = c->d_err; t.vals = c->d_vals; t.S = c->S;
+  return t;
+}

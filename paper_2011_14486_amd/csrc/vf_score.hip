@@ -22,6 +22,8 @@
 
 namespace {
 
+#include "vf_sched_dev.h"
+
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
@@ -425,10 +427,21 @@ __global__ __launch_bounds__(256) void k_pack_stream(const float *blob, FastDev 
 // of every layer, so the main loop has no per-wave conditions; the weight stream of a
 // wave is contiguous over all layers and is prefetched PD k-steps ahead without any
 // branch; the activation fragments are read one k-step ahead.
-template <int NC, int RT, int PD>
+//
+// GEN = false: the tile's features are read from x (raw int32, feature-major).
+// GEN = true: the tile's candidates are enumerated and featurized right here from
+// the scheduling tables of problem blockIdx.y (x is not used): the features go
+// straight into LDS as normalised bf16 and never touch HBM.
+struct GenArgs {
+  Tables t;
+  int stage;
+};
+
+template <int NC, int RT, int PD, bool GEN>
 __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
                                                   int use_valid_row, FastDev md, int ks, float *scores,
-                                                  int64_t ld_scores, float *pval, int32_t *pidx, int nparts) {
+                                                  int64_t ld_scores, float *pval, int32_t *pidx, int nparts,
+                                                  GenArgs ga) {
   constexpr int CT = NC / 32;
   constexpr int SEGS = 512 / NC;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -451,9 +464,55 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     for (int r = 0; r < RT; ++r) ring[j][r] = wp[(j * RT + r) * 64];
   wp += PD * RT * 64;
 
-  // ---- load: raw int32 [k][n] -> plog2 -> bf16 -> act[n][k]; all loads of a pass
-  // are issued before the first conversion
-  {
+  if (GEN) {
+    // ---- enumerate + featurize the tile: thread n < NC owns candidate n0 + n
+    __shared__ Dec dctx;
+    __shared__ vf_space sp;
+    __shared__ uint32_t nbh[96];  // rows 64..255, normalised, as bf16 pairs
+    const int F = md.dims[0];
+    build_dec(dctx, sp, ga.t, p, ga.stage);
+    if (F == 256 && tid >= 256 && tid < 352) {
+      const int q = tid - 256;
+      nbh[q] = pack_bf16(plog2_dev(dctx.nb[2 * q]), plog2_dev(dctx.nb[2 * q + 1]));
+    }
+    if (tid < NC) {
+      int32_t core[64];
+      bool valid = false;
+      const uint32_t cid = (uint32_t)(n0 + tid);
+      if ((int64_t)cid < M) {
+        uint32_t dec;
+        valid = eval_candidate<true>(dctx, sp, cid, dec, core);
+      } else {
+#pragma unroll
+        for (int k = 0; k < 64; ++k) core[k] = 0;
+      }
+      okf[tid] = valid;
+#pragma unroll
+      for (int k8 = 0; k8 < 8; ++k8) {
+        uint4 q;
+        q.x = pack_bf16(plog2_dev(core[k8 * 8 + 0]), plog2_dev(core[k8 * 8 + 1]));
+        q.y = pack_bf16(plog2_dev(core[k8 * 8 + 2]), plog2_dev(core[k8 * 8 + 3]));
+        q.z = pack_bf16(plog2_dev(core[k8 * 8 + 4]), plog2_dev(core[k8 * 8 + 5]));
+        q.w = pack_bf16(plog2_dev(core[k8 * 8 + 6]), plog2_dev(core[k8 * 8 + 7]));
+        *reinterpret_cast<uint4 *>(act + (size_t)tid * ks + k8 * 8) = q;
+      }
+    }
+    __syncthreads();
+    if (F == 256) {
+      // the 192 neighbour rows are the same for every candidate id below M
+      const int n = tid % NC, part = tid / NC;
+      const bool inb = (n0 + n) < M;
+      constexpr int PER = 24 / SEGS;
+      const uint4 *src = reinterpret_cast<const uint4 *>(nbh);
+#pragma unroll
+      for (int q = 0; q < PER; ++q) {
+        const uint4 v = inb ? src[part * PER + q] : make_uint4(0u, 0u, 0u, 0u);
+        *reinterpret_cast<uint4 *>(act + (size_t)n * ks + 64 + (part * PER + q) * 8) = v;
+      }
+    }
+  } else {
+    // ---- load: raw int32 [k][n] -> plog2 -> bf16 -> act[n][k]; all loads of a pass
+    // are issued before the first conversion
     const int F = md.dims[0];
     const int n = tid % NC;
     const bool inb = (n0 + n) < M;
@@ -906,8 +965,25 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
   return VF_OK;
 }
 
+static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
+                     int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage);
+
 int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
                   int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out) {
+  return score_mlp(c, x, prob_stride, nprob, M, ld, use_valid_row, scores, ld_scores, nparts_out, -1);
+}
+
+bool vfk_can_fuse_step(const vf_ctx *c) {
+  return c->has_model && c->model.kind == VF_MLP && c->model.dtype == VF_BF16 && c->pm.fast_rt != 0 &&
+         c->model.dims[0] == c->space.F;
+}
+
+int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out) {
+  return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, nparts_out, stage);
+}
+
+static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
+                     int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage) {
   const vf_model &m = c->model;
   const int L = m.n_layers;
   hipStream_t st = c->stream;
@@ -981,12 +1057,16 @@ int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, i
     fd.w_stream = reinterpret_cast<const uint4 *>(c->pm.w_stream);
     fd.wave_stride = c->pm.wave_stride; fd.aux = c->pm.aux; fd.wl_off = c->pm.aux_off[7];
     dim3 grid((unsigned)nparts, (unsigned)nprob);
-    void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, FastDev, int, float *, int64_t, float *, int32_t *, int);
-    if (wide) kern = k_mlp_fast<64, 4, 2>;
-    else kern = getenv("VF_PD8") ? k_mlp_fast<128, 2, 8> : k_mlp_fast<128, 2, 4>;
+    void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, FastDev, int, float *, int64_t, float *, int32_t *, int,
+                 GenArgs);
+    GenArgs ga;
+    ga.t = tables_of(c);
+    ga.stage = gen_stage;
+    if (gen_stage >= 0) kern = wide ? k_mlp_fast<64, 4, 2, true> : k_mlp_fast<128, 2, 4, true>;
+    else kern = wide ? k_mlp_fast<64, 4, 2, false> : k_mlp_fast<128, 2, 4, false>;
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, x, prob_stride, M, ld, use_valid_row, fd, ks, scores,
-                       ld_scores, c->d_pval, c->d_pidx, nparts);
+                       ld_scores, c->d_pval, c->d_pidx, nparts, ga);
     VF_HIP(c, hipGetLastError());
   } else if (nparts > 0) {
     vf_prof_scope prof(c, VF_PROF_SCORE);
