@@ -79,12 +79,14 @@ bool model_ok(const vf_model *m, size_t n_floats) {
 
 void free_pipeline(vf_ctx *c) {
   void *ps[] = {c->d_stages, c->d_intr, c->d_suffix, c->d_states, c->d_cf, c->d_prefix,
-                c->d_cids,   c->d_vals, c->d_alive,  c->d_forced};
+                c->d_cids,   c->d_vals, c->d_alive,  c->d_forced, c->d_decpack};
   for (void *p : ps)
     if (p) (void)hipFree(p);
   c->d_stages = c->d_intr = c->d_suffix = c->d_states = c->d_cf = c->d_prefix = c->d_cids = nullptr;
   c->d_alive = c->d_forced = nullptr;
   c->d_vals = nullptr;
+  c->d_decpack = nullptr;
+  c->dec_stage = -1;
   c->has_pipeline = false;
   c->S = c->B = c->n_sched = 0;
 }
@@ -227,6 +229,7 @@ int vf_set_pipeline(vf_ctx *c, const vf_stage *st, int S, int B) {
   if (rc == VF_OK) rc = dev_alloc(c, c->d_vals, n);
   if (rc == VF_OK) rc = dev_alloc(c, c->d_alive, (size_t)B);
   if (rc == VF_OK) rc = dev_alloc(c, c->d_forced, n);
+  if (rc == VF_OK) rc = dev_alloc(c, c->d_decpack, (size_t)B * VF_DECPACK_DWORDS);
   if (rc != VF_OK) {
     free_pipeline(c);
     return rc;

@@ -11,6 +11,8 @@
 
 // candidates per partial-argmin slot (one slot per scoring workgroup)
 #define VF_PART 128
+// size of one packed decision context (see vf_sched_dev.h)
+#define VF_DECPACK_DWORDS 412
 
 struct vf_packed_model {
   // fp32 path: the caller's blob copied as is
@@ -54,6 +56,8 @@ struct vf_ctx {
   int32_t *d_alive = nullptr;   // [B] 0 once a stage of the problem found no winner
   int32_t *d_err = nullptr;     // [1] set by a forced commit of an invalid candidate
   int32_t *d_forced = nullptr;  // [B][S] staging for vf_set_state
+  uint32_t *d_decpack = nullptr; // [B][VF_DECPACK_DWORDS] decision context of stage dec_stage
+  int dec_stage = -1;            // stage d_decpack was built for, -1: none
 
   vf_model model;
   vf_packed_model pm;
@@ -118,6 +122,8 @@ int vfk_featurize(vf_ctx *c, int stage, int32_t *feat);
 int vfk_commit_from_partials(vf_ctx *c, int stage, int nparts, int commit, int32_t *best_cid,
                              float *best_val);
 int vfk_commit_forced(vf_ctx *c, int stage);
+// builds d_decpack for `stage` unless it is already there
+int vfk_prepare(vf_ctx *c, int stage);
 
 // ---- vf_score.hip: value networks and argmin ----
 int vfk_pack_model(vf_ctx *c, const float *weights_dev);

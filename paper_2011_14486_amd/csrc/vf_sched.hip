@@ -118,11 +118,18 @@ __global__ __launch_bounds__(256) void k_featurize(Tables t, int stage, uint32_t
 // One workgroup (one wave) per problem: pick the winner of the decision (first
 // minimum over the partial minima, or a forced id), report it and, if asked, make
 // it s_i: state record, committed feature vector, running sums.
+__global__ __launch_bounds__(64) void k_prepare(Tables t, int stage, uint32_t *decpack) {
+  __shared__ DecPack pk;
+  write_decpack(pk, t, blockIdx.x, stage, decpack);
+}
+
 __global__ __launch_bounds__(64) void k_commit(Tables t, int stage, int nparts, const float *pval,
                                                const int32_t *pidx, const int32_t *forced, int commit,
-                                               uint32_t M, int32_t *best_cid, float *best_val) {
-  __shared__ Dec d;
-  __shared__ vf_space sp;
+                                               uint32_t M, int32_t *best_cid, float *best_val,
+                                               uint32_t *decpack_next) {
+  __shared__ DecPack pk;
+  Dec &d = pk.d;
+  vf_space &sp = pk.sp;
   const int b = blockIdx.x, S = t.S, lane = threadIdx.x;
   build_dec(d, sp, t, b, stage);
   float v = __builtin_inff();
@@ -142,39 +149,47 @@ __global__ __launch_bounds__(64) void k_commit(Tables t, int stage, int nparts, 
       if (oc >= 0 && (ov < v || (ov == v && (c < 0 || oc < c)))) { v = ov; c = oc; }
     }
   }
-  if (lane != 0) return;
-  if (best_cid) best_cid[b] = c;
-  if (best_val) best_val[b] = v;
-  if (!commit) return;
-  const size_t row = (size_t)b * S + stage;
-  int32_t *pre = t.prefix + ((size_t)b * (S + 1) + stage) * 2;
-  int32_t core[64];
-  bool ok = false;
-  if (c >= 0 && (uint32_t)c < M) {
-    uint32_t dec;
-    ok = eval_candidate<true>(d, sp, (uint32_t)c, dec, core);
-  }
-  if (!ok) {
-    if (forced) t.err[0] = 1;
-    t.alive[b] = 0;
-    t.cids[row] = -1;
-    t.vals[row] = __builtin_inff();
-    pre[2] = pre[0]; pre[3] = pre[1];
-    return;
-  }
+  if (lane == 0) {
+    if (best_cid) best_cid[b] = c;
+    if (best_val) best_val[b] = v;
+    if (commit) {
+      const size_t row = (size_t)b * S + stage;
+      int32_t *pre = t.prefix + ((size_t)b * (S + 1) + stage) * 2;
+      int32_t core[64];
+      bool ok = false;
+      if (c >= 0 && (uint32_t)c < M) {
+        uint32_t dec;
+        ok = eval_candidate<true>(d, sp, (uint32_t)c, dec, core);
+      }
+      if (!ok) {
+        if (forced) t.err[0] = 1;
+        t.alive[b] = 0;
+        t.cids[row] = -1;
+        t.vals[row] = __builtin_inff();
+        pre[2] = pre[0]; pre[3] = pre[1];
+      } else {
 #pragma unroll
-  for (int k = 0; k < 64; ++k) t.cf[row * 64 + k] = core[k];
-  int32_t *st = t.states + row * 16;
-  st[0] = core[17]; st[1] = core[18]; st[2] = core[19];
-  st[3] = core[23]; st[4] = core[26]; st[5] = core[29]; st[6] = core[32]; st[7] = core[33];
-  st[8] = core[34]; st[9] = core[35]; st[10] = core[36];
-  st[11] = core[37];
-  st[12] = core[20]; st[13] = core[21]; st[14] = core[22];
-  st[15] = 1;
-  t.cids[row] = c;
-  t.vals[row] = v;
-  pre[2] = sadd((uint32_t)pre[0], (uint32_t)core[40]);
-  pre[3] = sadd((uint32_t)pre[1], (uint32_t)core[50]);
+        for (int k = 0; k < 64; ++k) t.cf[row * 64 + k] = core[k];
+        int32_t *st = t.states + row * 16;
+        st[0] = core[17]; st[1] = core[18]; st[2] = core[19];
+        st[3] = core[23]; st[4] = core[26]; st[5] = core[29]; st[6] = core[32]; st[7] = core[33];
+        st[8] = core[34]; st[9] = core[35]; st[10] = core[36];
+        st[11] = core[37];
+        st[12] = core[20]; st[13] = core[21]; st[14] = core[22];
+        st[15] = 1;
+        t.cids[row] = c;
+        t.vals[row] = v;
+        pre[2] = sadd((uint32_t)pre[0], (uint32_t)core[40]);
+        pre[3] = sadd((uint32_t)pre[1], (uint32_t)core[50]);
+      }
+    }
+  }
+  // the next stage's decision context, for the fused scorer
+  if (commit && decpack_next && stage + 1 < S) {
+    __threadfence();
+    __syncthreads();
+    write_decpack(pk, t, b, stage + 1, decpack_next);
+  }
 }
 
 }  // namespace
@@ -186,6 +201,7 @@ int vfk_setup_tables(vf_ctx *c) {
 }
 
 int vfk_reset_state(vf_ctx *c) {
+  c->dec_stage = -1;
   size_t n = (size_t)c->B * c->S * 64;
   int blocks = (int)((n + 255) / 256);
   if (blocks > 1024) blocks = 1024;
@@ -218,15 +234,25 @@ int vfk_featurize(vf_ctx *c, int stage, int32_t *feat) {
 int vfk_commit_from_partials(vf_ctx *c, int stage, int nparts, int commit, int32_t *best_cid, float *best_val) {
   vf_prof_scope prof(c, VF_PROF_COMMIT);
   hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), stage, nparts, c->d_pval,
-                     c->d_pidx, (const int32_t *)nullptr, commit, (uint32_t)c->M, best_cid, best_val);
+                     c->d_pidx, (const int32_t *)nullptr, commit, (uint32_t)c->M, best_cid, best_val, c->d_decpack);
   VF_HIP(c, hipGetLastError());
+  if (commit) c->dec_stage = stage + 1 < c->S ? stage + 1 : -1;
   return VF_OK;
 }
 
 int vfk_commit_forced(vf_ctx *c, int stage) {
   hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), stage, 0,
                      (const float *)nullptr, (const int32_t *)nullptr, (const int32_t *)c->d_forced, 1,
-                     (uint32_t)c->M, (int32_t *)nullptr, (float *)nullptr);
+                     (uint32_t)c->M, (int32_t *)nullptr, (float *)nullptr, (uint32_t *)nullptr);
   VF_HIP(c, hipGetLastError());
+  c->dec_stage = -1;
+  return VF_OK;
+}
+
+int vfk_prepare(vf_ctx *c, int stage) {
+  if (c->dec_stage == stage) return VF_OK;
+  hipLaunchKernelGGL(k_prepare, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), stage, c->d_decpack);
+  VF_HIP(c, hipGetLastError());
+  c->dec_stage = stage;
   return VF_OK;
 }

@@ -251,6 +251,50 @@ __device__ __forceinline__ bool eval_candidate(const Dec &d, const vf_space &sp,
 }
 
 
+// ---- normalisation (Sec. 3.2: the network is fed normalised feature values)
+
+// piecewise-linear log2 of a non-negative integer: exponent + (significand - 1)
+__device__ __forceinline__ float plog2_dev(int32_t x) {
+  if (x <= 0) return 0.0f;
+  float xf = (float)x;  // round to nearest even
+  uint32_t u = __float_as_uint(xf);
+  int e = (int)(u >> 23) - 127;
+  float frac = __uint_as_float((u & 0x007fffffu) | 0x3f800000u) - 1.0f;  // exact
+  return (float)e + frac;
+}
+
+typedef __bf16 vf_bf16x2 __attribute__((ext_vector_type(2)));
+typedef float vf_floatx2 __attribute__((ext_vector_type(2)));
+
+// two floats -> packed bfloat16 pair (round to nearest even, v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  vf_floatx2 v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, vf_bf16x2));
+}
+
+// The decision context in the form the fused scorer wants it: built once per problem
+// and stage (by the commit of the stage before, or by k_prepare), fetched by every
+// scoring workgroup with one coalesced copy.
+struct DecPack {
+  Dec d;
+  vf_space sp;
+  uint32_t nbh[96];  // rows 64..255 normalised, as bf16 pairs
+  uint32_t pad[VF_DECPACK_DWORDS - (sizeof(Dec) + sizeof(vf_space)) / 4 - 96];
+};
+static_assert(sizeof(DecPack) == VF_DECPACK_DWORDS * 4, "DecPack size");
+
+// Builds the pack for (problem b, stage) in LDS and copies it to out[b].
+__device__ void write_decpack(DecPack &pk, const Tables &t, int b, int stage, uint32_t *out) {
+  build_dec(pk.d, pk.sp, t, b, stage);
+  for (int q = threadIdx.x; q < 96; q += blockDim.x)
+    pk.nbh[q] = pack_bf16(plog2_dev(pk.d.nb[2 * q]), plog2_dev(pk.d.nb[2 * q + 1]));
+  __syncthreads();
+  const uint32_t *src = reinterpret_cast<const uint32_t *>(&pk);
+  const int used = (int)((sizeof(Dec) + sizeof(vf_space)) / 4 + 96);
+  for (int i = threadIdx.x; i < VF_DECPACK_DWORDS; i += blockDim.x)
+    out[(size_t)b * VF_DECPACK_DWORDS + i] = i < used ? src[i] : 0u;
+}
+
 // Table pointers of a context.
 inline Tables tables_of(const vf_ctx *c) {
   Tables t;

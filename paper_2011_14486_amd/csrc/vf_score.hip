@@ -27,15 +27,6 @@ namespace {
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 
-__device__ __forceinline__ float plog2_dev(int32_t x) {
-  if (x <= 0) return 0.0f;
-  float xf = (float)x;  // round to nearest even
-  uint32_t u = __float_as_uint(xf);
-  int e = (int)(u >> 23) - 127;
-  float frac = __uint_as_float((u & 0x007fffffu) | 0x3f800000u) - 1.0f;  // exact
-  return (float)e + frac;
-}
-
 // float -> bfloat16 bits, round to nearest, ties to even
 __device__ __forceinline__ uint32_t bf16_bits(float v) {
   uint32_t u = __float_as_uint(v);
@@ -163,14 +154,6 @@ __global__ __launch_bounds__(256) void k_copy_f32(const float *src, float *dst, 
   if (i < n) dst[i] = round_bf16 ? bf16_val(src[i]) : src[i];
 }
 
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef float floatx2 __attribute__((ext_vector_type(2)));
-
-// two floats -> packed bfloat16 pair (round to nearest even, v_cvt_pk_bf16_f32)
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
-  floatx2 v = {lo, hi};
-  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
 // ReLU on the bit pattern: negative values (sign bit set, including -0) become +0,
 // everything else, NaN included, is kept
 __device__ __forceinline__ float relu_bits(float v) {
@@ -388,6 +371,7 @@ struct FastDev {
   const uint4 *w_stream;   // per wave: [layer][k step][row tile r][lane] fragments
   size_t wave_stride;      // in uint4
   const float *aux;
+  int naux;                // floats in aux (biases of all layers, output vector)
   size_t bias_off[8];
   size_t wl_off;
 };
@@ -433,8 +417,7 @@ __global__ __launch_bounds__(256) void k_pack_stream(const float *blob, FastDev 
 // the scheduling tables of problem blockIdx.y (x is not used): the features go
 // straight into LDS as normalised bf16 and never touch HBM.
 struct GenArgs {
-  Tables t;
-  int stage;
+  const uint32_t *decpack;  // [problem][VF_DECPACK_DWORDS], built for the stage being decided
 };
 
 template <int NC, int RT, int PD, bool GEN>
@@ -448,6 +431,8 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   uint16_t *act = reinterpret_cast<uint16_t *>(smem);                   // [NC][ks]
   float *red = reinterpret_cast<float *>(smem + (size_t)NC * ks * 2);   // [8][NC]
   int32_t *okf = reinterpret_cast<int32_t *>(red + 8 * NC);             // [NC]
+  float *auxs = reinterpret_cast<float *>(okf + NC);                    // [naux] biases, output vector
+  __shared__ DecPack pk;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -455,6 +440,13 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   const int64_t n0 = (int64_t)blockIdx.x * NC;
   const int32_t *xp = x + (size_t)p * prob_stride;
   const int NH = md.L - 1;
+
+  // first in flight: the decision context and the small fp32 vectors
+  uint32_t pkw = 0;
+  if (GEN && tid < VF_DECPACK_DWORDS) pkw = ga.decpack[(size_t)p * VF_DECPACK_DWORDS + tid];
+  float auxv[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q) auxv[q] = (tid + q * 512 < md.naux) ? md.aux[tid + q * 512] : 0.0f;
 
   const uint4 *wp = md.w_stream + (size_t)w * md.wave_stride + lane;
   uint4 ring[PD][RT];
@@ -464,17 +456,19 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     for (int r = 0; r < RT; ++r) ring[j][r] = wp[(j * RT + r) * 64];
   wp += PD * RT * 64;
 
+  if (GEN && tid < VF_DECPACK_DWORDS) reinterpret_cast<uint32_t *>(&pk)[tid] = pkw;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+    if (tid + q * 512 < md.naux) auxs[tid + q * 512] = auxv[q];
+  for (int i = tid + 2048; i < md.naux; i += 512) auxs[i] = md.aux[i];
+  __syncthreads();
+
   if (GEN) {
     // ---- enumerate + featurize the tile: thread n < NC owns candidate n0 + n
-    __shared__ Dec dctx;
-    __shared__ vf_space sp;
-    __shared__ uint32_t nbh[96];  // rows 64..255, normalised, as bf16 pairs
+    const Dec &dctx = pk.d;
+    const vf_space &sp = pk.sp;
+    const uint32_t *nbh = pk.nbh;
     const int F = md.dims[0];
-    build_dec(dctx, sp, ga.t, p, ga.stage);
-    if (F == 256 && tid >= 256 && tid < 352) {
-      const int q = tid - 256;
-      nbh[q] = pack_bf16(plog2_dev(dctx.nb[2 * q]), plog2_dev(dctx.nb[2 * q + 1]));
-    }
     if (tid < NC) {
       int32_t core[64];
       bool valid = false;
@@ -497,7 +491,6 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
         *reinterpret_cast<uint4 *>(act + (size_t)tid * ks + k8 * 8) = q;
       }
     }
-    __syncthreads();
     if (F == 256) {
       // the 192 neighbour rows are the same for every candidate id below M
       const int n = tid % NC, part = tid / NC;
@@ -584,7 +577,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
         for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
       }
     }
-    const float *bias = md.aux + md.bias_off[l];
+    const float *bias = auxs + md.bias_off[l];
     if (l < NH - 1) {
       __syncthreads();  // every wave has read the layer's input: it can be overwritten
 #pragma unroll
@@ -604,7 +597,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       }
       __syncthreads();
     } else {
-      const float *wl = md.aux + md.wl_off;
+      const float *wl = auxs + md.wl_off;
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
         const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
@@ -638,7 +631,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     float v = __builtin_inff();
     int32_t c = -1;
     if (tid < NC) {
-      float s = md.aux[md.bias_off[md.L - 1]];
+      float s = auxs[md.bias_off[md.L - 1]];
 #pragma unroll
       for (int g = 0; g < 8; ++g) s += red[g * NC + tid];
       if (scores && (n0 + tid) < M) scores[(size_t)p * ld_scores + n0 + tid] = s;
@@ -1056,16 +1049,21 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     for (int l = 0; l < 8; ++l) { fd.dims[l] = m.dims[l]; fd.bias_off[l] = c->pm.aux_off[l]; }
     fd.w_stream = reinterpret_cast<const uint4 *>(c->pm.w_stream);
     fd.wave_stride = c->pm.wave_stride; fd.aux = c->pm.aux; fd.wl_off = c->pm.aux_off[7];
+    fd.naux = (int)(c->pm.aux_off[7] + m.dims[L - 1]);
+    const size_t smem_fast = smem + (size_t)fd.naux * 4;
     dim3 grid((unsigned)nparts, (unsigned)nprob);
     void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, FastDev, int, float *, int64_t, float *, int32_t *, int,
                  GenArgs);
     GenArgs ga;
-    ga.t = tables_of(c);
-    ga.stage = gen_stage;
+    ga.decpack = c->d_decpack;
+    if (gen_stage >= 0) {
+      int rc2 = vfk_prepare(c, gen_stage);
+      if (rc2 != VF_OK) return rc2;
+    }
     if (gen_stage >= 0) kern = wide ? k_mlp_fast<64, 4, 2, true> : k_mlp_fast<128, 2, 4, true>;
     else kern = wide ? k_mlp_fast<64, 4, 2, false> : k_mlp_fast<128, 2, 4, false>;
-    VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, x, prob_stride, M, ld, use_valid_row, fd, ks, scores,
+    VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_fast));
+    hipLaunchKernelGGL(kern, grid, dim3(512), smem_fast, st, x, prob_stride, M, ld, use_valid_row, fd, ks, scores,
                        ld_scores, c->d_pval, c->d_pidx, nparts, ga);
     VF_HIP(c, hipGetLastError());
   } else if (nparts > 0) {
