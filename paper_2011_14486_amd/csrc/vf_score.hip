@@ -469,26 +469,42 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     const vf_space &sp = pk.sp;
     const uint32_t *nbh = pk.nbh;
     const int F = md.dims[0];
-    if (tid < NC) {
+    // four threads per candidate, each producing 16 of the 64 core rows: the parts a
+    // thread does not store are dead code in its copy of the evaluation
+    {
+      const int n = tid % NC, part = tid / NC;
+      const uint32_t cid = (uint32_t)(n0 + n);
+      const bool inb = (int64_t)cid < M;
       int32_t core[64];
-      bool valid = false;
-      const uint32_t cid = (uint32_t)(n0 + tid);
-      if ((int64_t)cid < M) {
-        uint32_t dec;
-        valid = eval_candidate<true>(dctx, sp, cid, dec, core);
-      } else {
-#pragma unroll
-        for (int k = 0; k < 64; ++k) core[k] = 0;
-      }
-      okf[tid] = valid;
-#pragma unroll
-      for (int k8 = 0; k8 < 8; ++k8) {
-        uint4 q;
-        q.x = pack_bf16(plog2_dev(core[k8 * 8 + 0]), plog2_dev(core[k8 * 8 + 1]));
-        q.y = pack_bf16(plog2_dev(core[k8 * 8 + 2]), plog2_dev(core[k8 * 8 + 3]));
-        q.z = pack_bf16(plog2_dev(core[k8 * 8 + 4]), plog2_dev(core[k8 * 8 + 5]));
-        q.w = pack_bf16(plog2_dev(core[k8 * 8 + 6]), plog2_dev(core[k8 * 8 + 7]));
-        *reinterpret_cast<uint4 *>(act + (size_t)tid * ks + k8 * 8) = q;
+      uint32_t dec;
+      auto put = [&](const int32_t *v, int row0) {
+        uint4 q0, q1;
+        q0.x = pack_bf16(plog2_dev(v[0]), plog2_dev(v[1]));
+        q0.y = pack_bf16(plog2_dev(v[2]), plog2_dev(v[3]));
+        q0.z = pack_bf16(plog2_dev(v[4]), plog2_dev(v[5]));
+        q0.w = pack_bf16(plog2_dev(v[6]), plog2_dev(v[7]));
+        q1.x = pack_bf16(plog2_dev(v[8]), plog2_dev(v[9]));
+        q1.y = pack_bf16(plog2_dev(v[10]), plog2_dev(v[11]));
+        q1.z = pack_bf16(plog2_dev(v[12]), plog2_dev(v[13]));
+        q1.w = pack_bf16(plog2_dev(v[14]), plog2_dev(v[15]));
+        if (!inb) q0 = q1 = make_uint4(0u, 0u, 0u, 0u);
+        uint4 *dst = reinterpret_cast<uint4 *>(act + (size_t)n * ks + row0);
+        dst[0] = q0;
+        dst[1] = q1;
+      };
+      if (part == 0) {
+        const bool valid = inb && eval_candidate<true>(dctx, sp, cid, dec, core);
+        okf[n] = valid;
+        put(core, 0);
+      } else if (part == 1) {
+        eval_candidate<true>(dctx, sp, cid, dec, core);
+        put(core + 16, 16);
+      } else if (part == 2) {
+        eval_candidate<true>(dctx, sp, cid, dec, core);
+        put(core + 32, 32);
+      } else if (part == 3) {
+        eval_candidate<true>(dctx, sp, cid, dec, core);
+        put(core + 48, 48);
       }
     }
     if (F == 256) {
@@ -543,13 +559,22 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   const uint16_t *brow = act + (size_t)(lane & 31) * ks + 8 * (lane >> 5);
   for (int l = 0; l < NH; ++l) {
     const int ksteps = md.dims[l] / 16;
+    // the accumulators start from the bias of their output row
+    const float *bias = auxs + md.bias_off[l];
     floatx16 acc[RT][CT];
 #pragma unroll
-    for (int r = 0; r < RT; ++r)
+    for (int r = 0; r < RT; ++r) {
+      const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
 #pragma unroll
-      for (int c = 0; c < CT; ++c)
+      for (int g = 0; g < 4; ++g) {
+        const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
 #pragma unroll
-        for (int j = 0; j < 16; ++j) acc[r][c][j] = 0.0f;
+        for (int c = 0; c < CT; ++c) {
+          acc[r][c][4 * g + 0] = bv.x; acc[r][c][4 * g + 1] = bv.y;
+          acc[r][c][4 * g + 2] = bv.z; acc[r][c][4 * g + 3] = bv.w;
+        }
+      }
+    }
     uint4 bcur[CT];
 #pragma unroll
     for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ks);
@@ -577,7 +602,6 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
         for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
       }
     }
-    const float *bias = auxs + md.bias_off[l];
     if (l < NH - 1) {
       __syncthreads();  // every wave has read the layer's input: it can be overwritten
 #pragma unroll
@@ -585,12 +609,11 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
         const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
 #pragma unroll
           for (int c = 0; c < CT; ++c) {
             uint2 q;
-            q.x = pack_bf16(relu_bits(acc[r][c][4 * g + 0] + bv.x), relu_bits(acc[r][c][4 * g + 1] + bv.y));
-            q.y = pack_bf16(relu_bits(acc[r][c][4 * g + 2] + bv.z), relu_bits(acc[r][c][4 * g + 3] + bv.w));
+            q.x = pack_bf16(relu_bits(acc[r][c][4 * g + 0]), relu_bits(acc[r][c][4 * g + 1]));
+            q.y = pack_bf16(relu_bits(acc[r][c][4 * g + 2]), relu_bits(acc[r][c][4 * g + 3]));
             *reinterpret_cast<uint2 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + mbase + 8 * g) = q;
           }
         }
@@ -603,12 +626,11 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
         const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-          const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
           const float4 wv = *reinterpret_cast<const float4 *>(wl + mbase + 8 * g);
 #pragma unroll
           for (int c = 0; c < CT; ++c) {
-            uint32_t q0 = pack_bf16(relu_bits(acc[r][c][4 * g + 0] + bv.x), relu_bits(acc[r][c][4 * g + 1] + bv.y));
-            uint32_t q1 = pack_bf16(relu_bits(acc[r][c][4 * g + 2] + bv.z), relu_bits(acc[r][c][4 * g + 3] + bv.w));
+            uint32_t q0 = pack_bf16(relu_bits(acc[r][c][4 * g + 0]), relu_bits(acc[r][c][4 * g + 1]));
+            uint32_t q1 = pack_bf16(relu_bits(acc[r][c][4 * g + 2]), relu_bits(acc[r][c][4 * g + 3]));
             float d = dot[c];
             d = fmaf(__uint_as_float(q0 << 16), wv.x, d);
             d = fmaf(__uint_as_float(q0 & 0xffff0000u), wv.y, d);
