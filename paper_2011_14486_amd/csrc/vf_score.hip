@@ -424,7 +424,7 @@ template <int NC, int RT, int PD, bool GEN>
 __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
                                                   int use_valid_row, FastDev md, int ks, float *scores,
                                                   int64_t ld_scores, float *pval, int32_t *pidx, int nparts,
-                                                  GenArgs ga) {
+                                                  int nprob, GenArgs ga) {
   constexpr int CT = NC / 32;
   constexpr int SEGS = 512 / NC;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -436,19 +436,20 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int p = blockIdx.y;
-  const int64_t n0 = (int64_t)blockIdx.x * NC;
-  const int32_t *xp = x + (size_t)p * prob_stride;
   const int NH = md.L - 1;
 
-  // first in flight: the decision context and the small fp32 vectors
-  uint32_t pkw = 0;
-  if (GEN && tid < VF_DECPACK_DWORDS) pkw = ga.decpack[(size_t)p * VF_DECPACK_DWORDS + tid];
-  float auxv[4];
+  // ---- once per workgroup: the small fp32 vectors into LDS, the weight ring primed
+  {
+    float auxv[4];
 #pragma unroll
-  for (int q = 0; q < 4; ++q) auxv[q] = (tid + q * 512 < md.naux) ? md.aux[tid + q * 512] : 0.0f;
-
-  const uint4 *wp = md.w_stream + (size_t)w * md.wave_stride + lane;
+    for (int q = 0; q < 4; ++q) auxv[q] = (tid + q * 512 < md.naux) ? md.aux[tid + q * 512] : 0.0f;
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      if (tid + q * 512 < md.naux) auxs[tid + q * 512] = auxv[q];
+    for (int i = tid + 2048; i < md.naux; i += 512) auxs[i] = md.aux[i];
+  }
+  const uint4 *const wbase = md.w_stream + (size_t)w * md.wave_stride + lane;
+  const uint4 *wp = wbase;
   uint4 ring[PD][RT];
 #pragma unroll
   for (int j = 0; j < PD; ++j)
@@ -456,11 +457,21 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     for (int r = 0; r < RT; ++r) ring[j][r] = wp[(j * RT + r) * 64];
   wp += PD * RT * 64;
 
-  if (GEN && tid < VF_DECPACK_DWORDS) reinterpret_cast<uint32_t *>(&pk)[tid] = pkw;
-#pragma unroll
-  for (int q = 0; q < 4; ++q)
-    if (tid + q * 512 < md.naux) auxs[tid + q * 512] = auxv[q];
-  for (int i = tid + 2048; i < md.naux; i += 512) auxs[i] = md.aux[i];
+  // ---- persistent loop: this workgroup's share of the (problem, tile) pairs, in
+  // problem-major order so that consecutive tiles mostly share the decision context
+  const int T = nparts * nprob;
+  const int t_begin = (int)((int64_t)blockIdx.x * T / gridDim.x);
+  const int t_end = (int)((int64_t)(blockIdx.x + 1) * T / gridDim.x);
+  int cur_p = -1;
+  for (int t = t_begin; t < t_end; ++t) {
+  const int p = t / nparts;
+  const int64_t n0 = (int64_t)(t - p * nparts) * NC;
+  const int32_t *xp = x + (size_t)p * prob_stride;
+  if (GEN && p != cur_p) {
+    if (tid < VF_DECPACK_DWORDS)
+      reinterpret_cast<uint32_t *>(&pk)[tid] = ga.decpack[(size_t)p * VF_DECPACK_DWORDS + tid];
+    cur_p = p;
+  }
   __syncthreads();
 
   if (GEN) {
@@ -579,6 +590,8 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
 #pragma unroll
     for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ks);
     for (int s0 = 0; s0 < ksteps; s0 += PD) {
+      // the last PD steps of a tile prefetch the first PD steps of the next one
+      if (l == NH - 1 && s0 + PD >= ksteps) wp = wbase;
 #pragma unroll
       for (int j = 0; j < PD; ++j) {
         uint4 a[RT], bnext[CT];
@@ -667,13 +680,15 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       __syncthreads();
       if (tid == 0) {
         for (int k = 1; k < NC / 64; ++k) take_min(v, c, sv[k], sc[k]);
-        pval[(size_t)p * nparts + blockIdx.x] = v;
-        pidx[(size_t)p * nparts + blockIdx.x] = c;
+        pval[(size_t)t] = v;
+        pidx[(size_t)t] = c;
       }
     } else if (tid == 0) {
-      pval[(size_t)p * nparts + blockIdx.x] = v;
-      pidx[(size_t)p * nparts + blockIdx.x] = c;
+      pval[(size_t)t] = v;
+      pidx[(size_t)t] = c;
     }
+  }
+  __syncthreads();  // the tile's LDS is free for the next one
   }
 }
 
@@ -1073,9 +1088,13 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     fd.wave_stride = c->pm.wave_stride; fd.aux = c->pm.aux; fd.wl_off = c->pm.aux_off[7];
     fd.naux = (int)(c->pm.aux_off[7] + m.dims[L - 1]);
     const size_t smem_fast = smem + (size_t)fd.naux * 4;
-    dim3 grid((unsigned)nparts, (unsigned)nprob);
+    // persistent: at most one workgroup per CU, each walking its share of the tiles
+    int ncu = 256;
+    (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
+    const int64_t tiles = (int64_t)nparts * nprob;
+    dim3 grid((unsigned)(tiles < ncu ? tiles : ncu));
     void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, FastDev, int, float *, int64_t, float *, int32_t *, int,
-                 GenArgs);
+                 int, GenArgs);
     GenArgs ga;
     ga.decpack = c->d_decpack;
     if (gen_stage >= 0) {
@@ -1086,7 +1105,7 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     else kern = wide ? k_mlp_fast<64, 4, 2, false> : k_mlp_fast<128, 2, 4, false>;
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_fast));
     hipLaunchKernelGGL(kern, grid, dim3(512), smem_fast, st, x, prob_stride, M, ld, use_valid_row, fd, ks, scores,
-                       ld_scores, c->d_pval, c->d_pidx, nparts, ga);
+                       ld_scores, c->d_pval, c->d_pidx, nparts, nprob, ga);
     VF_HIP(c, hipGetLastError());
   } else if (nparts > 0) {
     vf_prof_scope prof(c, VF_PROF_SCORE);
