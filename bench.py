@@ -19,6 +19,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at batch 256, scaled by a
+# plain 1 GiB copy (profiles/*_hbm_counters.txt); only valid for the default batch, and to be
+# set to None whenever the kernel changes without the counters being taken again
+TRAFFIC_SCORE_BYTES = {256: 7.58e6 + 1.11e6}
+TRAFFIC_FEATURIZE_BYTES = {256: 4.49e6 + 1073741824.0}
 
 
 def mlp_flops(dims):
@@ -46,6 +51,8 @@ def main():
     ap.add_argument("--batch", type=int, default=256, help="independent pipelines per step")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true", help="skip the single-pipeline latency measurement")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy a few times (reference for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -75,6 +82,14 @@ def main():
         vf.vf_reset_state(ctx)
         vf.vf_greedy_schedule(ctx, 0, S - 1, out=out)
 
+    if args.calibrate_copy:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -102,7 +117,7 @@ def main():
     score_ms = ms_score / max(n_score, 1)
     achieved = flops_per_launch / (score_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "k_mlp_fast<128,2,4,gen> (enumerate+featurize+MLP+argmin fused)", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
-                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_SCORE_BYTES.get(B),
                 "launch_ms": score_ms, "launches": n_score}
     # the materialising featurizer (vf_featurize) on the same batch: in the step above the
     # features are produced inside the scoring kernel and never written to HBM, so the
@@ -121,7 +136,7 @@ def main():
     feat_ms = ms_featk / max(n_featk, 1)
     feat_gbs = feat_bytes / (feat_ms * 1e-3) / 1e9
     roofline_feat = {"bound": "hbm", "kernel": "k_featurize", "achieved": feat_gbs, "peak": PEAK_HBM_GBS,
-                     "unit": "GB/s", "frac": feat_gbs / PEAK_HBM_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": feat_gbs / PEAK_HBM_GBS, "traffic": TRAFFIC_FEATURIZE_BYTES.get(B),
                      "launch_ms": feat_ms, "launches": n_featk,
                      "note": "vf_featurize alone, 10 launches after the timed region"}
 
