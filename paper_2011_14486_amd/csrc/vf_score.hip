@@ -696,12 +696,13 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
 
 struct LstmDev {
   int F, H;
-  const uint16_t *w_pack;  // [unit tile][gate][kstep][lane][8]
+  const uint16_t *w_pack;  // [unit tile][k step][gate][lane][8]
   const float *aux;        // b_ih + b_hh [4H], head vector [H], head bias [1]
 };
 
-// [W_ih | W_hh] as one [4H][F+H] matrix in A-fragment order, grouped so that the four
-// gate row tiles of a tile of 32 hidden units are adjacent.
+// [W_ih | W_hh] as one [4H][F+H] matrix in A-fragment order.  The wave that owns a
+// tile of 32 hidden units reads, per k-step, the four gate fragments of that tile:
+// they are adjacent, and the k-steps of one timestep form one contiguous stream.
 __global__ __launch_bounds__(256) void k_pack_lstm(const float *Wih, const float *Whh, int F, int H,
                                                    uint16_t *out) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
@@ -709,8 +710,8 @@ __global__ __launch_bounds__(256) void k_pack_lstm(const float *Wih, const float
   int e = (int)(i & 7), lane = (int)((i >> 3) & 63);
   size_t rest = i >> 9;
   int ksteps = (F + H) / 16;
-  int s = (int)(rest % ksteps); rest /= ksteps;
-  int g = (int)(rest % 4), u = (int)(rest / 4);
+  int g = (int)(rest % 4); rest /= 4;
+  int s = (int)(rest % ksteps), u = (int)(rest / ksteps);
   int row = g * H + u * 32 + (lane & 31), k = s * 16 + 8 * (lane >> 5) + e;
   float v = k < F ? Wih[(size_t)row * F + k] : Whh[(size_t)row * H + (k - F)];
   out[i] = (uint16_t)bf16_bits(v);
@@ -724,32 +725,48 @@ __global__ __launch_bounds__(256) void k_lstm_aux(const float *bih, const float 
   else if (i == 5 * H) aux[i] = bh[0];
 }
 
-__device__ __forceinline__ float sigmoid_dev(float z) { return __fdividef(1.0f, 1.0f + __expf(-z)); }
-__device__ __forceinline__ float tanh_dev(float z) { return 2.0f * sigmoid_dev(2.0f * z) - 1.0f; }
+__device__ __forceinline__ float sigmoid_dev(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
+__device__ __forceinline__ float tanh_dev(float z) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * z)); }
 
 // One workgroup walks NC sequences through all T steps.  Wave w owns hidden units
 // 32w..32w+31: the four gate row tiles of those units for every candidate column.
-template <int NC, int XPT>
+// Per step: the x_t part of the contraction (it does not depend on h_{t-1}), one
+// barrier, the h_{t-1} part, the gates.  h is double-buffered in LDS so that h_t is
+// written as it is produced; x_{t+1} is fetched a step ahead; the weight fragments
+// of a timestep are one contiguous stream per wave, kept PD k-steps ahead in a
+// register ring that wraps at the end of the step.
+template <int NC, int XPT, int PD>
 __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M, int T, LstmDev md, int xld,
                                                    int hld, float *scores, float *pval, int32_t *pidx) {
   constexpr int CT = NC / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t *xs = reinterpret_cast<uint16_t *>(smem);           // [2][NC][xld]
-  uint16_t *hs = xs + (size_t)2 * NC * xld;                    // [NC][hld]
-  float *red = reinterpret_cast<float *>(hs + (size_t)NC * hld);  // [8][NC]
+  uint16_t *xs = reinterpret_cast<uint16_t *>(smem);                  // [2][NC][xld]
+  uint16_t *hs = xs + (size_t)2 * NC * xld;                           // [2][NC][hld]
+  float *red = reinterpret_cast<float *>(hs + (size_t)2 * NC * hld);  // [8][NC]
+  float *auxs = red + 8 * NC;                                         // [5H+1]
 
-  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int F = md.F, H = md.H;
   const int64_t n0 = (int64_t)blockIdx.x * NC;
   const int cpr = F / 8;                 // 16-byte chunks per sequence row
   const int nchunks = NC * cpr;          // <= 512 * XPT
-  const int ksx = F / 16, ksteps = (F + H) / 16;
+  const int ksx = F / 16, ksh = H / 16, ksteps = ksx + ksh;
   const bool active = w < H / 32;
-  const uint4 *Wp = reinterpret_cast<const uint4 *>(md.w_pack) + (size_t)w * 4 * ksteps * 64;
-  const float *bias = md.aux, *wh = md.aux + 4 * H;
+  const int wu = active ? w : 0;         // idle waves shadow tile 0 but never store
+  const uint4 *const wbase = reinterpret_cast<const uint4 *>(md.w_pack) + (size_t)wu * ksteps * 4 * 64 + lane;
+  const uint4 *wp = wbase;
 
-  for (int i = tid; i < NC * hld / 2; i += 512) reinterpret_cast<uint32_t *>(hs)[i] = 0u;
+  uint4 ring[PD][4];
+#pragma unroll
+  for (int j = 0; j < PD; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) ring[j][g] = wp[(j * 4 + g) * 64];
+  wp += PD * 4 * 64;
+
+  for (int i = tid; i < NC * hld; i += 512) reinterpret_cast<uint32_t *>(hs)[i] = 0u;  // both h buffers
   for (int i = tid; i < 8 * NC; i += 512) red[i] = 0.0f;
+  for (int i = tid; i < 5 * H + 1; i += 512) auxs[i] = md.aux[i];
 
   uint4 xr[XPT];
   auto fetch = [&](int t) {
@@ -757,7 +774,7 @@ __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M,
     for (int q = 0; q < XPT; ++q) {
       int ch = tid + q * 512;
       uint4 v = make_uint4(0u, 0u, 0u, 0u);
-      if (ch < nchunks) {
+      if (ch < nchunks && t < T) {
         int n = ch / cpr, kc = ch % cpr;
         if (n0 + n < M) v = *reinterpret_cast<const uint4 *>(x + ((size_t)(n0 + n) * T + t) * F + kc * 8);
       }
@@ -783,85 +800,110 @@ __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M,
 #pragma unroll
     for (int j = 0; j < 16; ++j) cst[c][j] = 0.0f;
   }
-  if (T > 0) { fetch(0); stash(0); }
+  fetch(0);
+  stash(0);
+  fetch(1);
   __syncthreads();
 
+  const float *bias = auxs, *wh = auxs + 4 * H;
+  const int rowoff = (lane & 31), koff = 8 * (lane >> 5);
   for (int t = 0; t < T; ++t) {
-    if (t + 1 < T) fetch(t + 1);
+    // x_{t+1} (fetched during the previous step) goes to the buffer last read at t-1
+    stash((t + 1) & 1);
+    fetch(t + 2);
+
     floatx16 acc[4][CT];
-    float hn[CT][16];
-    if (active) {
 #pragma unroll
-      for (int g = 0; g < 4; ++g)
+    for (int g = 0; g < 4; ++g)
 #pragma unroll
-        for (int c = 0; c < CT; ++c)
-#pragma unroll
-          for (int j = 0; j < 16; ++j) acc[g][c][j] = 0.0f;
-      const uint16_t *xrow = xs + ((size_t)(t & 1) * NC + (lane & 31)) * xld + 8 * (lane >> 5);
-      const uint16_t *hrow = hs + (size_t)(lane & 31) * hld + 8 * (lane >> 5);
-#pragma unroll 2
-      for (int s = 0; s < ksteps; ++s) {
-        uint4 a[4], b[CT];
-#pragma unroll
-        for (int g = 0; g < 4; ++g) a[g] = Wp[((size_t)g * ksteps + s) * 64 + lane];
-#pragma unroll
-        for (int c = 0; c < CT; ++c)
-          b[c] = s < ksx ? *reinterpret_cast<const uint4 *>(xrow + (size_t)c * 32 * xld + s * 16)
-                         : *reinterpret_cast<const uint4 *>(hrow + (size_t)c * 32 * hld + (s - ksx) * 16);
-#pragma unroll
-        for (int g = 0; g < 4; ++g)
-#pragma unroll
-          for (int c = 0; c < CT; ++c)
-            acc[g][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                __builtin_bit_cast(bf16x8, a[g]), __builtin_bit_cast(bf16x8, b[c]), acc[g][c], 0, 0, 0);
-      }
-#pragma unroll
-      for (int j = 0; j < 16; ++j) {
-        const int m = w * 32 + 8 * (j >> 2) + 4 * (lane >> 5) + (j & 3);
-        const float bi = bias[m], bf = bias[H + m], bg = bias[2 * H + m], bo = bias[3 * H + m];
-        const float whm = wh[m];
+      for (int q = 0; q < 4; ++q) {
+        const float4 bv = *reinterpret_cast<const float4 *>(bias + g * H + wu * 32 + 4 * (lane >> 5) + 8 * q);
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
-          float ig = sigmoid_dev(acc[0][c][j] + bi);
-          float fg = sigmoid_dev(acc[1][c][j] + bf);
-          float gg = tanh_dev(acc[2][c][j] + bg);
-          float og = sigmoid_dev(acc[3][c][j] + bo);
+          acc[g][c][4 * q + 0] = bv.x; acc[g][c][4 * q + 1] = bv.y;
+          acc[g][c][4 * q + 2] = bv.z; acc[g][c][4 * q + 3] = bv.w;
+        }
+      }
+
+    auto kloop = [&](const uint16_t *src, int ld, int nsteps, bool last_part) {
+      const uint16_t *brow = src + (size_t)rowoff * ld + koff;
+      uint4 bcur[CT];
+#pragma unroll
+      for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ld);
+      for (int s0 = 0; s0 < nsteps; s0 += PD) {
+        if (last_part && s0 + PD >= nsteps) wp = wbase;  // wrap: next timestep's first fragments
+#pragma unroll
+        for (int j = 0; j < PD; ++j) {
+          uint4 a[4], bnext[CT];
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            a[g] = ring[j][g];
+            ring[j][g] = wp[g * 64];
+          }
+          wp += 4 * 64;
+#pragma unroll
+          for (int c = 0; c < CT; ++c)
+            bnext[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ld + (s0 + j + 1) * 16);
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int c = 0; c < CT; ++c)
+              acc[g][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                  __builtin_bit_cast(bf16x8, a[g]), __builtin_bit_cast(bf16x8, bcur[c]), acc[g][c], 0, 0, 0);
+#pragma unroll
+          for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
+        }
+      }
+    };
+
+    kloop(xs + (size_t)(t & 1) * NC * xld, xld, ksx, false);
+    __syncthreads();  // h_{t-1} is complete; x_{t+1} is visible for the next step
+    kloop(hs + (size_t)(t & 1) * NC * hld, hld, ksh, true);
+
+    uint16_t *hout = hs + (size_t)((t + 1) & 1) * NC * hld;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const float4 whv = *reinterpret_cast<const float4 *>(wh + wu * 32 + 4 * (lane >> 5) + 8 * q);
+      const float whq[4] = {whv.x, whv.y, whv.z, whv.w};
+#pragma unroll
+      for (int c = 0; c < CT; ++c) {
+        float hv[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int j = 4 * q + e;
+          float ig = sigmoid_dev(acc[0][c][j]);
+          float fg = sigmoid_dev(acc[1][c][j]);
+          float gg = tanh_dev(acc[2][c][j]);
+          float og = sigmoid_dev(acc[3][c][j]);
           float cn = fg * cst[c][j] + ig * gg;
           cst[c][j] = cn;
-          float h = og * tanh_dev(cn);
-          hn[c][j] = h;
-          vsum[c] = fmaf(whm, h, vsum[c]);
+          hv[e] = og * tanh_dev(cn);
+          vsum[c] = fmaf(whq[e], hv[e], vsum[c]);
+        }
+        if (active) {
+          uint2 pkd;
+          pkd.x = pack_bf16(hv[0], hv[1]);
+          pkd.y = pack_bf16(hv[2], hv[3]);
+          *reinterpret_cast<uint2 *>(hout + (size_t)(c * 32 + (lane & 31)) * hld + w * 32 + 8 * q + 4 * (lane >> 5)) = pkd;
         }
       }
     }
-    __syncthreads();  // h_{t-1} and x_t have been read by every wave
-    if (active) {
-#pragma unroll
-      for (int c = 0; c < CT; ++c)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          uint2 q;
-          q.x = bf16_bits(hn[c][4 * g + 0]) | bf16_bits(hn[c][4 * g + 1]) << 16;
-          q.y = bf16_bits(hn[c][4 * g + 2]) | bf16_bits(hn[c][4 * g + 3]) << 16;
-          *reinterpret_cast<uint2 *>(hs + (size_t)(c * 32 + (lane & 31)) * hld + w * 32 + 8 * g + 4 * (lane >> 5)) = q;
-        }
-    }
-    if (t + 1 < T) stash((t + 1) & 1);
-    __syncthreads();
   }
 
   // v = sum_t (w . h_t + b): add the two lane halves, then the waves in order
+  if (active) {
 #pragma unroll
-  for (int c = 0; c < CT; ++c) {
-    float v = vsum[c] + __shfl_xor(vsum[c], 32);
-    if (lane < 32) red[w * NC + c * 32 + lane] = v;
+    for (int c = 0; c < CT; ++c) {
+      float v = vsum[c] + __shfl_xor(vsum[c], 32);
+      if (lane < 32) red[w * NC + c * 32 + lane] = v;
+    }
   }
   __syncthreads();
   {
     float v = __builtin_inff();
     int32_t cbest = -1;
     if (tid < NC) {
-      float s = (float)T * md.aux[5 * H];
+      float s = (float)T * auxs[5 * H];
 #pragma unroll
       for (int k = 0; k < 8; ++k) s += red[k * NC + tid];
       const bool inb = (n0 + tid) < M;
@@ -1131,12 +1173,17 @@ int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores
   const int nparts = (int)((M + NC - 1) / NC);
   int rc = vfk_ensure_parts(c, (size_t)(nparts > 0 ? nparts : 1));
   if (rc != VF_OK) return rc;
-  const size_t smem = (size_t)2 * NC * xld * 2 + (size_t)NC * hld * 2 + (size_t)8 * NC * 4;
+  const size_t smem = (size_t)2 * NC * xld * 2 + (size_t)2 * NC * hld * 2 + (size_t)8 * NC * 4 +
+                      (size_t)(5 * md.H + 1) * 4;
   if (nparts > 0) {
     vf_prof_scope prof(c, VF_PROF_SCORE);
-    VF_HIP(c, hipFuncSetAttribute((const void *)k_lstm_bf16<NC, 4>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
-    hipLaunchKernelGGL((k_lstm_bf16<NC, 4>), dim3((unsigned)nparts), dim3(512), smem, c->stream, x, M, T, md, xld, hld,
-                       scores, c->d_pval, c->d_pidx);
+    // ring depth 2: F and H are multiples of 32, so both parts have an even number of
+    // k-steps (depth 4 spills registers and measured slower)
+    void (*kern)(const uint16_t *, int64_t, int, LstmDev, int, int, float *, float *, int32_t *) =
+        k_lstm_bf16<NC, 4, 2>;
+    VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    hipLaunchKernelGGL(kern, dim3((unsigned)nparts), dim3(512), smem, c->stream, x, M, T, md, xld, hld, scores,
+                       c->d_pval, c->d_pidx);
     VF_HIP(c, hipGetLastError());
   }
   *nparts_out = nparts;
