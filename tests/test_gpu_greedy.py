@@ -165,3 +165,58 @@ def test_mobilenet_shaped_first_stages(vf, ovf):
     rst, _ = ovf.states(pipe, sp, cids)
     assert np.array_equal(rst, st)
     vf.vf_destroy(ctx)
+
+
+def test_fused_step_ragged_tiles_uneven_share(vf, ovf):
+    """The fused enumerate+featurize+score kernel with a candidate count that is not a
+    multiple of its tile (ragged last tile) and more (problem, tile) pairs than
+    workgroups, unevenly divided: every problem's schedule equals the checker's."""
+    sp = I.make_space([1, 2, 3, 8], [1, 2, 5], [1, 4, 16], [(0, 1, 2), (2, 1, 0), (1, 0, 2)], 2, 2,
+                      [I.ROOT, I.L1, I.L2, I.INLINE], 3, 256)
+    assert I.space_dense_count(sp) == 5184 and 5184 % 128 != 0
+    S, B = 4, 37
+    pipes = np.stack([I.random_pipeline(S, 300 + b) for b in range(B)])
+    dims = [256, 512, 512, 1]
+    w = I.mlp_weights(dims, 5, bias_std=0.1)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipes); vf.vf_set_model(ctx, model, w)
+    st, cids, vals = vf.vf_greedy_schedule(ctx)
+    st, cids, vals = st.cpu().numpy(), cids.cpu().numpy(), vals.cpu().numpy()
+    for b in range(B):
+        compare_schedule(ovf, pipes[b], sp, model, w, cids[b], vals[b], st[b], TOL[1])
+    # the unfused route (featurize to memory, then score) takes the same decisions
+    pre = cids[:, :2].copy()
+    vf.vf_set_state(ctx, pre)
+    feat = vf.vf_featurize(ctx, 2)
+    M = vf.vf_dense_count(ctx)
+    for b in (0, 17, 36):
+        s, bi, bv = vf.vf_score(ctx, feat[b].contiguous(), M=M, want_scores=True)
+        valid = feat[b, 16, :M].cpu().numpy() != 0
+        s = s.cpu().numpy()
+        best = int(np.flatnonzero(valid)[np.argmin(s[valid])])
+        assert best == cids[b, 2] and s[best] == vals[b, 2]
+    vf.vf_destroy(ctx)
+
+
+def test_benchmark_configuration_batch256(vf, ovf):
+    """The launch configuration bench.py times: 256 ResNet-18-shaped pipelines at once.
+    The checker follows three of them completely; for all of them the committed ids
+    replay to the same state records (every decision was a valid candidate)."""
+    B = 256
+    pipes = I.resnet18_batch(B, seed=2)
+    sp = I.resnet18_space()
+    dims = [256, 512, 512, 1]
+    w = I.mlp_weights(dims, 0)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipes); vf.vf_set_model(ctx, model, w)
+    st, cids, vals = vf.vf_greedy_schedule(ctx)
+    st, cids, vals = st.cpu().numpy(), cids.cpu().numpy(), vals.cpu().numpy()
+    vf.vf_destroy(ctx)
+    assert (cids >= 0).all() and np.isfinite(vals).all()
+    for b in (0, 101, 255):
+        compare_schedule(ovf, pipes[b], sp, model, w, cids[b], vals[b], st[b], TOL[1])
+    for b in range(0, B, 8):
+        rst, _ = ovf.states(pipes[b], sp, cids[b])
+        assert np.array_equal(rst, st[b])
