@@ -156,6 +156,23 @@ def main():
         single_ms = (time.perf_counter() - t1) / reps * 1e3
         vf.vf_destroy(ctx1)
 
+    # end-to-end greedy schedule of the 100-stage MobileNet-V2-shaped pipeline, 16384
+    # candidates per decision, same value network (latency of a single large problem)
+    mb_ms = None
+    if not args.no_latency:
+        ctx5 = vf.vf_create(0)
+        vf.vf_set_space(ctx5, I.mobilenetv2_space()); vf.vf_set_pipeline(ctx5, I.mobilenetv2_shaped())
+        vf.vf_set_model(ctx5, model, w)
+        for _ in range(2):
+            vf.vf_reset_state(ctx5); vf.vf_greedy_schedule(ctx5)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(5):
+            vf.vf_reset_state(ctx5); vf.vf_greedy_schedule(ctx5)
+        torch.cuda.synchronize()
+        mb_ms = (time.perf_counter() - t1) / 5 * 1e3
+        vf.vf_destroy(ctx5)
+
     line = {
         "metric": "candidate schedules scored/sec (V(s) eval) + end-to-end greedy schedule ms",
         "value": value, "unit": "candidates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -167,6 +184,7 @@ def main():
                                "seeded width/resolution variants)",
                    "batch": B, "stages": S, "candidates_per_decision": M, "candidates_per_step": cand_per_step},
         "greedy_ms_single_pipeline": single_ms,
+        "greedy_ms_mobilenetv2_100_stages_16384_candidates": mb_ms,
         "kernel_ms_per_step": {"featurize": ms_feat / args.steps, "score": ms_score / args.steps,
                                "commit": ms_commit / args.steps},
         "roofline": roofline,

@@ -148,3 +148,28 @@ def test_lstm_bf16(vf, ovf, F, H, T, B):
     ref = ovf.score_lstm(model, w, xb)
     assert score_err(s, ref) <= TOL[1]
     check_argmin(int(bi.cpu()[0]), float(bv.cpu()[0]), ref, None, TOL[1])
+
+
+def test_recurrent_workload_sample(vf, ovf):
+    """The 16,384-sequence LSTM workload (T = 50, F = 128, H = 256) at full size on the GPU;
+    the checker scores a sample of 256 sequences (the first 128 and one seeded block)."""
+    import torch
+    F, H, T, B = 128, 256, 50, 16384
+    w = I.lstm_weights(F, H, seed=0)
+    model = I.model_record(I.LSTM, [F, H, 1], I.BF16)
+    xb = I.feature_sequences(0, B, T=T, F=F, seed=4)
+    ctx = vf.vf_create(0)
+    vf.vf_set_model(ctx, model, w)
+    xd = torch.from_numpy(xb.view(np.int16)).cuda().view(torch.bfloat16)
+    s, bi, bv = vf.vf_score(ctx, xd, vf.VF_X_SEQ_BF16)
+    s2, _, _ = vf.vf_score(ctx, xd, vf.VF_X_SEQ_BF16)
+    torch.cuda.synchronize()
+    s = s.cpu().numpy()
+    assert np.array_equal(s, s2.cpu().numpy())            # run to run identical
+    vf.vf_destroy(ctx)
+    blk = int(np.random.default_rng(4).integers(1, B // 128))
+    idx = np.concatenate([np.arange(128), np.arange(blk * 128, blk * 128 + 128)])
+    ref = ovf.score_lstm(model, w, xb[idx])
+    assert score_err(s[idx], ref) <= TOL[1]
+    assert np.isfinite(s).all()
+    assert int(bi.cpu()[0]) == int(np.argmin(s)) and float(bv.cpu()[0]) == s.min()
