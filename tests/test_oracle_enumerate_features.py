@@ -275,3 +275,62 @@ def test_bad_arguments(ovf):
     pipe2 = pipe.copy(); pipe2[1, 8] = 2  # anchor listed later
     with pytest.raises(ovf.OracleError):
         ovf.featurize(pipe2, sp, [], 0)
+
+
+def test_intrinsic_closed_forms_per_kind(ovf):
+    """Block A for each stage kind, from the definitions: a conv reads C_in channels and has
+    C*C_in*KH*KW weights; a depthwise conv reads its own C channels and has C*KH*KW weights
+    whatever RC says; an ADD reads two inputs; pointwise and ADD do one op per point."""
+    sp = I.make_space([1, 2], [1, 2], [1, 2], [(0, 1, 2)], 1, 1, [I.ROOT], 1, 64)
+    W, H, C = 12, 10, 6
+    cases = {
+        I.CONV: dict(rec=I.stage_record(I.CONV, W, H, C, RC=5, KH=3, KW=7, stride=2, anchor=-1),
+                     R=105, macs=W * H * C * 105, ins=(W * 2) * (H * 2) * 5, w=C * 5 * 21),
+        I.DWCONV: dict(rec=I.stage_record(I.DWCONV, W, H, C, RC=2, KH=3, KW=5, stride=1, anchor=-1),
+                       R=30, macs=W * H * C * 30, ins=W * H * C, w=C * 15),
+        I.POINTWISE: dict(rec=I.stage_record(I.POINTWISE, W, H, C, anchor=-1), R=1, macs=W * H * C,
+                          ins=W * H * C, w=0),
+        I.ADD: dict(rec=I.stage_record(I.ADD, W, H, C, anchor=-1), R=1, macs=W * H * C,
+                    ins=2 * W * H * C, w=0),
+    }
+    for kind, c in cases.items():
+        pipe = np.array([c["rec"]], np.int32)
+        feat = ovf.featurize(pipe, sp, [], 0).astype(np.int64)
+        a = feat[:16, 0]
+        pts = W * H * C
+        assert a[0] == kind and tuple(a[1:4]) == (W, H, C) and a[4] == c["R"] and a[7] == pts
+        assert a[5] == pipe[0, 5] * pipe[0, 6] and a[6] == pipe[0, 7]
+        assert a[8] == c["macs"] and a[9] == c["ins"] and a[10] == c["w"] and a[11] == 4 * pts
+        assert a[12] == 16 * c["macs"] // (c["ins"] + c["w"] + pts)
+        # tile features of the candidate f = (2, 2, 2): cid = 1 + 2*(1 + 2*1) = 7
+        col = feat[:, 7]
+        s_, kh, kw = int(pipe[0, 7]), int(pipe[0, 5]), int(pipe[0, 6])
+        span = ((2 - 1) * s_ + kw) * ((2 - 1) * s_ + kh)
+        want_in = span * (5 if kind == I.CONV else 2) * (2 if kind == I.ADD else 1)
+        want_w = {I.CONV: 2 * 5 * kh * kw, I.DWCONV: 2 * kh * kw}.get(kind, 0)
+        assert col[16] == 1 and col[43] == want_in and col[44] == want_w and col[45] == 8 + want_in + want_w
+
+
+def test_region_under_an_anisotropic_kernel(ovf):
+    """A consumer with KW != KH: the producer region per consumer tile is
+    ((fx-1)*s + KW) x ((fy-1)*s + KH), clipped to the producer's extents."""
+    sp = I.make_space([1, 2, 4], [1, 2, 4], [1, 2], [(0, 1, 2), (1, 0, 2)], 1, 1, [I.ROOT, I.L1, I.L2], 1, 64)
+    KW, KH, s_ = 7, 3, 2
+    pipe = np.array([I.stage_record(I.CONV, 8, 8, 4, RC=3, KH=KH, KW=KW, stride=s_, anchor=-1, n_consumers=0, in0=1),
+                     I.stage_record(I.POINTWISE, 21, 17, 3, anchor=0)], np.int32)
+    _, v0, _ = ovf.enumerate_candidates(pipe, sp, [], 0)
+    for c0 in np.flatnonzero(v0):
+        st, _ = ovf.states(pipe, sp, [int(c0)])
+        fa, Oa, pa = st[0, 0:3], st[0, 12:15], int(st[0, 3])
+        feat = ovf.featurize(pipe, sp, [int(c0)], 1).astype(np.int64)
+        ok = feat[16] == 1
+        l2 = ok & (feat[32] == I.L2)
+        if l2.any():
+            want = (min(21, (fa[0] - 1) * s_ + KW), min(17, (fa[1] - 1) * s_ + KH), 3)  # conv anchor: all channels
+            assert (feat[34:37, l2] == np.array(want)[:, None]).all()
+        l1 = ok & (feat[32] == I.L1)
+        if l1.any():
+            box = np.array([8, 8, 4]); d0 = [(0, 1, 2), (1, 0, 2)][pa][0]; box[d0] = fa[d0]
+            want = (min(21, (box[0] - 1) * s_ + KW), min(17, (box[1] - 1) * s_ + KH), 3)
+            assert (feat[34:37, l1] == np.array(want)[:, None]).all()
+            assert (feat[37, l1] == Oa[d0]).all()

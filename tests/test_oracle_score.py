@@ -79,9 +79,9 @@ def test_mlp_against_library_linear(ovf, dims, dtype):
         xn = torch.from_numpy(xn).to(torch.bfloat16).to(torch.float32).numpy()
     want = torch_mlp(dims, w, xn, dtype == I.BF16)
     scale = max(np.sqrt(np.mean(want ** 2)), 1e-30)
-    # both sides accumulate in double; what is left is the final float rounding and, in
-    # bf16 mode, the rare activation that sits on a rounding boundary
-    tol = 2e-7 if dtype == I.FP32 else 2e-3
+    # both sides accumulate in double and round at the same declared points; what is left
+    # is the final float rounding
+    tol = 2e-7 if dtype == I.FP32 else 1e-6
     assert np.max(np.abs(got - want) / np.maximum(np.abs(want), scale)) < tol
 
 
@@ -157,7 +157,9 @@ def test_lstm_against_library(ovf, dtype):
     got = ovf.score_lstm(I.model_record(I.LSTM, [F, H, 1], dtype), w, xb).astype(np.float64)
     want = torch_lstm(F, H, w, xs, dtype == I.BF16)
     scale = np.sqrt(np.mean(want ** 2))
-    tol = 3e-7 if dtype == I.FP32 else 2e-3
+    # the library version rounds at the same declared points (weights, x_t, fed-back h), so
+    # the two agree to float rounding; a missing rounding point shows up at the 1e-3 level
+    tol = 3e-7 if dtype == I.FP32 else 1e-6
     assert np.max(np.abs(got - want) / np.maximum(np.abs(want), scale)) < tol
 
 
