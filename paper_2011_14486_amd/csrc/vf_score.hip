@@ -537,7 +537,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     const int n = tid % NC;
     const bool inb = (n0 + n) < M;
     const int32_t *col = xp + n0 + n;
-    constexpr int G = 4;  // groups of 8 features per pass
+    constexpr int G = 2;  // groups of 8 features per pass
     for (int k8 = tid / NC; k8 < F / 8; k8 += SEGS * G) {
       int32_t raw[G][8];
 #pragma unroll
