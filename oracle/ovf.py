@@ -57,6 +57,7 @@ def lib():
         L.ovf_score_lstm.argtypes = [vp, vp, vp, i64, i32, vp]
         L.ovf_argmin.argtypes = [vp, vp, i64, i32, vp, vp]
         L.ovf_greedy.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+        L.ovf_beam.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.ovf_num_threads.restype = i32
         _lib = L
     return _lib
@@ -188,6 +189,22 @@ def greedy(stages, space, model=None, weights=None, vfun=None, first=0, last=Non
                           first, last, _p(forced), _p(cids), _p(values), _p(top2), _p(st), _p(ne))
     _check(rc)
     return dict(cids=cids, values=values, top2=top2, states=st, n_evals=int(ne[0]))
+
+
+def beam(stages, space, width, model=None, weights=None, vfun=None):
+    """Beam search of the given width guided by V.  Returns dict(cids [width][S],
+    values [width][S], n_beams, n_evals); width = 1 is the greedy scan."""
+    stages = _i32(stages, (-1, 16)); space = _i32(space)
+    S = len(stages)
+    cids = np.full((width, S), -1, np.int32); values = np.full((width, S), np.inf, np.float32)
+    nb = np.zeros(1, np.int32); ne = np.zeros(1, np.int64)
+    cb = VFUN(vfun) if vfun is not None else None
+    if model is not None:
+        model = _i32(model); weights = np.ascontiguousarray(weights, np.float32)
+    _check(lib().ovf_beam(_p(stages), S, _p(space), _p(model), _p(weights),
+                          C.cast(cb, C.c_void_p) if cb is not None else None, None, width,
+                          _p(cids), _p(values), _p(nb), _p(ne)))
+    return dict(cids=cids, values=values, n_beams=int(nb[0]), n_evals=int(ne[0]))
 
 
 def num_threads():

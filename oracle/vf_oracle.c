@@ -774,6 +774,102 @@ int ovf_greedy(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_mo
   return rc;
 }
 
+/* ------------------------------------------------------------ beam search */
+
+typedef struct { float v; int32_t beam; int32_t cid; } beam_item;
+
+static int beam_item_less(const void *pa, const void *pb) {
+  const beam_item *a = (const beam_item *)pa, *b = (const beam_item *)pb;
+  if (a->v < b->v) return -1;
+  if (a->v > b->v) return 1;
+  if (a->beam != b->beam) return a->beam < b->beam ? -1 : 1;
+  if (a->cid != b->cid) return a->cid < b->cid ? -1 : 1;
+  return 0;
+}
+
+/* Beam search guided by V (Sections 3.1 and 4.1 use "a standard beam search" next to
+ * the greedy scan): keep the `width` best partial schedules per layer instead of one.
+ * Layer by layer, every kept partial schedule is extended by every valid candidate of
+ * the next layer, each extension is scored by V, and the `width` smallest scores
+ * survive (ties: lower parent index, then lower candidate id; +inf and NaN never
+ * survive).  width = 1 is Algorithm 1.  cids / values are [width][S] (value of the
+ * state after each layer); rows are ordered by the score of the last layer reached;
+ * unused rows and layers are -1 / +inf.  *n_beams = surviving schedules at the end. */
+int ovf_beam(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_model *m,
+             const float *weights, ovf_vfun vfun, void *user, int width, int32_t *cids,
+             float *values, int32_t *n_beams, int64_t *n_evals) {
+  if (!space_ok(sp) || !pipeline_ok(stages, S) || width < 1) return OVF_EINVAL;
+  if (!vfun && (!mlp_ok(m) || m->dims[0] != sp->F)) return OVF_EINVAL;
+  const int64_t M = ovf_dense_count(sp), Mp = ovf_padded_count(sp);
+  const int F = sp->F;
+  int32_t *cur = (int32_t *)malloc(sizeof(int32_t) * (size_t)width * S);
+  float *curv = (float *)malloc(sizeof(float) * (size_t)width * S);
+  int32_t *nxt = (int32_t *)malloc(sizeof(int32_t) * (size_t)width * S);
+  float *nxtv = (float *)malloc(sizeof(float) * (size_t)width * S);
+  beam_item *items = (beam_item *)malloc(sizeof(beam_item) * (size_t)width * (size_t)M);
+  int32_t *feat = (int32_t *)malloc(sizeof(int32_t) * (size_t)F * (size_t)Mp);
+  float *sc = (float *)malloc(sizeof(float) * (size_t)M);
+  if (!cur || !curv || !nxt || !nxtv || !items || !feat || !sc) {
+    free(cur); free(curv); free(nxt); free(nxtv); free(items); free(feat); free(sc);
+    return OVF_ENOMEM;
+  }
+  for (size_t k = 0; k < (size_t)width * S; ++k) { cur[k] = -1; curv[k] = INFINITY; }
+  int live = 1; /* the empty schedule s_0 */
+  int64_t evals = 0;
+  int rc = OVF_OK;
+  for (int i = 0; i < S && live > 0 && rc == OVF_OK; ++i) {
+    size_t n_items = 0;
+    for (int b = 0; b < live && rc == OVF_OK; ++b) {
+      rc = ovf_featurize(stages, S, sp, cur + (size_t)b * S, i, feat);
+      if (rc != OVF_OK) break;
+      if (vfun) {
+        for (int64_t cid = 0; cid < M; ++cid) {
+          int32_t core[64];
+          for (int k = 0; k < 64; ++k) core[k] = feat[(size_t)k * Mp + cid];
+          sc[cid] = core[16] ? (float)vfun(user, i, (int32_t)cid, core) : INFINITY;
+        }
+      } else {
+        rc = ovf_score_mlp(m, weights, feat, Mp, M, sc);
+        if (rc != OVF_OK) break;
+      }
+      for (int64_t cid = 0; cid < M; ++cid) {
+        if (!feat[(size_t)16 * Mp + cid]) continue;
+        ++evals;
+        if (sc[cid] < INFINITY) { /* false for NaN too */
+          items[n_items].v = sc[cid]; items[n_items].beam = b; items[n_items].cid = (int32_t)cid;
+          ++n_items;
+        }
+      }
+    }
+    if (rc != OVF_OK) break;
+    qsort(items, n_items, sizeof(beam_item), beam_item_less);
+    int keep = n_items < (size_t)width ? (int)n_items : width;
+    for (size_t k = 0; k < (size_t)width * S; ++k) { nxt[k] = -1; nxtv[k] = INFINITY; }
+    for (int j = 0; j < keep; ++j) {
+      const beam_item *it = &items[j];
+      memcpy(nxt + (size_t)j * S, cur + (size_t)it->beam * S, sizeof(int32_t) * (size_t)i);
+      memcpy(nxtv + (size_t)j * S, curv + (size_t)it->beam * S, sizeof(float) * (size_t)i);
+      nxt[(size_t)j * S + i] = it->cid;
+      nxtv[(size_t)j * S + i] = it->v;
+    }
+    if (keep == 0) {
+      /* nothing survives: the schedules found so far end here, in their order */
+      break;
+    }
+    int32_t *t1 = cur; cur = nxt; nxt = t1;
+    float *t2 = curv; curv = nxtv; nxtv = t2;
+    live = keep;
+  }
+  if (rc == OVF_OK) {
+    memcpy(cids, cur, sizeof(int32_t) * (size_t)width * S);
+    memcpy(values, curv, sizeof(float) * (size_t)width * S);
+    if (n_beams) *n_beams = live;
+    if (n_evals) *n_evals = evals;
+  }
+  free(cur); free(curv); free(nxt); free(nxtv); free(items); free(feat); free(sc);
+  return rc;
+}
+
 int ovf_num_threads(void) {
   int n = 1;
 #ifdef _OPENMP
