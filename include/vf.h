@@ -177,6 +177,21 @@ int vf_argmin_step(vf_ctx *ctx, int stage, int commit, int32_t *best_cid_dev, fl
 int vf_greedy_schedule(vf_ctx *ctx, int first_stage, int last_stage, vf_state *out_states_dev,
                        int32_t *out_cids_dev, float *out_values_dev);
 
+/* Beam search guided by V (Secs. 3.1 and 4.1 use a standard beam search next to the
+ * greedy scan; Algorithm 2 completes prefixes with it).  The context's `batch` problems
+ * are the beam slots of ONE network: every slot must hold the same pipeline (else
+ * VF_EINVAL) and the beam width is `batch`.  Starts from problem 0's current schedule
+ * (first_stage == vf_n_scheduled(); after vf_reset_state that is s_0); the other slots'
+ * schedules are discarded.  Per layer every surviving partial schedule is extended by
+ * every valid candidate, all extensions are scored, and the `batch` smallest scores
+ * survive, ordered by (score, parent slot, candidate id); +inf and NaN never survive.
+ * If a layer has no survivor the schedules found so far are kept and end there.
+ * Outputs as vf_greedy_schedule, row j = j-th best schedule; unused rows are zero
+ * states, -1, +inf.  n_beams_dev[1] (nullable) = number of schedules found.  Width 1
+ * takes the same decisions as vf_greedy_schedule. */
+int vf_beam_search(vf_ctx *ctx, int first_stage, int last_stage, vf_state *out_states_dev,
+                   int32_t *out_cids_dev, float *out_values_dev, int32_t *n_beams_dev);
+
 /* ---- diagnostics ---------------------------------------------------------- */
 
 /* Static description of an error code. */

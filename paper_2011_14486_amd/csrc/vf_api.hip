@@ -1,5 +1,7 @@
 // C ABI of libvf: argument checking, context tables, and the per-layer loop of
 // Algorithm 1 as a sequence of kernel launches on the caller's stream.
+#include <string.h>
+
 #include <new>
 #include <vector>
 
@@ -87,6 +89,14 @@ void free_pipeline(vf_ctx *c) {
   c->d_vals = nullptr;
   c->d_decpack = nullptr;
   c->dec_stage = -1;
+  void *alt[] = {c->d_alt_states, c->d_alt_cf, c->d_alt_prefix, c->d_alt_cids, c->d_alt_vals, c->d_alt_alive,
+                 c->d_sel_val,    c->d_sel_idx, c->d_sel_n};
+  for (void *p : alt)
+    if (p) (void)hipFree(p);
+  c->d_alt_states = c->d_alt_cf = c->d_alt_prefix = c->d_alt_cids = c->d_alt_alive = nullptr;
+  c->d_alt_vals = nullptr;
+  c->d_sel_val = nullptr;
+  c->d_sel_idx = c->d_sel_n = nullptr;
   c->has_pipeline = false;
   c->S = c->B = c->n_sched = 0;
 }
@@ -181,7 +191,8 @@ void vf_destroy(vf_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   free_pipeline(c);
   vfk_free_model(c);
-  void *ps[] = {c->d_space, c->d_err, c->d_feat, c->d_act[0], c->d_act[1], c->d_pval, c->d_pidx};
+  void *ps[] = {c->d_space, c->d_err,  c->d_feat,   c->d_act[0], c->d_act[1],
+                c->d_pval,  c->d_pidx, c->d_scores, c->d_tk_val, c->d_tk_idx};
   for (void *p : ps)
     if (p) (void)hipFree(p);
   if (c->ev0) (void)hipEventDestroy(c->ev0);
@@ -234,6 +245,8 @@ int vf_set_pipeline(vf_ctx *c, const vf_stage *st, int S, int B) {
     free_pipeline(c);
     return rc;
   }
+  c->h_stages.assign(st, st + n);
+  c->beam_checked = false;
   VF_HIP(c, hipMemcpyAsync(c->d_stages, st, n * sizeof(vf_stage), hipMemcpyHostToDevice, c->stream));
   VF_HIP(c, hipStreamSynchronize(c->stream));  // the host array may go away after return
   rc = vfk_setup_tables(c);
@@ -379,6 +392,39 @@ int vf_greedy_schedule(vf_ctx *c, int first, int last, vf_state *out_states, int
     VF_HIP(c, hipMemcpyAsync(out_states, c->d_states, n * sizeof(vf_state), hipMemcpyDeviceToDevice, c->stream));
   if (out_cids) VF_HIP(c, hipMemcpyAsync(out_cids, c->d_cids, n * 4, hipMemcpyDeviceToDevice, c->stream));
   if (out_vals) VF_HIP(c, hipMemcpyAsync(out_vals, c->d_vals, n * 4, hipMemcpyDeviceToDevice, c->stream));
+  return VF_OK;
+}
+
+int vf_beam_search(vf_ctx *c, int first, int last, vf_state *out_states, int32_t *out_cids, float *out_vals,
+                   int32_t *n_beams) {
+  if (!c) return VF_EINVAL;
+  if (!c->has_pipeline || !c->has_model) return VF_ESTATE;
+  if (c->model.kind != VF_MLP || c->model.dims[0] != c->space.F) return VF_EINVAL;
+  if (first < 0 || last >= c->S || first > last + 1) return VF_EINVAL;
+  if (first != c->n_sched) return VF_ESTATE;
+  if ((int64_t)c->B * c->Mpad >= ((int64_t)1 << 31)) return VF_EINVAL;
+  if (!c->beam_checked) {
+    for (int b = 1; b < c->B; ++b)
+      if (memcmp(c->h_stages.data(), c->h_stages.data() + (size_t)b * c->S, sizeof(vf_stage) * (size_t)c->S) != 0)
+        return VF_EINVAL;  // the slots of a beam search hold one and the same network
+    c->beam_checked = true;
+  }
+  DeviceGuard g(c->device);
+  int rc = vfk_beam_init(c, first);
+  if (rc != VF_OK) return rc;
+  for (int i = first; i <= last; ++i) {
+    rc = vfk_step_scores(c, i);
+    if (rc != VF_OK) return rc;
+    rc = vfk_beam_select_commit(c, i);
+    if (rc != VF_OK) return rc;
+    c->n_sched = i + 1;
+  }
+  const size_t n = (size_t)c->B * c->S;
+  if (out_states)
+    VF_HIP(c, hipMemcpyAsync(out_states, c->d_states, n * sizeof(vf_state), hipMemcpyDeviceToDevice, c->stream));
+  if (out_cids) VF_HIP(c, hipMemcpyAsync(out_cids, c->d_cids, n * 4, hipMemcpyDeviceToDevice, c->stream));
+  if (out_vals) VF_HIP(c, hipMemcpyAsync(out_vals, c->d_vals, n * 4, hipMemcpyDeviceToDevice, c->stream));
+  if (n_beams) VF_HIP(c, hipMemcpyAsync(n_beams, c->d_sel_n + 1, 4, hipMemcpyDeviceToDevice, c->stream));
   return VF_OK;
 }
 

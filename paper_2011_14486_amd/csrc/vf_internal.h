@@ -59,6 +59,18 @@ struct vf_ctx {
   uint32_t *d_decpack = nullptr; // [B][VF_DECPACK_DWORDS] decision context of stage dec_stage
   int dec_stage = -1;            // stage d_decpack was built for, -1: none
 
+  // beam search: a second set of state tables (the survivors of a layer are written
+  // there, then the two sets swap), masked scores, selection scratch
+  int32_t *d_alt_states = nullptr, *d_alt_cf = nullptr, *d_alt_prefix = nullptr, *d_alt_cids = nullptr;
+  float *d_alt_vals = nullptr;
+  int32_t *d_alt_alive = nullptr;
+  float *d_scores = nullptr; size_t score_elems = 0;   // [B][Mpad]
+  float *d_tk_val = nullptr; int32_t *d_tk_idx = nullptr; size_t tk_elems = 0;  // chunk partials
+  float *d_sel_val = nullptr; int32_t *d_sel_idx = nullptr;  // [B] survivors (value, beam*Mpad+cid)
+  int32_t *d_sel_n = nullptr;    // [2]: survivors of this layer, live schedules so far
+  std::vector<vf_stage> h_stages;  // host copy of the stage records
+  bool beam_checked = false;       // all slots verified to hold the same pipeline
+
   vf_model model;
   vf_packed_model pm;
 
@@ -138,6 +150,12 @@ int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, i
 // MLPs of uniform hidden width whose input width is the space's F).
 bool vfk_can_fuse_step(const vf_ctx *c);
 int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out);
+// Scores of every candidate of `stage` for all problems into d_scores [B][Mpad]; invalid
+// candidates and padding columns get +inf.
+int vfk_step_scores(vf_ctx *c, int stage);
+// beam search pieces (vf_sched.hip)
+int vfk_beam_init(vf_ctx *c, int first_stage);
+int vfk_beam_select_commit(vf_ctx *c, int stage);
 int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores, int *nparts_out);
 int vfk_argmin_groups(vf_ctx *c, int64_t M, int nparts, int parts_per_group, int ngroups,
                       int32_t *best_idx, float *best_val);

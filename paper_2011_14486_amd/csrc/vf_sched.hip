@@ -9,6 +9,8 @@
 // its anchor, the neighbour feature rows) is worked out once per workgroup and kept
 // in LDS; the per-candidate part is integer arithmetic saturating at 2^31-1
 // (Sec. 3.2: intrinsic and acquired features).
+#include <utility>
+
 #include "vf_internal.h"
 
 namespace {
@@ -192,6 +194,193 @@ __global__ __launch_bounds__(64) void k_commit(Tables t, int stage, int nparts, 
   }
 }
 
+// ------------------------------------------------------------ beam search
+//
+// Secs. 3.1 and 4.1 run "a standard beam search" guided by V next to the greedy scan.
+// The B problems of the context are the beam slots of one network.  Per layer: every
+// live slot's candidates are scored (masked scores [B][Mpad]); the B smallest of all
+// B*M scores survive, ordered by (score, parent slot, candidate id); survivor j copies
+// its parent's schedule into slot j of the other table set and commits its candidate.
+
+struct AltTables {
+  int32_t *states, *cf, *prefix, *cids, *alive;
+  float *vals;
+};
+
+__device__ __forceinline__ void take_min_u(float &v, int32_t &c, float ov, int32_t oc) {
+  if (oc >= 0 && (ov < v || (ov == v && (c < 0 || oc < c)))) { v = ov; c = oc; }
+}
+
+// block-wide first minimum of (v, c); every thread gets the result
+__device__ void block_min(float &v, int32_t &c, float *sv, int32_t *sc) {
+  for (int off = 32; off > 0; off >>= 1) {
+    float ov = __shfl_down(v, off);
+    int32_t oc = __shfl_down(c, off);
+    take_min_u(v, c, ov, oc);
+  }
+  const int w = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { sv[w] = v; sc[w] = c; }
+  __syncthreads();
+  v = sv[0]; c = sc[0];
+  for (int k = 1; k < nw; ++k) take_min_u(v, c, sv[k], sc[k]);
+}
+
+// The k smallest of one chunk of 2048 scores (flat index = slot * Mpad + candidate id).
+__global__ __launch_bounds__(256) void k_topk_chunks(const float *scores, uint32_t M, uint32_t Mpad, uint32_t total,
+                                                     int k, float *out_val, int32_t *out_idx) {
+  __shared__ float sv[4];
+  __shared__ int32_t sc[4];
+  const uint32_t base = blockIdx.x * 2048u;
+  float v[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t i = base + threadIdx.x + e * 256u;
+    float s = __builtin_inff();
+    if (i < total && (i % Mpad) < M) {
+      const float t = scores[i];
+      if (t < s) s = t;  // NaN and +inf never survive
+    }
+    v[e] = s;
+  }
+  for (int r = 0; r < k; ++r) {
+    float bv = __builtin_inff();
+    int32_t bi = -1;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (v[e] < bv) { bv = v[e]; bi = (int32_t)(base + threadIdx.x + e * 256u); }
+    // within a thread the scan above runs in increasing index order: first minimum
+    block_min(bv, bi, sv, sc);
+    if (threadIdx.x == 0) {
+      out_val[(size_t)blockIdx.x * k + r] = bv;
+      out_idx[(size_t)blockIdx.x * k + r] = bi;
+    }
+    if (bi >= 0) {
+      const uint32_t off = (uint32_t)bi - base;
+      if ((off & 255u) == threadIdx.x) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          if ((off >> 8) == (uint32_t)e) v[e] = __builtin_inff();
+      }
+    }
+  }
+}
+
+// The k smallest over all chunk results -> the layer's survivors, in order.
+__global__ __launch_bounds__(256) void k_topk_merge(float *val, const int32_t *idx, int n, int k, float *sel_val,
+                                                    int32_t *sel_idx, int32_t *sel_n) {
+  __shared__ float sv[4];
+  __shared__ int32_t sc[4];
+  int found = 0;
+  for (int r = 0; r < k; ++r) {
+    float bv = __builtin_inff();
+    int32_t bi = -1, bpos = -1;
+    for (int i = threadIdx.x; i < n; i += 256) {
+      const float t = reinterpret_cast<volatile float *>(val)[i];  // retired entries must be seen
+      const int32_t id = idx[i];
+      if (id >= 0 && (t < bv || (t == bv && id < bi))) { bv = t; bi = id; bpos = i; }
+    }
+    float gv = bv;
+    int32_t gi = bi;
+    block_min(gv, gi, sv, sc);
+    if (gi >= 0 && gi == bi && bpos >= 0) reinterpret_cast<volatile float *>(val)[bpos] = __builtin_inff();  // owner retires it
+    if (threadIdx.x == 0) {
+      sel_val[r] = gv;
+      sel_idx[r] = gi;
+    }
+    if (gi >= 0) ++found;
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    sel_n[0] = found;
+    if (found > 0) sel_n[1] = found;
+  }
+}
+
+// First layer of a beam search: only slot 0 (the context's current schedule of
+// problem 0) is live; the other slots and the whole second table set are cleared.
+__global__ __launch_bounds__(256) void k_beam_init(Tables t, AltTables alt, int B, int32_t *sel_n) {
+  const int S = t.S;
+  const size_t i0 = (size_t)blockIdx.x * blockDim.x + threadIdx.x, step = (size_t)gridDim.x * blockDim.x;
+  const size_t n = (size_t)B * S;
+  for (size_t i = i0; i < n * 64; i += step) { if (i >= (size_t)S * 64) t.cf[i] = 0; alt.cf[i] = 0; }
+  for (size_t i = i0; i < n * 16; i += step) { if (i >= (size_t)S * 16) t.states[i] = 0; alt.states[i] = 0; }
+  for (size_t i = i0; i < (size_t)B * (S + 1) * 2; i += step) { if (i >= (size_t)(S + 1) * 2) t.prefix[i] = 0; alt.prefix[i] = 0; }
+  for (size_t i = i0; i < n; i += step) {
+    if (i >= (size_t)S) { t.cids[i] = -1; t.vals[i] = __builtin_inff(); }
+    alt.cids[i] = -1; alt.vals[i] = __builtin_inff();
+  }
+  for (size_t i = i0; i < (size_t)B; i += step) { t.alive[i] = (i == 0) ? t.alive[0] : 0; alt.alive[i] = 0; }
+  if (i0 == 0) { sel_n[0] = 0; sel_n[1] = 1; }
+}
+
+// Survivor j of the layer: copy the parent's schedule, commit the candidate, build the
+// next layer's decision context.  Slots past the survivors are cleared.  If nothing
+// survived the schedules end: every slot is carried over unchanged and marked dead.
+__global__ __launch_bounds__(64) void k_beam_commit(Tables t, AltTables nw, int stage, uint32_t M, uint32_t Mpad,
+                                                    const float *sel_val, const int32_t *sel_idx, const int32_t *sel_n,
+                                                    uint32_t *decpack_next) {
+  __shared__ DecPack pk;
+  const int j = blockIdx.x, S = t.S, lane = threadIdx.x;
+  const int nsel = sel_n[0];
+  const size_t dst = (size_t)j * S;
+  int src_slot = -1;
+  int32_t cid = -1;
+  if (nsel == 0) src_slot = j;
+  else if (j < nsel) { src_slot = sel_idx[j] / (int32_t)Mpad; cid = sel_idx[j] % (int32_t)Mpad; }
+  const int rows = nsel == 0 ? S : stage;  // committed rows to carry over
+  if (src_slot >= 0) {
+    const size_t src = (size_t)src_slot * S;
+    for (int i = lane; i < rows * 64; i += 64) nw.cf[dst * 64 + i] = t.cf[src * 64 + i];
+    for (int i = lane; i < rows * 16; i += 64) nw.states[dst * 16 + i] = t.states[src * 16 + i];
+    for (int i = lane; i < rows; i += 64) { nw.cids[dst + i] = t.cids[src + i]; nw.vals[dst + i] = t.vals[src + i]; }
+    for (int i = lane; i < (S + 1) * 2; i += 64)
+      nw.prefix[(size_t)j * (S + 1) * 2 + i] = (nsel == 0 || i < (stage + 1) * 2) ? t.prefix[(size_t)src_slot * (S + 1) * 2 + i] : 0;
+  } else {
+    for (int i = lane; i < (stage + 1) * 64; i += 64) nw.cf[dst * 64 + i] = 0;
+    for (int i = lane; i < (stage + 1) * 16; i += 64) nw.states[dst * 16 + i] = 0;
+    for (int i = lane; i <= stage; i += 64) { nw.cids[dst + i] = -1; nw.vals[dst + i] = __builtin_inff(); }
+    for (int i = lane; i < (S + 1) * 2; i += 64) nw.prefix[(size_t)j * (S + 1) * 2 + i] = 0;
+  }
+  if (cid >= 0) {
+    build_dec(pk.d, pk.sp, t, src_slot, stage);  // the parent's context, from the old tables
+    if (lane == 0) {
+      int32_t core[64];
+      uint32_t dec;
+      const bool ok = (uint32_t)cid < M && eval_candidate<true>(pk.d, pk.sp, (uint32_t)cid, dec, core);
+      const size_t row = dst + stage;
+      int32_t *pre = nw.prefix + ((size_t)j * (S + 1) + stage) * 2;
+      if (ok) {
+#pragma unroll
+        for (int k = 0; k < 64; ++k) nw.cf[row * 64 + k] = core[k];
+        int32_t *st = nw.states + row * 16;
+        st[0] = core[17]; st[1] = core[18]; st[2] = core[19];
+        st[3] = core[23]; st[4] = core[26]; st[5] = core[29]; st[6] = core[32]; st[7] = core[33];
+        st[8] = core[34]; st[9] = core[35]; st[10] = core[36];
+        st[11] = core[37];
+        st[12] = core[20]; st[13] = core[21]; st[14] = core[22];
+        st[15] = 1;
+        nw.cids[row] = cid;
+        nw.vals[row] = sel_val[j];
+        pre[2] = sadd((uint32_t)pre[0], (uint32_t)core[40]);
+        pre[3] = sadd((uint32_t)pre[1], (uint32_t)core[50]);
+      } else {
+        t.err[0] = 1;  // cannot happen: only valid candidates have finite scores
+      }
+      nw.alive[j] = ok ? 1 : 0;
+    }
+  } else if (lane == 0) {
+    nw.alive[j] = 0;
+  }
+  if (decpack_next && stage + 1 < S) {
+    __threadfence();
+    __syncthreads();
+    Tables tn = t;
+    tn.states = nw.states; tn.cf = nw.cf; tn.prefix = nw.prefix; tn.cids = nw.cids; tn.alive = nw.alive; tn.vals = nw.vals;
+    write_decpack(pk, tn, j, stage + 1, decpack_next);
+  }
+}
+
 }  // namespace
 
 int vfk_setup_tables(vf_ctx *c) {
@@ -254,5 +443,78 @@ int vfk_prepare(vf_ctx *c, int stage) {
   hipLaunchKernelGGL(k_prepare, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), stage, c->d_decpack);
   VF_HIP(c, hipGetLastError());
   c->dec_stage = stage;
+  return VF_OK;
+}
+
+static int beam_alloc(vf_ctx *c) {
+  if (c->d_alt_states) return VF_OK;
+  const size_t n = (size_t)c->S * c->B;
+  struct { void **p; size_t bytes; } want[] = {
+      {(void **)&c->d_alt_states, n * 16 * 4}, {(void **)&c->d_alt_cf, n * 64 * 4},
+      {(void **)&c->d_alt_prefix, (size_t)c->B * (c->S + 1) * 2 * 4}, {(void **)&c->d_alt_cids, n * 4},
+      {(void **)&c->d_alt_vals, n * 4}, {(void **)&c->d_alt_alive, (size_t)c->B * 4},
+      {(void **)&c->d_sel_val, (size_t)c->B * 4}, {(void **)&c->d_sel_idx, (size_t)c->B * 4},
+      {(void **)&c->d_sel_n, 2 * 4}};
+  for (auto &w : want) {
+    if (*w.p) continue;
+    if (hipMalloc(w.p, w.bytes ? w.bytes : 4) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
+  }
+  return VF_OK;
+}
+
+static AltTables alt_of(const vf_ctx *c) {
+  AltTables a;
+  a.states = c->d_alt_states; a.cf = c->d_alt_cf; a.prefix = c->d_alt_prefix; a.cids = c->d_alt_cids;
+  a.alive = c->d_alt_alive; a.vals = c->d_alt_vals;
+  return a;
+}
+
+int vfk_beam_init(vf_ctx *c, int first_stage) {
+  (void)first_stage;
+  int rc = beam_alloc(c);
+  if (rc != VF_OK) return rc;
+  size_t n = (size_t)c->B * c->S * 64;
+  int blocks = (int)((n + 255) / 256);
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(k_beam_init, dim3(blocks), dim3(256), 0, c->stream, tables_of(c), alt_of(c), c->B, c->d_sel_n);
+  VF_HIP(c, hipGetLastError());
+  c->dec_stage = -1;
+  return VF_OK;
+}
+
+// scores of the layer are in d_scores: select the survivors, commit them into the other
+// table set, swap the sets
+int vfk_beam_select_commit(vf_ctx *c, int stage) {
+  const uint32_t total = (uint32_t)((size_t)c->B * c->Mpad);
+  const int nchunks = (int)((total + 2047u) / 2048u), k = c->B;
+  const size_t want = (size_t)nchunks * k;
+  if (want > c->tk_elems) {
+    if (c->d_tk_val) { VF_HIP(c, hipStreamSynchronize(c->stream)); (void)hipFree(c->d_tk_val); (void)hipFree(c->d_tk_idx); }
+    c->d_tk_val = nullptr; c->d_tk_idx = nullptr; c->tk_elems = 0;
+    if (hipMalloc((void **)&c->d_tk_val, want * 4) != hipSuccess || hipMalloc((void **)&c->d_tk_idx, want * 4) != hipSuccess) {
+      (void)hipGetLastError();
+      return VF_ENOMEM;
+    }
+    c->tk_elems = want;
+  }
+  hipLaunchKernelGGL(k_topk_chunks, dim3(nchunks), dim3(256), 0, c->stream, c->d_scores, (uint32_t)c->M,
+                     (uint32_t)c->Mpad, total, k, c->d_tk_val, c->d_tk_idx);
+  VF_HIP(c, hipGetLastError());
+  hipLaunchKernelGGL(k_topk_merge, dim3(1), dim3(256), 0, c->stream, c->d_tk_val, c->d_tk_idx, (int)want, k,
+                     c->d_sel_val, c->d_sel_idx, c->d_sel_n);
+  VF_HIP(c, hipGetLastError());
+  {
+    vf_prof_scope prof(c, VF_PROF_COMMIT);
+    hipLaunchKernelGGL(k_beam_commit, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), alt_of(c), stage,
+                       (uint32_t)c->M, (uint32_t)c->Mpad, c->d_sel_val, c->d_sel_idx, c->d_sel_n, c->d_decpack);
+    VF_HIP(c, hipGetLastError());
+  }
+  std::swap(c->d_states, c->d_alt_states);
+  std::swap(c->d_cf, c->d_alt_cf);
+  std::swap(c->d_prefix, c->d_alt_prefix);
+  std::swap(c->d_cids, c->d_alt_cids);
+  std::swap(c->d_vals, c->d_alt_vals);
+  std::swap(c->d_alive, c->d_alt_alive);
+  c->dec_stage = stage + 1 < c->S ? stage + 1 : -1;
   return VF_OK;
 }

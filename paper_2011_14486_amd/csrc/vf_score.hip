@@ -669,7 +669,9 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       float s = auxs[md.bias_off[md.L - 1]];
 #pragma unroll
       for (int g = 0; g < 8; ++g) s += red[g * NC + tid];
-      if (scores && (n0 + tid) < M) scores[(size_t)p * ld_scores + n0 + tid] = s;
+      // scores of a generated tile are masked: invalid candidates and padding read +inf
+      if (scores && (GEN ? (n0 + tid) < ld_scores : (n0 + tid) < M))
+        scores[(size_t)p * ld_scores + n0 + tid] = (GEN && okf[tid] == 0) ? __builtin_inff() : s;
       if (okf[tid] != 0 && s < v) { v = s; c = (int32_t)(n0 + tid); }
       wave_min(v, c);
     }
@@ -1052,6 +1054,40 @@ bool vfk_can_fuse_step(const vf_ctx *c) {
 
 int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out) {
   return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, nparts_out, stage);
+}
+
+namespace {
+// masks the scores of invalid candidates (validity row of the feature matrix) and of
+// the padding columns with +inf
+__global__ __launch_bounds__(256) void k_mask_scores(float *scores, const int32_t *feat, int64_t feat_stride,
+                                                     int64_t M, int64_t Mpad) {
+  const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int p = blockIdx.y;
+  if (n >= Mpad) return;
+  const bool ok = n < M && feat[(size_t)p * feat_stride + (size_t)16 * Mpad + n] != 0;
+  if (!ok) scores[(size_t)p * Mpad + n] = __builtin_inff();
+}
+}  // namespace
+
+int vfk_step_scores(vf_ctx *c, int stage) {
+  const size_t want = (size_t)c->B * c->Mpad;
+  int rc = grow(c, c->d_scores, c->score_elems, want);
+  if (rc != VF_OK) return rc;
+  int nparts = 0;
+  if (vfk_can_fuse_step(c)) return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, stage);
+  // general models: materialise the features, score, mask
+  const size_t fwant = (size_t)c->B * c->space.F * c->Mpad;
+  rc = grow(c, c->d_feat, c->feat_elems, fwant);
+  if (rc != VF_OK) return rc;
+  rc = vfk_featurize(c, stage, c->d_feat);
+  if (rc != VF_OK) return rc;
+  const int64_t fstride = (int64_t)c->space.F * c->Mpad;
+  rc = score_mlp(c, c->d_feat, fstride, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, -1);
+  if (rc != VF_OK) return rc;
+  hipLaunchKernelGGL(k_mask_scores, dim3((unsigned)((c->Mpad + 255) / 256), (unsigned)c->B), dim3(256), 0, c->stream,
+                     c->d_scores, c->d_feat, fstride, c->M, c->Mpad);
+  VF_HIP(c, hipGetLastError());
+  return VF_OK;
 }
 
 static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
