@@ -226,72 +226,55 @@ __device__ void block_min(float &v, int32_t &c, float *sv, int32_t *sc) {
   for (int k = 1; k < nw; ++k) take_min_u(v, c, sv[k], sc[k]);
 }
 
-// The k smallest of one chunk of 2048 scores (flat index = slot * Mpad + candidate id).
-__global__ __launch_bounds__(256) void k_topk_chunks(const float *scores, uint32_t M, uint32_t Mpad, uint32_t total,
-                                                     int k, float *out_val, int32_t *out_idx) {
+// One selection pass: every block reduces 2048 (value, index) pairs to its k smallest,
+// ordered by (value, index).  First pass (idx_in == nullptr): values are the masked
+// scores, index = slot * Mpad + candidate id, columns >= M are skipped.  Later passes
+// read the pairs of the pass before.  The last pass (one block) also counts.
+__global__ __launch_bounds__(256) void k_topk_pass(const float *val_in, const int32_t *idx_in, uint32_t n,
+                                                   uint32_t M, uint32_t Mpad, int k, float *val_out,
+                                                   int32_t *idx_out, int32_t *sel_n) {
   __shared__ float sv[4];
   __shared__ int32_t sc[4];
   const uint32_t base = blockIdx.x * 2048u;
   float v[8];
+  int32_t id[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     const uint32_t i = base + threadIdx.x + e * 256u;
     float s = __builtin_inff();
-    if (i < total && (i % Mpad) < M) {
-      const float t = scores[i];
-      if (t < s) s = t;  // NaN and +inf never survive
+    int32_t ix = -1;
+    if (i < n) {
+      if (idx_in) {
+        ix = idx_in[i];
+        if (ix >= 0) s = val_in[i];
+      } else if ((i % Mpad) < M) {
+        const float t = val_in[i];
+        if (t < s) { s = t; ix = (int32_t)i; }  // NaN and +inf never survive
+      }
     }
     v[e] = s;
+    id[e] = ix;
   }
+  int found = 0;
   for (int r = 0; r < k; ++r) {
     float bv = __builtin_inff();
     int32_t bi = -1;
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-      if (v[e] < bv) { bv = v[e]; bi = (int32_t)(base + threadIdx.x + e * 256u); }
-    // within a thread the scan above runs in increasing index order: first minimum
+      if (id[e] >= 0 && (v[e] < bv || (v[e] == bv && (bi < 0 || id[e] < bi)))) { bv = v[e]; bi = id[e]; }
     block_min(bv, bi, sv, sc);
     if (threadIdx.x == 0) {
-      out_val[(size_t)blockIdx.x * k + r] = bv;
-      out_idx[(size_t)blockIdx.x * k + r] = bi;
+      val_out[(size_t)blockIdx.x * k + r] = bv;
+      idx_out[(size_t)blockIdx.x * k + r] = bi;
     }
     if (bi >= 0) {
-      const uint32_t off = (uint32_t)bi - base;
-      if ((off & 255u) == threadIdx.x) {
+      ++found;
 #pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if ((off >> 8) == (uint32_t)e) v[e] = __builtin_inff();
-      }
+      for (int e = 0; e < 8; ++e)
+        if (id[e] == bi) id[e] = -1;  // indices are unique: only the owner retires it
     }
   }
-}
-
-// The k smallest over all chunk results -> the layer's survivors, in order.
-__global__ __launch_bounds__(256) void k_topk_merge(float *val, const int32_t *idx, int n, int k, float *sel_val,
-                                                    int32_t *sel_idx, int32_t *sel_n) {
-  __shared__ float sv[4];
-  __shared__ int32_t sc[4];
-  int found = 0;
-  for (int r = 0; r < k; ++r) {
-    float bv = __builtin_inff();
-    int32_t bi = -1, bpos = -1;
-    for (int i = threadIdx.x; i < n; i += 256) {
-      const float t = reinterpret_cast<volatile float *>(val)[i];  // retired entries must be seen
-      const int32_t id = idx[i];
-      if (id >= 0 && (t < bv || (t == bv && id < bi))) { bv = t; bi = id; bpos = i; }
-    }
-    float gv = bv;
-    int32_t gi = bi;
-    block_min(gv, gi, sv, sc);
-    if (gi >= 0 && gi == bi && bpos >= 0) reinterpret_cast<volatile float *>(val)[bpos] = __builtin_inff();  // owner retires it
-    if (threadIdx.x == 0) {
-      sel_val[r] = gv;
-      sel_idx[r] = gi;
-    }
-    if (gi >= 0) ++found;
-    __syncthreads();
-  }
-  if (threadIdx.x == 0) {
+  if (sel_n && threadIdx.x == 0) {
     sel_n[0] = found;
     if (found > 0) sel_n[1] = found;
   }
@@ -491,18 +474,31 @@ int vfk_beam_select_commit(vf_ctx *c, int stage) {
   if (want > c->tk_elems) {
     if (c->d_tk_val) { VF_HIP(c, hipStreamSynchronize(c->stream)); (void)hipFree(c->d_tk_val); (void)hipFree(c->d_tk_idx); }
     c->d_tk_val = nullptr; c->d_tk_idx = nullptr; c->tk_elems = 0;
-    if (hipMalloc((void **)&c->d_tk_val, want * 4) != hipSuccess || hipMalloc((void **)&c->d_tk_idx, want * 4) != hipSuccess) {
+    if (hipMalloc((void **)&c->d_tk_val, want * 8) != hipSuccess || hipMalloc((void **)&c->d_tk_idx, want * 8) != hipSuccess) {
       (void)hipGetLastError();
       return VF_ENOMEM;
     }
     c->tk_elems = want;
   }
-  hipLaunchKernelGGL(k_topk_chunks, dim3(nchunks), dim3(256), 0, c->stream, c->d_scores, (uint32_t)c->M,
-                     (uint32_t)c->Mpad, total, k, c->d_tk_val, c->d_tk_idx);
-  VF_HIP(c, hipGetLastError());
-  hipLaunchKernelGGL(k_topk_merge, dim3(1), dim3(256), 0, c->stream, c->d_tk_val, c->d_tk_idx, (int)want, k,
-                     c->d_sel_val, c->d_sel_idx, c->d_sel_n);
-  VF_HIP(c, hipGetLastError());
+  // passes of 2048 -> k until one block is left; buffers alternate between the two halves
+  float *va = c->d_tk_val, *vb = c->d_tk_val + want;
+  int32_t *ia = c->d_tk_idx, *ib = c->d_tk_idx + want;
+  const float *vin = c->d_scores;
+  const int32_t *iin = nullptr;
+  uint32_t n = total;
+  for (;;) {
+    const int blocks = (int)((n + 2047u) / 2048u);
+    const bool last_pass = blocks == 1;
+    hipLaunchKernelGGL(k_topk_pass, dim3(blocks), dim3(256), 0, c->stream, vin, iin, n, (uint32_t)c->M,
+                       (uint32_t)c->Mpad, k, last_pass ? c->d_sel_val : va, last_pass ? c->d_sel_idx : ia,
+                       last_pass ? c->d_sel_n : (int32_t *)nullptr);
+    VF_HIP(c, hipGetLastError());
+    if (last_pass) break;
+    vin = va; iin = ia;
+    n = (uint32_t)blocks * (uint32_t)k;
+    std::swap(va, vb);
+    std::swap(ia, ib);
+  }
   {
     vf_prof_scope prof(c, VF_PROF_COMMIT);
     hipLaunchKernelGGL(k_beam_commit, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), alt_of(c), stage,

@@ -44,7 +44,7 @@ struct Dec {
 };
 
 // Intrinsic block of one stage record (schedule-invariant, Sec. 3.2).
-__device__ void intrinsic_of(const int32_t *w, int j, int S, int32_t *a) {
+[[maybe_unused]] __device__ void intrinsic_of(const int32_t *w, int j, int S, int32_t *a) {
   uint32_t kind = w[0], W = w[1], H = w[2], C = w[3], RC = w[4], KH = w[5], KW = w[6];
   uint32_t stride = w[7], eb = w[12];
   uint32_t R = smul(smul(RC, KH), KW);
@@ -284,7 +284,7 @@ struct DecPack {
 static_assert(sizeof(DecPack) == VF_DECPACK_DWORDS * 4, "DecPack size");
 
 // Builds the pack for (problem b, stage) in LDS and copies it to out[b].
-__device__ void write_decpack(DecPack &pk, const Tables &t, int b, int stage, uint32_t *out) {
+[[maybe_unused]] __device__ void write_decpack(DecPack &pk, const Tables &t, int b, int stage, uint32_t *out) {
   build_dec(pk.d, pk.sp, t, b, stage);
   for (int q = threadIdx.x; q < 96; q += blockDim.x)
     pk.nbh[q] = pack_bf16(plog2_dev(pk.d.nb[2 * q]), plog2_dev(pk.d.nb[2 * q + 1]));
