@@ -57,6 +57,10 @@ def lib():
         L.ovf_score_lstm.argtypes = [vp, vp, vp, i64, i32, vp]
         L.ovf_argmin.argtypes = [vp, vp, i64, i32, vp, vp]
         L.ovf_greedy.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, i32, vp, vp, vp, vp, vp, vp]
+        L.ovf_philox4x32_10.argtypes = [vp, vp, vp]
+        L.ovf_noise.restype = C.c_float
+        L.ovf_noise.argtypes = [C.c_uint64, i32, i32, i32]
+        L.ovf_rollouts.argtypes = [vp, i32, vp, vp, vp, C.c_float, C.c_uint64, i32, i32, vp, vp, vp, vp]
         L.ovf_beam.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.ovf_num_threads.restype = i32
         _lib = L
@@ -189,6 +193,30 @@ def greedy(stages, space, model=None, weights=None, vfun=None, first=0, last=Non
                           first, last, _p(forced), _p(cids), _p(values), _p(top2), _p(st), _p(ne))
     _check(rc)
     return dict(cids=cids, values=values, top2=top2, states=st, n_evals=int(ne[0]))
+
+
+def philox4x32_10(ctr, key):
+    c = np.asarray(ctr, np.uint32); k = np.asarray(key, np.uint32); out = np.zeros(4, np.uint32)
+    lib().ovf_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def noise(seed, rollout, stage, cid):
+    return float(lib().ovf_noise(seed, rollout, stage, cid))
+
+
+def rollouts(stages, space, model, weights, eps, seed, n_rollouts, first_rollout=0, forced=None):
+    """n_rollouts noisy greedy schedules.  Returns dict(cids, values, top2), each [n][S]."""
+    stages = _i32(stages, (-1, 16)); space = _i32(space); model = _i32(model)
+    weights = np.ascontiguousarray(weights, np.float32)
+    S = len(stages)
+    cids = np.full((n_rollouts, S), -1, np.int32)
+    values = np.full((n_rollouts, S), np.inf, np.float32); top2 = np.full((n_rollouts, S), np.inf, np.float32)
+    if forced is not None:
+        forced = _i32(forced, (n_rollouts, S))
+    _check(lib().ovf_rollouts(_p(stages), S, _p(space), _p(model), _p(weights), C.c_float(eps), seed,
+                              first_rollout, n_rollouts, _p(forced), _p(cids), _p(values), _p(top2)))
+    return dict(cids=cids, values=values, top2=top2)
 
 
 def beam(stages, space, width, model=None, weights=None, vfun=None):

@@ -684,6 +684,33 @@ int ovf_argmin(const float *scores, const uint8_t *valid, int64_t M, int32_t gro
   return OVF_OK;
 }
 
+/* ------------------------------------------------------------------ noise */
+
+/* Philox4x32-10 counter-based generator (Salmon, Moraes, Dror, Shaw: "Parallel random
+ * numbers: as easy as 1, 2, 3", SC'11): ten rounds of two 32x32->64 multiplications
+ * and xors on a 128-bit counter, the 64-bit key bumped by the Weyl constants between
+ * rounds. */
+void ovf_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]) {
+  uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3], k0 = key[0], k1 = key[1];
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    uint64_t p0 = (uint64_t)0xD2511F53u * c0, p1 = (uint64_t)0xCD9E8D57u * c2;
+    uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0, n1 = (uint32_t)p1;
+    uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1, n3 = (uint32_t)p0;
+    c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+  }
+  out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Noise in [-1, 1) attached to (rollout, layer, candidate): the first Philox word of
+ * counter (cid, stage, rollout, 0) under key = seed, top 24 bits, as k * 2^-23 - 1. */
+float ovf_noise(uint64_t seed, int32_t rollout, int32_t stage, int32_t cid) {
+  uint32_t ctr[4] = { (uint32_t)cid, (uint32_t)stage, (uint32_t)rollout, 0u };
+  uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) }, out[4];
+  ovf_philox4x32_10(ctr, key, out);
+  return (float)(out[0] >> 8) * 0x1p-23f - 1.0f;
+}
+
 /* ----------------------------------------------------------------- greedy */
 
 /* Algorithm 1 over stages first..last with stages 0..first-1 already committed to
@@ -693,10 +720,10 @@ int ovf_argmin(const float *scores, const uint8_t *valid, int64_t M, int32_t gro
  * inside the tolerance margin); top2[i] receives the second smallest score.
  * On return cids/values/states hold s_1..s_n; a stage with no winner gets -1 / +inf
  * and ends the schedule.  n_evals counts V evaluations (Section 2: N*M, not M^N). */
-int ovf_greedy(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_model *m,
-               const float *weights, ovf_vfun vfun, void *user, int first, int last,
-               const int32_t *forced, int32_t *cids, float *values, float *top2,
-               ovf_state *states, int64_t *n_evals) {
+static int greedy_impl(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_model *m,
+                       const float *weights, ovf_vfun vfun, void *user, int first, int last,
+                       const int32_t *forced, int32_t *cids, float *values, float *top2,
+                       ovf_state *states, int64_t *n_evals, float eps, uint64_t seed, int32_t rollout) {
   if (!space_ok(sp) || !pipeline_ok(stages, S)) return OVF_EINVAL;
   if (first < 0 || last >= S || first > last + 1) return OVF_EINVAL;
   if (!vfun && (!mlp_ok(m) || m->dims[0] != sp->F)) return OVF_EINVAL;
@@ -748,6 +775,13 @@ int ovf_greedy(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_mo
       rc = ovf_score_mlp(m, weights, xcol, M, M, sc);
       if (rc != OVF_OK) break;
     }
+    /* Section 3.1: exploration adds a small random noise to the predictions */
+    if (eps != 0.0f)
+      for (int64_t cid = 0; cid < M; ++cid)
+        if (ok[cid]) {
+          float t = eps * ovf_noise(seed, rollout, i, (int32_t)cid);
+          sc[cid] = sc[cid] + t;
+        }
     /* the scan of Algorithm 1 */
     float v = INFINITY, v2 = INFINITY;
     int32_t s = -1;
@@ -772,6 +806,34 @@ int ovf_greedy(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_mo
   }
   free(st); free(cf); free(sc); free(ok); free(xcol);
   return rc;
+}
+
+int ovf_greedy(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_model *m,
+               const float *weights, ovf_vfun vfun, void *user, int first, int last,
+               const int32_t *forced, int32_t *cids, float *values, float *top2,
+               ovf_state *states, int64_t *n_evals) {
+  return greedy_impl(stages, S, sp, m, weights, vfun, user, first, last, forced, cids, values, top2,
+                     states, n_evals, 0.0f, 0, 0);
+}
+
+/* BestSchedule(n, V_eps) of Algorithm 2 / Section 3.1: the greedy scan with a small
+ * random noise added to every prediction, n_rollouts times.  Rollout k adds
+ * eps * ovf_noise(seed, first_rollout + k, layer, candidate) to the score (one float
+ * multiply, one float add) before the scan; the kept value is the noisy one.
+ * cids / values / top2 are [n_rollouts][S]; forced (nullable, [n_rollouts][S]) as in
+ * ovf_greedy. */
+int ovf_rollouts(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_model *m,
+                 const float *weights, float eps, uint64_t seed, int32_t first_rollout,
+                 int32_t n_rollouts, const int32_t *forced, int32_t *cids, float *values, float *top2) {
+  if (n_rollouts < 0) return OVF_EINVAL;
+  for (int32_t k = 0; k < n_rollouts; ++k) {
+    int rc = greedy_impl(stages, S, sp, m, weights, NULL, NULL, 0, S - 1,
+                         forced ? forced + (size_t)k * S : NULL, cids + (size_t)k * S,
+                         values + (size_t)k * S, top2 ? top2 + (size_t)k * S : NULL, NULL, NULL, eps, seed,
+                         first_rollout + k);
+    if (rc != OVF_OK) return rc;
+  }
+  return OVF_OK;
 }
 
 /* ------------------------------------------------------------ beam search */
