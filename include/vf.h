@@ -177,6 +177,17 @@ int vf_argmin_step(vf_ctx *ctx, int stage, int commit, int32_t *best_cid_dev, fl
 int vf_greedy_schedule(vf_ctx *ctx, int first_stage, int last_stage, vf_state *out_states_dev,
                        int32_t *out_cids_dev, float *out_values_dev);
 
+/* Exploration noise (Sec. 3.1, BestSchedule(n, V_eps) of Algorithm 2: a small random
+ * noise is added to the predictions so that repeated greedy runs cover different
+ * schedules).  From now on vf_argmin_step and vf_greedy_schedule scan
+ * V(s) + eps * u(seed, first_rollout + b, layer, candidate id) for problem b, with u in
+ * [-1, 1) = (top 24 bits of the first Philox4x32-10 word of counter (id, layer,
+ * rollout, 0) under key seed) * 2^-23 - 1, one fp32 multiply and one fp32 add; the
+ * reported values are the noisy ones.  A batch of B copies of one network is thus B
+ * different rollouts.  eps = 0 (the initial state) switches the noise off.  vf_score
+ * and vf_beam_search never add noise.  VF_EINVAL for a negative or non-finite eps. */
+int vf_set_noise(vf_ctx *ctx, float eps, uint64_t seed, int32_t first_rollout);
+
 /* Beam search guided by V (Secs. 3.1 and 4.1 use a standard beam search next to the
  * greedy scan; Algorithm 2 completes prefixes with it).  The context's `batch` problems
  * are the beam slots of ONE network: every slot must hold the same pipeline (else

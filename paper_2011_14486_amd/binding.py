@@ -22,7 +22,7 @@ VF_X_RAW_I32, VF_X_SEQ_BF16 = 0, 1
 EXPORTS = [
     "vf_create", "vf_destroy", "vf_set_space", "vf_set_pipeline", "vf_set_model", "vf_reset_state",
     "vf_set_state", "vf_n_scheduled", "vf_dense_count", "vf_padded_count", "vf_enumerate",
-    "vf_featurize", "vf_score", "vf_argmin_step", "vf_greedy_schedule", "vf_beam_search", "vf_strerror",
+    "vf_featurize", "vf_score", "vf_argmin_step", "vf_greedy_schedule", "vf_beam_search", "vf_set_noise", "vf_strerror",
     "vf_last_hip_error", "vf_timer_start", "vf_timer_stop", "vf_timer_elapsed_ms",
     "vf_profile_enable", "vf_profile_read",
 ]
@@ -71,6 +71,7 @@ def lib():
         L.vf_score.argtypes = [vp, vp, i32, i64, i64, i32, vp, vp, vp]
         L.vf_argmin_step.argtypes = [vp, C.c_int, C.c_int, vp, vp]
         L.vf_greedy_schedule.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp]
+        L.vf_set_noise.argtypes = [vp, C.c_float, C.c_uint64, i32]
         L.vf_beam_search.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp, vp]
         L.vf_strerror.argtypes = [C.c_int]
         L.vf_strerror.restype = C.c_char_p
@@ -250,6 +251,10 @@ def vf_greedy_schedule(ctx, first=0, last=None, out=None):
     st, cids, vals = out
     _check(ctx, lib().vf_greedy_schedule(ctx.handle, first, last, _ptr(st), _ptr(cids), _ptr(vals)))
     return st, cids, vals
+
+
+def vf_set_noise(ctx, eps, seed=0, first_rollout=0):
+    _check(ctx, lib().vf_set_noise(ctx.handle, C.c_float(eps), seed, first_rollout))
 
 
 def vf_beam_search(ctx, first=0, last=None):

@@ -142,7 +142,7 @@ int step(vf_ctx *c, int stage, int commit, int32_t *best_cid, float *best_val) {
   rc = vfk_featurize(c, stage, c->d_feat);
   if (rc != VF_OK) return rc;
   int nparts = 0;
-  rc = vfk_score_mlp(c, c->d_feat, (int64_t)c->space.F * c->Mpad, c->B, c->M, c->Mpad, 1, nullptr, 0, &nparts);
+  rc = vfk_score_mlp(c, c->d_feat, (int64_t)c->space.F * c->Mpad, c->B, c->M, c->Mpad, 1, nullptr, 0, &nparts, stage);
   if (rc != VF_OK) return rc;
   return vfk_commit_from_partials(c, stage, nparts, commit, best_cid, best_val);
 }
@@ -341,7 +341,7 @@ int vf_score(vf_ctx *c, const void *x, int32_t x_kind, int64_t M, int64_t ld, in
   int nparts = 0, part = 0, rc;
   if (x_kind == VF_X_RAW_I32) {
     if (c->model.kind != VF_MLP || ld < M) return VF_EINVAL;
-    rc = vfk_score_mlp(c, (const int32_t *)x, 0, 1, M, ld, 0, scores, ld, &nparts);
+    rc = vfk_score_mlp(c, (const int32_t *)x, 0, 1, M, ld, 0, scores, ld, &nparts, -1);
     int maxw = 0;
     for (int l = 0; l < c->model.n_layers; ++l)
       if (c->model.dims[l] > maxw) maxw = c->model.dims[l];
@@ -392,6 +392,14 @@ int vf_greedy_schedule(vf_ctx *c, int first, int last, vf_state *out_states, int
     VF_HIP(c, hipMemcpyAsync(out_states, c->d_states, n * sizeof(vf_state), hipMemcpyDeviceToDevice, c->stream));
   if (out_cids) VF_HIP(c, hipMemcpyAsync(out_cids, c->d_cids, n * 4, hipMemcpyDeviceToDevice, c->stream));
   if (out_vals) VF_HIP(c, hipMemcpyAsync(out_vals, c->d_vals, n * 4, hipMemcpyDeviceToDevice, c->stream));
+  return VF_OK;
+}
+
+int vf_set_noise(vf_ctx *c, float eps, uint64_t seed, int32_t first_rollout) {
+  if (!c || !(eps >= 0.0f) || eps > 3.0e38f || first_rollout < 0) return VF_EINVAL;
+  c->noise_eps = eps;
+  c->noise_seed = seed;
+  c->noise_first = first_rollout;
   return VF_OK;
 }
 

@@ -68,6 +68,10 @@ struct vf_ctx {
   float *d_tk_val = nullptr; int32_t *d_tk_idx = nullptr; size_t tk_elems = 0;  // chunk partials
   float *d_sel_val = nullptr; int32_t *d_sel_idx = nullptr;  // [B] survivors (value, beam*Mpad+cid)
   int32_t *d_sel_n = nullptr;    // [2]: survivors of this layer, live schedules so far
+  // exploration noise added to the scores in the argmin scan of step / greedy calls
+  float noise_eps = 0.0f;
+  uint64_t noise_seed = 0;
+  int32_t noise_first = 0;
   std::vector<vf_stage> h_stages;  // host copy of the stage records
   bool beam_checked = false;       // all slots verified to hold the same pipeline
 
@@ -142,10 +146,11 @@ int vfk_pack_model(vf_ctx *c, const float *weights_dev);
 void vfk_free_model(vf_ctx *c);
 // Scores nprob problems of M candidates each: x + p*prob_stride is [F][ld].
 // use_valid_row: row 16 of x is the validity flag (invalid -> +inf).
+// noise_stage >= 0: the context's exploration noise for that layer is added before the scan.
 // Writes scores (nullable, [nprob][ld_scores]) and the partial minima
 // (ctx->d_pval / d_pidx, [nprob][nparts], ids local to the problem).
 int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
-                  int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out);
+                  int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int noise_stage);
 // Enumerate + featurize + score + partial argmin of one stage in a single kernel (bf16
 // MLPs of uniform hidden width whose input width is the space's F).
 bool vfk_can_fuse_step(const vf_ctx *c);

@@ -272,6 +272,36 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, vf_bf16x2));
 }
 
+// ---- exploration noise (Sec. 3.1: a small random noise is added to the predictions)
+
+// Philox4x32-10 (Salmon et al., SC'11), first output word
+__device__ __forceinline__ uint32_t philox_first(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                                 uint32_t k0, uint32_t k1) {
+#pragma unroll
+  for (int round = 0; round < 10; ++round) {
+    if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+    const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+    const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+    const uint32_t n0 = hi1 ^ c1 ^ k0, n2 = hi0 ^ c3 ^ k1;
+    c0 = n0; c1 = lo1; c2 = n2; c3 = lo0;
+  }
+  return c0;
+}
+
+struct NoiseArgs {
+  float eps;            // 0: no noise
+  uint32_t k0, k1;      // seed
+  int32_t stage;
+  int32_t first_rollout;  // problem p is rollout first_rollout + p
+};
+
+// score + eps * u, u in [-1, 1) from the counter (candidate, layer, rollout)
+__device__ __forceinline__ float add_noise(const NoiseArgs &na, float s, int p, int32_t cid) {
+  const uint32_t x = philox_first((uint32_t)cid, (uint32_t)na.stage, (uint32_t)(na.first_rollout + p), 0u, na.k0, na.k1);
+  const float u = (float)(x >> 8) * 0x1p-23f - 1.0f;
+  return __fadd_rn(s, __fmul_rn(na.eps, u));
+}
+
 // The decision context in the form the fused scorer wants it: built once per problem
 // and stage (by the commit of the stage before, or by k_prepare), fetched by every
 // scoring workgroup with one coalesced copy.

@@ -85,7 +85,8 @@ __global__ __launch_bounds__(256) void k_mlp_f32_layer(const void *in_, int64_t 
 // One (value, id) pair per block of VF_PART candidates of each problem.
 __global__ __launch_bounds__(VF_PART) void k_argmin_parts(const float *scores, int64_t score_stride,
                                                           const int32_t *valid_row, int64_t valid_stride,
-                                                          int64_t M, int nparts, float *pval, int32_t *pidx) {
+                                                          int64_t M, int nparts, float *pval, int32_t *pidx,
+                                                          NoiseArgs na) {
   __shared__ float sv[VF_PART / 64];
   __shared__ int32_t sc[VF_PART / 64];
   const int p = blockIdx.y;
@@ -95,6 +96,7 @@ __global__ __launch_bounds__(VF_PART) void k_argmin_parts(const float *scores, i
   if (n < M) {
     float s = scores[(size_t)p * score_stride + n];
     bool ok = valid_row ? valid_row[(size_t)p * valid_stride + n] != 0 : true;
+    if (na.eps != 0.0f) s = add_noise(na, s, p, (int32_t)n);
     if (ok && s < v) { v = s; c = (int32_t)n; }
   }
   wave_min(v, c);
@@ -170,7 +172,8 @@ __device__ __forceinline__ float relu_bits(float v) {
 template <int NC, int RT, int PD>
 __global__ __launch_bounds__(512) void k_mlp_bf16(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
                                                   int use_valid_row, MlpDev md, int ks, float *scores,
-                                                  int64_t ld_scores, float *pval, int32_t *pidx, int nparts) {
+                                                  int64_t ld_scores, float *pval, int32_t *pidx, int nparts,
+                                                  NoiseArgs na) {
   constexpr int CT = NC / 32;
   constexpr int SEGS = 512 / NC;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -343,6 +346,7 @@ __global__ __launch_bounds__(512) void k_mlp_bf16(const int32_t *x, int64_t prob
 #pragma unroll
       for (int g = 0; g < 8; ++g) s += red[g * NC + tid];
       if (scores && (n0 + tid) < M) scores[(size_t)p * ld_scores + n0 + tid] = s;
+      if (na.eps != 0.0f) s = add_noise(na, s, p, (int32_t)(n0 + tid));
       if (okf[tid] != 0 && s < v) { v = s; c = (int32_t)(n0 + tid); }
       wave_min(v, c);
     }
@@ -424,7 +428,7 @@ template <int NC, int RT, int PD, bool GEN>
 __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
                                                   int use_valid_row, FastDev md, int ks, float *scores,
                                                   int64_t ld_scores, float *pval, int32_t *pidx, int nparts,
-                                                  int nprob, GenArgs ga) {
+                                                  int nprob, GenArgs ga, NoiseArgs na) {
   constexpr int CT = NC / 32;
   constexpr int SEGS = 512 / NC;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -672,6 +676,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       // scores of a generated tile are masked: invalid candidates and padding read +inf
       if (scores && (GEN ? (n0 + tid) < ld_scores : (n0 + tid) < M))
         scores[(size_t)p * ld_scores + n0 + tid] = (GEN && okf[tid] == 0) ? __builtin_inff() : s;
+      if (na.eps != 0.0f) s = add_noise(na, s, p, (int32_t)(n0 + tid));
       if (okf[tid] != 0 && s < v) { v = s; c = (int32_t)(n0 + tid); }
       wave_min(v, c);
     }
@@ -1040,11 +1045,12 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
 }
 
 static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
-                     int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage);
+                     int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage,
+                     int noise_stage);
 
 int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
-                  int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out) {
-  return score_mlp(c, x, prob_stride, nprob, M, ld, use_valid_row, scores, ld_scores, nparts_out, -1);
+                  int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int noise_stage) {
+  return score_mlp(c, x, prob_stride, nprob, M, ld, use_valid_row, scores, ld_scores, nparts_out, -1, noise_stage);
 }
 
 bool vfk_can_fuse_step(const vf_ctx *c) {
@@ -1053,7 +1059,7 @@ bool vfk_can_fuse_step(const vf_ctx *c) {
 }
 
 int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out) {
-  return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, nparts_out, stage);
+  return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, nparts_out, stage, stage);
 }
 
 namespace {
@@ -1074,7 +1080,7 @@ int vfk_step_scores(vf_ctx *c, int stage) {
   int rc = grow(c, c->d_scores, c->score_elems, want);
   if (rc != VF_OK) return rc;
   int nparts = 0;
-  if (vfk_can_fuse_step(c)) return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, stage);
+  if (vfk_can_fuse_step(c)) return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, stage, -1);
   // general models: materialise the features, score, mask
   const size_t fwant = (size_t)c->B * c->space.F * c->Mpad;
   rc = grow(c, c->d_feat, c->feat_elems, fwant);
@@ -1082,7 +1088,7 @@ int vfk_step_scores(vf_ctx *c, int stage) {
   rc = vfk_featurize(c, stage, c->d_feat);
   if (rc != VF_OK) return rc;
   const int64_t fstride = (int64_t)c->space.F * c->Mpad;
-  rc = score_mlp(c, c->d_feat, fstride, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, -1);
+  rc = score_mlp(c, c->d_feat, fstride, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, -1, -1);
   if (rc != VF_OK) return rc;
   hipLaunchKernelGGL(k_mask_scores, dim3((unsigned)((c->Mpad + 255) / 256), (unsigned)c->B), dim3(256), 0, c->stream,
                      c->d_scores, c->d_feat, fstride, c->M, c->Mpad);
@@ -1091,7 +1097,12 @@ int vfk_step_scores(vf_ctx *c, int stage) {
 }
 
 static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
-                     int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage) {
+                     int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage,
+                     int noise_stage) {
+  NoiseArgs na;
+  na.eps = noise_stage >= 0 ? c->noise_eps : 0.0f;
+  na.k0 = (uint32_t)c->noise_seed; na.k1 = (uint32_t)(c->noise_seed >> 32);
+  na.stage = noise_stage; na.first_rollout = c->noise_first;
   const vf_model &m = c->model;
   const int L = m.n_layers;
   hipStream_t st = c->stream;
@@ -1137,7 +1148,7 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     if (nparts > 0) {
       hipLaunchKernelGGL(k_argmin_parts, dim3((unsigned)nparts, (unsigned)nprob), dim3(VF_PART), 0, st,
                          final_scores, final_stride, use_valid_row ? x + (size_t)16 * ld : (const int32_t *)nullptr,
-                         prob_stride, M, nparts, c->d_pval, c->d_pidx);
+                         prob_stride, M, nparts, c->d_pval, c->d_pidx, na);
       VF_HIP(c, hipGetLastError());
     }
     *nparts_out = nparts;
@@ -1172,7 +1183,7 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     const int64_t tiles = (int64_t)nparts * nprob;
     dim3 grid((unsigned)(tiles < ncu ? tiles : ncu));
     void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, FastDev, int, float *, int64_t, float *, int32_t *, int,
-                 int, GenArgs);
+                 int, GenArgs, NoiseArgs);
     GenArgs ga;
     ga.decpack = c->d_decpack;
     if (gen_stage >= 0) {
@@ -1183,17 +1194,18 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     else kern = wide ? k_mlp_fast<64, 4, 2, false> : k_mlp_fast<128, 2, 4, false>;
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_fast));
     hipLaunchKernelGGL(kern, grid, dim3(512), smem_fast, st, x, prob_stride, M, ld, use_valid_row, fd, ks, scores,
-                       ld_scores, c->d_pval, c->d_pidx, nparts, nprob, ga);
+                       ld_scores, c->d_pval, c->d_pidx, nparts, nprob, ga, na);
     VF_HIP(c, hipGetLastError());
   } else if (nparts > 0) {
     vf_prof_scope prof(c, VF_PROF_SCORE);
     dim3 grid((unsigned)nparts, (unsigned)nprob);
-    void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, MlpDev, int, float *, int64_t, float *, int32_t *, int);
+    void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, MlpDev, int, float *, int64_t, float *, int32_t *, int,
+                 NoiseArgs);
     if (wide) kern = k_mlp_bf16<64, 4, 2>;
     else kern = k_mlp_bf16<128, 2, 2>;
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, x, prob_stride, M, ld, use_valid_row, md, ks, scores,
-                       ld_scores, c->d_pval, c->d_pidx, nparts);
+                       ld_scores, c->d_pval, c->d_pidx, nparts, na);
     VF_HIP(c, hipGetLastError());
   }
   *nparts_out = nparts;

@@ -1,0 +1,97 @@
+"""GPU parity: noisy greedy rollouts (Sec. 3.1 / Alg. 2) against the CPU checker."""
+import numpy as np
+import pytest
+
+from paper_2011_14486_amd import inputs as I
+from tests.util import TOL, score_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vf():
+    import paper_2011_14486_amd as pkg
+    return pkg.load()
+
+
+def gpu_rollouts(vf, pipe, sp, model, w, B, eps, seed, first=0):
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp)
+    vf.vf_set_pipeline(ctx, np.repeat(pipe[None], B, axis=0))
+    vf.vf_set_model(ctx, model, w)
+    vf.vf_set_noise(ctx, eps, seed, first)
+    st, cids, vals = vf.vf_greedy_schedule(ctx)
+    return ctx, cids.cpu().numpy(), vals.cpu().numpy(), st.cpu().numpy()
+
+
+@pytest.mark.parametrize("dtype,dims", [(I.FP32, [64, 128, 128, 1]), (I.BF16, [64, 128, 128, 1])])
+def test_noise_alone_is_bit_exact(vf, ovf, dtype, dims):
+    """Zero weights: every score is the output bias, so the scan sees bias + eps*noise only.
+    The noise has no tolerance: decisions and values must equal the checker's bit for bit,
+    on the fp32 kernels and on the MFMA path."""
+    pipe, sp = I.tiny_conv_relu(), I.tiny_space()
+    w = np.zeros(I.mlp_param_count(dims), np.float32); w[-1] = 0.625
+    model = I.model_record(I.MLP, dims, dtype)
+    B, eps, seed = 9, 0.37, 0xfeedbeefcafe
+    ctx, cids, vals, st = gpu_rollouts(vf, pipe, sp, model, w, B, eps, seed, first=5)
+    ref = ovf.rollouts(pipe, sp, model, w, eps, seed, B, first_rollout=5)
+    assert np.array_equal(cids, ref["cids"]) and np.array_equal(vals, ref["values"])
+    assert len({tuple(r) for r in cids}) > 1
+    vf.vf_destroy(ctx)
+
+
+def test_noisy_rollouts_fused_bf16(vf, ovf):
+    """A batch of copies of one network is a batch of different rollouts; each follows the
+    checker's rollout with the same id (decisions inside the score tolerance are forced)."""
+    pipe, sp = I.resnet18_shaped(), I.resnet18_space()
+    dims = [256, 512, 512, 1]
+    w = I.mlp_weights(dims, 0)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    B, eps, seed = 6, 0.5, 2024
+    ctx, cids, vals, st = gpu_rollouts(vf, pipe, sp, model, w, B, eps, seed)
+    assert len({tuple(r) for r in cids}) == B                     # all different
+    forced = np.full((B, 20), -1, np.int32)
+    for _ in range(21):
+        ref = ovf.rollouts(pipe, sp, model, w, eps, seed, B, forced=forced)
+        bad = np.argwhere(ref["cids"] != cids)
+        if len(bad) == 0:
+            break
+        k, i = (int(t) for t in bad[0])
+        margin = abs(float(ref["top2"][k, i]) - float(ref["values"][k, i])) / max(abs(float(ref["values"][k, i])), 1.0)
+        assert margin <= TOL[1], f"rollout {k} layer {i}: decision differs outside the margin ({margin})"
+        forced[k, i] = cids[k, i]
+    else:
+        raise AssertionError("rollouts do not converge")
+    assert score_err(vals.ravel(), ref["values"].ravel()) <= TOL[1]
+    for k in range(B):
+        rst, _ = ovf.states(pipe, sp, cids[k])
+        assert np.array_equal(rst, st[k])
+    # switching the noise off gives back the plain greedy schedule in every slot
+    vf.vf_set_noise(ctx, 0.0)
+    vf.vf_reset_state(ctx)
+    _, c0, v0 = vf.vf_greedy_schedule(ctx)
+    c0 = c0.cpu().numpy()
+    assert (c0 == c0[0]).all()
+    with pytest.raises(vf.VfError):
+        vf.vf_set_noise(ctx, -1.0)
+    vf.vf_destroy(ctx)
+
+
+def test_noisy_rollouts_unfused_path(vf, ovf):
+    """A model outside the fused path: features materialised, generic MFMA scorer."""
+    sp = I.make_space([1, 2, 4], [1, 2], [1, 4], [(0, 1, 2), (2, 1, 0)], 2, 1,
+                      [I.ROOT, I.L1, I.L2, I.INLINE], 1, 64)
+    pipe = I.random_pipeline(4, 52)
+    dims = [64, 96, 32, 1]
+    w = I.mlp_weights(dims, 9, bias_std=0.1)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    B, eps, seed = 4, 0.2, 5
+    ctx, cids, vals, st = gpu_rollouts(vf, pipe, sp, model, w, B, eps, seed)
+    ref = ovf.rollouts(pipe, sp, model, w, eps, seed, B)
+    if not np.array_equal(cids, ref["cids"]):
+        k, i = (int(t) for t in np.argwhere(ref["cids"] != cids)[0])
+        margin = abs(float(ref["top2"][k, i]) - float(ref["values"][k, i])) / max(abs(float(ref["values"][k, i])), 1.0)
+        assert margin <= TOL[1]
+    else:
+        assert score_err(vals.ravel(), ref["values"].ravel()) <= TOL[1]
+    vf.vf_destroy(ctx)
