@@ -605,6 +605,9 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
           ring[j][r] = wp[r * 64];
         }
         wp += RT * 64;
+        // keep the prefetch where it is: the scheduler would otherwise sink these loads
+        // towards their use, PD k-steps later, and lose the latency cover
+        __builtin_amdgcn_sched_barrier(0);
         // fragments of the next k-step (one step past the end stays inside the tile's LDS)
 #pragma unroll
         for (int c = 0; c < CT; ++c)
