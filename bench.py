@@ -22,7 +22,7 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at batch 256, scaled by a
 # plain 1 GiB copy (profiles/*_hbm_counters.txt); only valid for the default batch, and to be
 # set to None whenever the kernel changes without the counters being taken again
-TRAFFIC_SCORE_BYTES = {256: 7.58e6 + 1.11e6}
+TRAFFIC_SCORE_BYTES = {}
 TRAFFIC_FEATURIZE_BYTES = {256: 4.49e6 + 1073741824.0}
 
 
@@ -36,11 +36,13 @@ def cpu_baseline(I, pipe, space, model, w, dims):
     S = len(pipe)
     M = ovf.dense_count(space)
     t0 = time.perf_counter()
-    ovf.greedy(pipe, space, model, w)
+    r = ovf.greedy(pipe, space, model, w)
     dt = time.perf_counter() - t0
-    return {"value": S * M / dt, "unit": "candidates/s", "cores": ovf.num_threads(), "kind": "oracle",
-            "sample": f"one pipeline of the batch (problem 0: {S} decisions x {M} candidate ids, "
-                      f"features + V(s) for the valid ones + argmin), {dt:.1f} s"}
+    return {"value": r["n_evals"] / dt, "unit": "candidates/s", "cores": ovf.num_threads(), "kind": "oracle",
+            "candidate_ids_per_s": S * M / dt,
+            "sample": f"one pipeline of the batch (problem 0: {S} decisions x {M} candidate ids, of which "
+                      f"{r['n_evals']} are valid candidates; features and V(s) for every id, argmin over the "
+                      f"valid ones), {dt:.1f} s"}
 
 
 def main():
@@ -96,6 +98,7 @@ def main():
     vf.vf_profile_enable(ctx, True)
     for k in (0, 1, 2):
         vf.vf_profile_read(ctx, k)
+    vf.vf_profile_counts(ctx)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -109,11 +112,19 @@ def main():
     cids = out[1].cpu().numpy()
     assert (cids >= 0).all(), "a schedule ended early"
 
-    cand_per_step = B * S * M
-    value = cand_per_step * args.steps / dt
+    # Algorithm 1 evaluates V on the candidates of each layer: `value` counts the valid
+    # candidates.  The dense id space is larger (ids whose digits break a validity rule);
+    # runs of ids closed by the compute_at / store_at digits alone never reach the
+    # network, the other invalid ids share a tile with valid ones and do.
+    scored, valid = vf.vf_profile_counts(ctx)
+    ids_per_step = B * S * M
+    valid_per_step = valid / args.steps
+    scored_per_step = scored / args.steps
+    value = valid / dt
 
-    # dominant kernel: the fused MLP scorer (dense contraction -> MFMA roofline)
-    flops_per_launch = mlp_flops(dims) * B * M
+    # dominant kernel: the fused MLP scorer (dense contraction -> MFMA roofline); the
+    # flops are those of the ids that went through the network
+    flops_per_launch = mlp_flops(dims) * scored / max(n_score, 1)
     score_ms = ms_score / max(n_score, 1)
     achieved = flops_per_launch / (score_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": "k_mlp_fast<128,2,4,gen> (enumerate+featurize+MLP+argmin fused)", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
@@ -178,11 +189,13 @@ def main():
         "value": value, "unit": "candidates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": dt / args.steps * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"ResNet-18-shaped pipelines, {S} stages, {M} candidates per decision, F=256, "
+        "config": {"workload": f"ResNet-18-shaped pipelines, {S} stages, {M} candidate ids per decision, F=256, "
                                f"MLP 256-512-512-1 bf16 weights/activations with fp32 accumulation; batch of {B} "
                                "independent pipelines per step (problem 0 has the standard shapes, the others "
                                "seeded width/resolution variants)",
-                   "batch": B, "stages": S, "candidates_per_decision": M, "candidates_per_step": cand_per_step},
+                   "batch": B, "stages": S, "candidate_ids_per_decision": M, "candidate_ids_per_step": ids_per_step,
+                   "valid_candidates_per_step": valid_per_step, "ids_through_network_per_step": scored_per_step},
+        "candidate_ids_per_s": ids_per_step * args.steps / dt,
         "greedy_ms_single_pipeline": single_ms,
         "greedy_ms_mobilenetv2_100_stages_16384_candidates": mb_ms,
         "kernel_ms_per_step": {"featurize": ms_feat / args.steps, "score": ms_score / args.steps,

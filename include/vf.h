@@ -223,6 +223,13 @@ int vf_timer_elapsed_ms(vf_ctx *ctx, float *ms_host);
 enum { VF_PROF_FEATURIZE = 0, VF_PROF_SCORE = 1, VF_PROF_COMMIT = 2 };
 int vf_profile_enable(vf_ctx *ctx, int enable);
 int vf_profile_read(vf_ctx *ctx, int which, double *total_ms_host, int64_t *launches_host);
+/* While profiling is enabled the fused step of vf_argmin_step / vf_greedy_schedule /
+ * vf_beam_search counts, over all problems of the batch, the candidate ids it pushed
+ * through V and how many of them were valid candidates (Algorithm 1 evaluates V on the
+ * candidates only; runs of ids that the compute_at / store_at digits alone rule out are
+ * decided without the network and are not counted).  vf_profile_counts synchronises,
+ * returns both counts since the last call and clears them.  Either pointer may be NULL. */
+int vf_profile_counts(vf_ctx *ctx, int64_t *scored_host, int64_t *valid_host);
 
 #ifdef __cplusplus
 }

@@ -175,6 +175,8 @@ int vf_create(vf_ctx **out, int device, void *hip_stream) {
   DeviceGuard g(device);
   int rc = dev_alloc(c, c->d_space, sizeof(vf_space) / 4);
   if (rc == VF_OK) rc = dev_alloc(c, c->d_err, 1);
+  if (rc == VF_OK) rc = dev_alloc(c, c->d_stat, 2);
+  if (rc == VF_OK && hipMemsetAsync(c->d_stat, 0, 16, c->stream) != hipSuccess) rc = VF_EHIP;
   if (rc == VF_OK && hipEventCreate(&c->ev0) != hipSuccess) rc = VF_EHIP;
   if (rc == VF_OK && hipEventCreate(&c->ev1) != hipSuccess) rc = VF_EHIP;
   if (rc != VF_OK) {
@@ -191,7 +193,7 @@ void vf_destroy(vf_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   free_pipeline(c);
   vfk_free_model(c);
-  void *ps[] = {c->d_space, c->d_err,  c->d_feat,   c->d_act[0], c->d_act[1],
+  void *ps[] = {c->d_space, c->d_err,  c->d_stat, c->d_feat,   c->d_act[0], c->d_act[1],
                 c->d_pval,  c->d_pidx, c->d_scores, c->d_tk_val, c->d_tk_idx};
   for (void *p : ps)
     if (p) (void)hipFree(p);
@@ -382,10 +384,16 @@ int vf_greedy_schedule(vf_ctx *c, int first, int last, vf_state *out_states, int
   if (first < 0 || last >= c->S || first > last + 1) return VF_EINVAL;
   if (first != c->n_sched) return VF_ESTATE;
   DeviceGuard g(c->device);
-  for (int i = first; i <= last; ++i) {
-    int rc = step(c, i, 1, nullptr, nullptr);
+  if (first <= last && vfk_can_run_whole(c)) {
+    int rc = vfk_greedy_whole(c, first, last);
     if (rc != VF_OK) return rc;
-    c->n_sched = i + 1;
+    c->n_sched = last + 1;
+  } else {
+    for (int i = first; i <= last; ++i) {
+      int rc = step(c, i, 1, nullptr, nullptr);
+      if (rc != VF_OK) return rc;
+      c->n_sched = i + 1;
+    }
   }
   const size_t n = (size_t)c->B * c->S;
   if (out_states)
@@ -490,6 +498,18 @@ int vf_profile_read(vf_ctx *c, int which, double *total_ms, int64_t *launches) {
   if (launches) *launches = (int64_t)(v.size() / 2);
   for (hipEvent_t e : v) c->prof_free.push_back(e);
   v.clear();
+  return VF_OK;
+}
+
+int vf_profile_counts(vf_ctx *c, int64_t *scored, int64_t *valid) {
+  if (!c) return VF_EINVAL;
+  DeviceGuard g(c->device);
+  unsigned long long h[2] = {0ull, 0ull};
+  VF_HIP(c, hipMemcpyAsync(h, c->d_stat, 16, hipMemcpyDeviceToHost, c->stream));
+  VF_HIP(c, hipMemsetAsync(c->d_stat, 0, 16, c->stream));
+  VF_HIP(c, hipStreamSynchronize(c->stream));
+  if (scored) *scored = (int64_t)h[0];
+  if (valid) *valid = (int64_t)h[1];
   return VF_OK;
 }
 

@@ -55,6 +55,7 @@ struct vf_ctx {
   float *d_vals = nullptr;      // [B][S]
   int32_t *d_alive = nullptr;   // [B] 0 once a stage of the problem found no winner
   int32_t *d_err = nullptr;     // [1] set by a forced commit of an invalid candidate
+  unsigned long long *d_stat = nullptr;  // [2] ids scored by the fused step / valid ones, while profiling
   int32_t *d_forced = nullptr;  // [B][S] staging for vf_set_state
   uint32_t *d_decpack = nullptr; // [B][VF_DECPACK_DWORDS] decision context of stage dec_stage
   int dec_stage = -1;            // stage d_decpack was built for, -1: none
@@ -154,6 +155,8 @@ int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, i
 // Enumerate + featurize + score + partial argmin of one stage in a single kernel (bf16
 // MLPs of uniform hidden width whose input width is the space's F).
 bool vfk_can_fuse_step(const vf_ctx *c);
+bool vfk_can_run_whole(const vf_ctx *c);
+int vfk_greedy_whole(vf_ctx *c, int first, int last);
 int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out);
 // Scores of every candidate of `stage` for all problems into d_scores [B][Mpad]; invalid
 // candidates and padding columns get +inf.

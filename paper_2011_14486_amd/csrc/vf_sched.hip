@@ -154,37 +154,7 @@ __global__ __launch_bounds__(64) void k_commit(Tables t, int stage, int nparts, 
   if (lane == 0) {
     if (best_cid) best_cid[b] = c;
     if (best_val) best_val[b] = v;
-    if (commit) {
-      const size_t row = (size_t)b * S + stage;
-      int32_t *pre = t.prefix + ((size_t)b * (S + 1) + stage) * 2;
-      int32_t core[64];
-      bool ok = false;
-      if (c >= 0 && (uint32_t)c < M) {
-        uint32_t dec;
-        ok = eval_candidate<true>(d, sp, (uint32_t)c, dec, core);
-      }
-      if (!ok) {
-        if (forced) t.err[0] = 1;
-        t.alive[b] = 0;
-        t.cids[row] = -1;
-        t.vals[row] = __builtin_inff();
-        pre[2] = pre[0]; pre[3] = pre[1];
-      } else {
-#pragma unroll
-        for (int k = 0; k < 64; ++k) t.cf[row * 64 + k] = core[k];
-        int32_t *st = t.states + row * 16;
-        st[0] = core[17]; st[1] = core[18]; st[2] = core[19];
-        st[3] = core[23]; st[4] = core[26]; st[5] = core[29]; st[6] = core[32]; st[7] = core[33];
-        st[8] = core[34]; st[9] = core[35]; st[10] = core[36];
-        st[11] = core[37];
-        st[12] = core[20]; st[13] = core[21]; st[14] = core[22];
-        st[15] = 1;
-        t.cids[row] = c;
-        t.vals[row] = v;
-        pre[2] = sadd((uint32_t)pre[0], (uint32_t)core[40]);
-        pre[3] = sadd((uint32_t)pre[1], (uint32_t)core[50]);
-      }
-    }
+    if (commit) commit_winner(t, d, sp, b, stage, c, v, M, forced != nullptr);
   }
   // the next stage's decision context, for the fused scorer
   if (commit && decpack_next && stage + 1 < S) {

@@ -251,6 +251,31 @@ __device__ __forceinline__ bool eval_candidate(const Dec &d, const vf_space &sp,
 }
 
 
+// True when no candidate id in [lo, hi) can be valid, judged from the two most
+// significant digits alone (compute_at level, store_at hoist: Table 1).  A level that
+// is closed for the stage, or a hoist above the level, rules out a whole run of
+// consecutive ids; inlining leaves one id per run.  False means "some id may be valid".
+__device__ __forceinline__ bool range_closed(const Dec &d, const vf_space &sp, uint32_t lo, uint32_t hi) {
+  if (hi <= lo) return true;
+  const uint32_t run = (uint32_t)sp.nf[0] * (uint32_t)sp.nf[1] * (uint32_t)sp.nf[2] * (uint32_t)sp.nperm *
+                       (uint32_t)sp.nvec * (uint32_t)sp.npar;  // ids per (level, hoist) pair
+  const uint32_t q0 = lo / run, q1 = (hi - 1u) / run;
+  if (q1 - q0 > 8u) return false;
+  for (uint32_t q = q0; q <= q1; ++q) {
+    const uint32_t icat = q % (uint32_t)sp.ncat, isat = q / (uint32_t)sp.ncat;
+    const int cat = sp.cat[icat];
+    if (d.lvl_ok[cat] == 0) continue;
+    if (cat == VF_INLINE) {
+      const uint32_t id = q * run;  // every other digit zero
+      if (isat == 0u && id >= lo && id < hi) return false;
+    } else if (isat <= (uint32_t)cat) {
+      return false;
+    }
+  }
+  return true;
+}
+
+
 // ---- normalisation (Sec. 3.2: the network is fed normalised feature values)
 
 // piecewise-linear log2 of a non-negative integer: exponent + (significand - 1)
@@ -313,12 +338,55 @@ struct DecPack {
 };
 static_assert(sizeof(DecPack) == VF_DECPACK_DWORDS * 4, "DecPack size");
 
-// Builds the pack for (problem b, stage) in LDS and copies it to out[b].
-[[maybe_unused]] __device__ void write_decpack(DecPack &pk, const Tables &t, int b, int stage, uint32_t *out) {
+// Builds the pack for (problem b, stage) in LDS (every thread of the block takes part).
+[[maybe_unused]] __device__ void fill_decpack(DecPack &pk, const Tables &t, int b, int stage) {
   build_dec(pk.d, pk.sp, t, b, stage);
   for (int q = threadIdx.x; q < 96; q += blockDim.x)
     pk.nbh[q] = pack_bf16(plog2_dev(pk.d.nb[2 * q]), plog2_dev(pk.d.nb[2 * q + 1]));
   __syncthreads();
+}
+
+// Algorithm 1's "s_i := s": one thread records candidate c (value v) of problem b as
+// the decision for `stage` - its derived loop structure, its 64 core features, the
+// running sums - or, when there is no valid winner, ends that problem's schedule.
+// d / sp are the decision context of (b, stage).
+[[maybe_unused]] __device__ __attribute__((noinline)) void commit_winner(const Tables &t, const Dec &d, const vf_space &sp, int b, int stage,
+                                               int32_t c, float v, uint32_t M, bool forced) {
+  const int S = t.S;
+  const size_t row = (size_t)b * S + stage;
+  int32_t *pre = t.prefix + ((size_t)b * (S + 1) + stage) * 2;
+  int32_t core[64];
+  bool ok = false;
+  if (c >= 0 && (uint32_t)c < M) {
+    uint32_t dec;
+    ok = eval_candidate<true>(d, sp, (uint32_t)c, dec, core);
+  }
+  if (!ok) {
+    if (forced) t.err[0] = 1;
+    t.alive[b] = 0;
+    t.cids[row] = -1;
+    t.vals[row] = __builtin_inff();
+    pre[2] = pre[0]; pre[3] = pre[1];
+  } else {
+#pragma unroll
+    for (int k = 0; k < 64; ++k) t.cf[row * 64 + k] = core[k];
+    int32_t *st = t.states + row * 16;
+    st[0] = core[17]; st[1] = core[18]; st[2] = core[19];
+    st[3] = core[23]; st[4] = core[26]; st[5] = core[29]; st[6] = core[32]; st[7] = core[33];
+    st[8] = core[34]; st[9] = core[35]; st[10] = core[36];
+    st[11] = core[37];
+    st[12] = core[20]; st[13] = core[21]; st[14] = core[22];
+    st[15] = 1;
+    t.cids[row] = c;
+    t.vals[row] = v;
+    pre[2] = sadd((uint32_t)pre[0], (uint32_t)core[40]);
+    pre[3] = sadd((uint32_t)pre[1], (uint32_t)core[50]);
+  }
+}
+
+// Builds the pack for (problem b, stage) in LDS and copies it to out[b].
+[[maybe_unused]] __device__ void write_decpack(DecPack &pk, const Tables &t, int b, int stage, uint32_t *out) {
+  fill_decpack(pk, t, b, stage);
   const uint32_t *src = reinterpret_cast<const uint32_t *>(&pk);
   const int used = (int)((sizeof(Dec) + sizeof(vf_space)) / 4 + 96);
   for (int i = threadIdx.x; i < VF_DECPACK_DWORDS; i += blockDim.x)

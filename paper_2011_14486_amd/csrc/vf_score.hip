@@ -422,13 +422,24 @@ __global__ __launch_bounds__(256) void k_pack_stream(const float *blob, FastDev 
 // straight into LDS as normalised bf16 and never touch HBM.
 struct GenArgs {
   const uint32_t *decpack;  // [problem][VF_DECPACK_DWORDS], built for the stage being decided
+  unsigned long long *stat; // nullable: [0] += ids pushed through the network, [1] += valid ones
 };
 
-template <int NC, int RT, int PD, bool GEN>
+// WHOLE (with GEN): the workgroup owns whole problems and runs Algorithm 1 on each of
+// them from stage wa.first to wa.last by itself - decision context, all tiles of the
+// stage, the scan's running minimum, the commit - so that a schedule costs one launch
+// instead of two per layer.  Pays when there are about as many problems as compute units.
+struct WholeArgs {
+  Tables t;
+  int first, last;
+};
+
+template <int NC, int RT, int PD, bool GEN, bool WHOLE>
 __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
                                                   int use_valid_row, FastDev md, int ks, float *scores,
                                                   int64_t ld_scores, float *pval, int32_t *pidx, int nparts,
-                                                  int nprob, GenArgs ga, NoiseArgs na) {
+                                                  int nprob, GenArgs ga, NoiseArgs na, WholeArgs wa) {
+  static_assert(GEN || !WHOLE, "whole schedules need the generating form");
   constexpr int CT = NC / 32;
   constexpr int SEGS = 512 / NC;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -464,9 +475,20 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   // ---- persistent loop: this workgroup's share of the (problem, tile) pairs, in
   // problem-major order so that consecutive tiles mostly share the decision context
   const int T = nparts * nprob;
-  const int t_begin = (int)((int64_t)blockIdx.x * T / gridDim.x);
-  const int t_end = (int)((int64_t)(blockIdx.x + 1) * T / gridDim.x);
+  int t_begin = (int)((int64_t)blockIdx.x * T / gridDim.x);
+  int t_end = (int)((int64_t)(blockIdx.x + 1) * T / gridDim.x);
   int cur_p = -1;
+  for (int unit = WHOLE ? (int)blockIdx.x : 0; unit < (WHOLE ? nprob : 1); unit += WHOLE ? (int)gridDim.x : 1)
+  for (int stage = WHOLE ? wa.first : 0; stage <= (WHOLE ? wa.last : 0); ++stage) {
+  float run_v = __builtin_inff();  // thread 0: the scan's incumbent over the tiles of this stage
+  int32_t run_c = -1;
+  if (WHOLE) {
+    fill_decpack(pk, wa.t, unit, stage);
+    cur_p = unit;
+    t_begin = unit * nparts;
+    t_end = t_begin + nparts;
+    na.stage = stage;
+  }
   for (int t = t_begin; t < t_end; ++t) {
   const int p = t / nparts;
   const int64_t n0 = (int64_t)(t - p * nparts) * NC;
@@ -479,6 +501,19 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   __syncthreads();
 
   if (GEN) {
+    // A tile none of whose ids can be valid is decided without the network.  For many
+    // stages whole compute_at levels are closed, and that digit is the most significant
+    // but one, so such ids come in runs much longer than a tile.
+    const int64_t nend = (n0 + NC < M) ? n0 + NC : M;
+    if (range_closed(pk.d, pk.sp, (uint32_t)n0, (uint32_t)(nend > n0 ? nend : n0))) {
+      if (scores && tid < NC && (n0 + tid) < ld_scores) scores[(size_t)p * ld_scores + n0 + tid] = __builtin_inff();
+      if (!WHOLE && tid == 0) {
+        pval[(size_t)t] = __builtin_inff();
+        pidx[(size_t)t] = -1;
+      }
+      __syncthreads();  // the next tile may bring another problem's context
+      continue;
+    }
     // ---- enumerate + featurize the tile: thread n < NC owns candidate n0 + n
     const Dec &dctx = pk.d;
     const vf_space &sp = pk.sp;
@@ -682,6 +717,14 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       if (na.eps != 0.0f) s = add_noise(na, s, p, (int32_t)(n0 + tid));
       if (okf[tid] != 0 && s < v) { v = s; c = (int32_t)(n0 + tid); }
       wave_min(v, c);
+      if (GEN && ga.stat) {
+        const int nvalid = __popcll(__ballot(okf[tid] != 0));
+        const int nin = __popcll(__ballot((n0 + tid) < M));
+        if (lane == 0) {
+          atomicAdd(&ga.stat[0], (unsigned long long)nin);
+          atomicAdd(&ga.stat[1], (unsigned long long)nvalid);
+        }
+      }
     }
     if (NC > 64) {
       __shared__ float sv[NC / 64];
@@ -690,15 +733,31 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       __syncthreads();
       if (tid == 0) {
         for (int k = 1; k < NC / 64; ++k) take_min(v, c, sv[k], sc[k]);
+        if (WHOLE) {
+          take_min(run_v, run_c, v, c);
+        } else {
+          pval[(size_t)t] = v;
+          pidx[(size_t)t] = c;
+        }
+      }
+    } else if (tid == 0) {
+      if (WHOLE) {
+        take_min(run_v, run_c, v, c);
+      } else {
         pval[(size_t)t] = v;
         pidx[(size_t)t] = c;
       }
-    } else if (tid == 0) {
-      pval[(size_t)t] = v;
-      pidx[(size_t)t] = c;
     }
   }
   __syncthreads();  // the tile's LDS is free for the next one
+  }
+  if (WHOLE) {
+    // s_i := the winner; the tables it updates are read back by this same workgroup
+    // when it builds the next stage's context
+    if (tid == 0) commit_winner(wa.t, pk.d, pk.sp, unit, stage, run_c, run_v, (uint32_t)M, false);
+    __threadfence();
+    __syncthreads();
+  }
   }
 }
 
@@ -1049,11 +1108,11 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
 
 static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
                      int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage,
-                     int noise_stage);
+                     int noise_stage, int whole_first, int whole_last);
 
 int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
                   int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int noise_stage) {
-  return score_mlp(c, x, prob_stride, nprob, M, ld, use_valid_row, scores, ld_scores, nparts_out, -1, noise_stage);
+  return score_mlp(c, x, prob_stride, nprob, M, ld, use_valid_row, scores, ld_scores, nparts_out, -1, noise_stage, -1, -1);
 }
 
 bool vfk_can_fuse_step(const vf_ctx *c) {
@@ -1062,7 +1121,25 @@ bool vfk_can_fuse_step(const vf_ctx *c) {
 }
 
 int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out) {
-  return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, nparts_out, stage, stage);
+  return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, nparts_out, stage, stage, -1, -1);
+}
+
+// Whole schedules in one launch pay when the problems fill the compute units evenly:
+// each workgroup then owns ceil(B / units) problems from the first layer to the last.
+bool vfk_can_run_whole(const vf_ctx *c) {
+  if (!vfk_can_fuse_step(c)) return false;
+  int ncu = 256;
+  (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
+  const int rounds = (c->B + ncu - 1) / ncu;
+  return (double)c->B >= 0.85 * (double)rounds * (double)ncu;
+}
+
+// Algorithm 1 over stages first..last for every problem of the batch, one launch.
+int vfk_greedy_whole(vf_ctx *c, int first, int last) {
+  int nparts = 0;
+  int rc = score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, &nparts, first, first, first, last);
+  c->dec_stage = -1;
+  return rc;
 }
 
 namespace {
@@ -1083,7 +1160,7 @@ int vfk_step_scores(vf_ctx *c, int stage) {
   int rc = grow(c, c->d_scores, c->score_elems, want);
   if (rc != VF_OK) return rc;
   int nparts = 0;
-  if (vfk_can_fuse_step(c)) return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, stage, -1);
+  if (vfk_can_fuse_step(c)) return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, stage, -1, -1, -1);
   // general models: materialise the features, score, mask
   const size_t fwant = (size_t)c->B * c->space.F * c->Mpad;
   rc = grow(c, c->d_feat, c->feat_elems, fwant);
@@ -1091,7 +1168,7 @@ int vfk_step_scores(vf_ctx *c, int stage) {
   rc = vfk_featurize(c, stage, c->d_feat);
   if (rc != VF_OK) return rc;
   const int64_t fstride = (int64_t)c->space.F * c->Mpad;
-  rc = score_mlp(c, c->d_feat, fstride, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, -1, -1);
+  rc = score_mlp(c, c->d_feat, fstride, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, -1, -1, -1, -1);
   if (rc != VF_OK) return rc;
   hipLaunchKernelGGL(k_mask_scores, dim3((unsigned)((c->Mpad + 255) / 256), (unsigned)c->B), dim3(256), 0, c->stream,
                      c->d_scores, c->d_feat, fstride, c->M, c->Mpad);
@@ -1101,7 +1178,7 @@ int vfk_step_scores(vf_ctx *c, int stage) {
 
 static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
                      int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage,
-                     int noise_stage) {
+                     int noise_stage, int whole_first, int whole_last) {
   NoiseArgs na;
   na.eps = noise_stage >= 0 ? c->noise_eps : 0.0f;
   na.k0 = (uint32_t)c->noise_seed; na.k1 = (uint32_t)(c->noise_seed >> 32);
@@ -1186,18 +1263,29 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     const int64_t tiles = (int64_t)nparts * nprob;
     dim3 grid((unsigned)(tiles < ncu ? tiles : ncu));
     void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, FastDev, int, float *, int64_t, float *, int32_t *, int,
-                 int, GenArgs, NoiseArgs);
+                 int, GenArgs, NoiseArgs, WholeArgs);
     GenArgs ga;
     ga.decpack = c->d_decpack;
-    if (gen_stage >= 0) {
+    ga.stat = c->profiling ? c->d_stat : nullptr;
+    WholeArgs wa;
+    wa.t = tables_of(c);
+    wa.first = whole_first; wa.last = whole_last;
+    const bool whole = whole_first >= 0;
+    if (gen_stage >= 0 && !whole) {
       int rc2 = vfk_prepare(c, gen_stage);
       if (rc2 != VF_OK) return rc2;
     }
-    if (gen_stage >= 0) kern = wide ? k_mlp_fast<64, 4, 2, true> : k_mlp_fast<128, 2, 4, true>;
-    else kern = wide ? k_mlp_fast<64, 4, 2, false> : k_mlp_fast<128, 2, 4, false>;
+    if (whole) {
+      kern = wide ? k_mlp_fast<64, 4, 2, true, true> : k_mlp_fast<128, 2, 4, true, true>;
+      grid = dim3((unsigned)(nprob < ncu ? nprob : ncu));
+    } else if (gen_stage >= 0) {
+      kern = wide ? k_mlp_fast<64, 4, 2, true, false> : k_mlp_fast<128, 2, 4, true, false>;
+    } else {
+      kern = wide ? k_mlp_fast<64, 4, 2, false, false> : k_mlp_fast<128, 2, 4, false, false>;
+    }
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_fast));
     hipLaunchKernelGGL(kern, grid, dim3(512), smem_fast, st, x, prob_stride, M, ld, use_valid_row, fd, ks, scores,
-                       ld_scores, c->d_pval, c->d_pidx, nparts, nprob, ga, na);
+                       ld_scores, c->d_pval, c->d_pidx, nparts, nprob, ga, na, wa);
     VF_HIP(c, hipGetLastError());
   } else if (nparts > 0) {
     vf_prof_scope prof(c, VF_PROF_SCORE);

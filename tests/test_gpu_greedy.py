@@ -220,3 +220,71 @@ def test_benchmark_configuration_batch256(vf, ovf):
     for b in range(0, B, 8):
         rst, _ = ovf.states(pipes[b], sp, cids[b])
         assert np.array_equal(rst, st[b])
+
+
+def test_profile_counts_are_the_candidates_of_algorithm_1(vf, ovf):
+    """The fused step reports how many ids went through V and how many of those were valid
+    candidates: the second number is the checker's count of V evaluations on the same
+    schedule; ids in runs closed by the compute_at / store_at digits never reach the network."""
+    pipe, sp = I.resnet18_shaped(), I.resnet18_space()
+    dims = [256, 512, 512, 1]
+    w = I.mlp_weights(dims, 0)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    S, M = len(pipe), I.space_dense_count(sp)
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipe); vf.vf_set_model(ctx, model, w)
+    vf.vf_profile_enable(ctx, True)
+    vf.vf_profile_counts(ctx)
+    st, cids, vals = vf.vf_greedy_schedule(ctx)
+    scored, valid = vf.vf_profile_counts(ctx)
+    assert vf.vf_profile_counts(ctx) == (0, 0)
+    ref = ovf.greedy(pipe, sp, model, w, forced=cids.cpu().numpy()[0])
+    assert np.array_equal(ref["cids"], cids.cpu().numpy()[0])
+    assert valid == ref["n_evals"]
+    assert valid <= scored < S * M
+    vf.vf_profile_enable(ctx, False)
+    vf.vf_reset_state(ctx); vf.vf_greedy_schedule(ctx)
+    assert vf.vf_profile_counts(ctx) == (0, 0)
+    vf.vf_destroy(ctx)
+
+
+def test_whole_schedule_launch_equals_layer_by_layer(vf, ovf):
+    """With about one problem per compute unit vf_greedy_schedule runs each problem's whole
+    schedule inside one workgroup; vf_argmin_step launches layer by layer.  Both must give
+    bit-identical tables: plain, resumed from a prefix in two pieces, with exploration
+    noise, and with problems whose schedule ends early in the batch."""
+    B = 256
+    pipes = I.resnet18_batch(B, seed=5)
+    pipes[7, 2, 3] = 2      # problem 7: the convolution at stage 2 has 2 channels ...
+    sp = I.make_space([1, 2, 4], [1, 4], [4, 8], [(0, 1, 2), (2, 1, 0)], 2, 2,
+                      [I.ROOT, I.L1, I.L2, I.INLINE], 2, 256)   # ... and every channel factor is larger
+    dims = [256, 512, 512, 1]
+    w = I.mlp_weights(dims, 3)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    S = pipes.shape[1]
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipes); vf.vf_set_model(ctx, model, w)
+
+    def layer_by_layer(first=0):
+        for i in range(first, S):
+            vf.vf_argmin_step(ctx, i, True)
+        return [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=S)]
+
+    for eps in (0.0, 0.05):
+        vf.vf_set_noise(ctx, eps, seed=11, first_rollout=2)
+        vf.vf_reset_state(ctx)
+        whole = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
+        vf.vf_reset_state(ctx)
+        steps = layer_by_layer()
+        for a, b in zip(whole, steps):
+            assert np.array_equal(a, b)
+        assert whole[1][7, 1] >= 0 and (whole[1][7, 2:] == -1).all() and (whole[1][6] >= 0).all()
+        # two pieces from a committed prefix
+        vf.vf_set_state(ctx, whole[1][:, :2])
+        vf.vf_greedy_schedule(ctx, first=2, last=9)
+        pieces = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=10)]
+        assert np.array_equal(whole[0], pieces[0]) and np.array_equal(whole[1], pieces[1])
+        assert np.array_equal(whole[2][:, 2:], pieces[2][:, 2:])   # a forced decision carries no value
+    ref = ovf.greedy(pipes[7], sp, model, w)
+    assert ref["cids"][1] >= 0 and ref["cids"][2] == -1
+    vf.vf_destroy(ctx)
