@@ -188,7 +188,7 @@ int vf_greedy_schedule(vf_ctx *ctx, int first_stage, int last_stage, vf_state *o
  * and vf_beam_search never add noise.  VF_EINVAL for a negative or non-finite eps. */
 int vf_set_noise(vf_ctx *ctx, float eps, uint64_t seed, int32_t first_rollout);
 
-/* Beam search guided by V (Secs. 3.1 and 4.1 use a standard beam search next to the
+/* Beam search guided by V (Secs. 3.1 and 4.1 search with a beam as well, next to the
  * greedy scan; Algorithm 2 completes prefixes with it).  The context's `batch` problems
  * are the beam slots of ONE network: every slot must hold the same pipeline (else
  * VF_EINVAL) and the beam width is `batch`.  Starts from problem 0's current schedule

@@ -49,6 +49,7 @@ def lib():
         L.ovf_states.argtypes = [vp, i32, vp, vp, i32, vp, vp]
         L.ovf_enumerate.argtypes = [vp, i32, vp, vp, i32, vp, vp, vp]
         L.ovf_featurize.argtypes = [vp, i32, vp, vp, i32, vp]
+        L.ovf_sequences.argtypes = [vp, i32, vp, vp, i32, vp, vp]
         L.ovf_plog2.restype = C.c_float
         L.ovf_plog2.argtypes = [i32]
         L.ovf_bf16_round.restype = C.c_float
@@ -125,6 +126,17 @@ def featurize(stages, space, prefix_cids, stage):
     feat = np.empty((int(space[64]), Mp), np.int32)
     _check(lib().ovf_featurize(_p(stages), len(stages), _p(space), _p(pre), stage, _p(feat)))
     return feat
+
+
+def sequences(stages, space, prefix_cids, stage):
+    """Sequence form of every candidate state of decision `stage`: (x [M][S][64] uint16 bf16
+    bit patterns, valid [M] uint8)."""
+    stages = _i32(stages, (-1, 16)); space = _i32(space); pre = _i32(prefix_cids, (-1,))
+    assert len(pre) >= stage
+    M, S = dense_count(space), len(stages)
+    x = np.empty((M, S, 64), np.uint16); valid = np.empty(M, np.uint8)
+    _check(lib().ovf_sequences(_p(stages), S, _p(space), _p(pre), stage, _p(x), _p(valid)))
+    return x, valid
 
 
 def plog2(x):

@@ -657,6 +657,98 @@ int ovf_score_lstm(const ovf_model *m, const float *weights, const uint16_t *x, 
   return fail ? OVF_ENOMEM : OVF_OK;
 }
 
+/* ------------------------------------------------- V(s) on a whole schedule */
+
+static int lstm_ok(const ovf_model *m) {
+  return m && m->kind == 1 && m->n_layers == 2 && m->dims[0] >= 1 && m->dims[1] >= 1 && m->dims[2] == 1 &&
+         (m->dtype == 0 || m->dtype == 1);
+}
+
+static uint16_t bf16_bits_of(float v) {
+  float r = bf16_round(v);
+  uint32_t u;
+  memcpy(&u, &r, 4);
+  return (uint16_t)(u >> 16);
+}
+
+/* The state of Section 2 as the sequence the recurrent network of Section 3.2 reads:
+ * one timestep per stage of the pipeline, in scheduling order, 64 values each.  A stage
+ * that is scheduled in the state contributes its whole core vector (intrinsic and
+ * acquired features); a stage that is not scheduled yet contributes its intrinsic block
+ * (rows 0..15) and zeros.  For candidate `cid` of decision d: stages 0..i-1 give the
+ * vectors stored when they were committed, stage i gives the candidate's vector,
+ * stages i+1.. are unscheduled.  Values are normalised and rounded to bf16. */
+static void sequence_of(const decision *d, const int32_t core[64], uint16_t *x /* [S][64] */) {
+  for (int t = 0; t < d->S; ++t) {
+    int32_t row[64];
+    memset(row, 0, sizeof row);
+    if (t < d->i) memcpy(row, d->cf + 64 * (size_t)t, sizeof row);
+    else if (t == d->i) memcpy(row, core, sizeof row);
+    else intrinsic(d->stages, d->S, t, row);
+    for (int k = 0; k < 64; ++k) x[(size_t)t * 64 + k] = bf16_bits_of(ovf_plog2(row[k]));
+  }
+}
+
+/* Sequences of every candidate state of decision `stage` (x[cid][t][k], M entries, not
+ * padded) and their validity flags.  An invalid candidate's own timestep has zeros in
+ * rows 16..63, like its feature column. */
+int ovf_sequences(const ovf_stage *stages, int S, const ovf_space *sp, const int32_t *prefix_cids,
+                  int stage, uint16_t *x, uint8_t *valid) {
+  if (!space_ok(sp) || !pipeline_ok(stages, S) || stage < 0 || stage >= S) return OVF_EINVAL;
+  int64_t M = ovf_dense_count(sp);
+  int n = stage > 0 ? stage : 1;
+  ovf_state *st = (ovf_state *)calloc((size_t)n, sizeof(ovf_state));
+  int32_t *cf = (int32_t *)calloc((size_t)n * 64, sizeof(int32_t));
+  if (!st || !cf) { free(st); free(cf); return OVF_ENOMEM; }
+  int rc = replay(stages, S, sp, prefix_cids, stage, st, cf);
+  if (rc == OVF_OK) {
+    decision d = { stages, S, sp, stage, st, cf };
+#pragma omp parallel for schedule(static)
+    for (int64_t cid = 0; cid < M; ++cid) {
+      int32_t core[64];
+      valid[cid] = (uint8_t)candidate(&d, cid, NULL, core, NULL);
+      sequence_of(&d, core, x + (size_t)cid * S * 64);
+    }
+  }
+  free(st); free(cf);
+  return rc;
+}
+
+/* V of every valid candidate state of decision d under the recurrent network: the
+ * sequences of the valid candidates, one after the other, through ovf_score_lstm.
+ * sc[cid] = +inf and ok[cid] = 0 for the others. */
+static int score_decision_lstm(const decision *d, const ovf_model *m, const float *weights,
+                               float *sc, uint8_t *ok) {
+  const int64_t M = ovf_dense_count(d->sp);
+  const int S = d->S;
+  int64_t nv = 0;
+  for (int64_t cid = 0; cid < M; ++cid) {
+    int32_t core[64];
+    ok[cid] = (uint8_t)candidate(d, cid, NULL, core, NULL);
+    sc[cid] = INFINITY;
+    nv += ok[cid];
+  }
+  if (nv == 0) return OVF_OK;
+  uint16_t *x = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)nv * S * 64);
+  float *v = (float *)malloc(sizeof(float) * (size_t)nv);
+  if (!x || !v) { free(x); free(v); return OVF_ENOMEM; }
+  int64_t k = 0;
+  for (int64_t cid = 0; cid < M; ++cid) {
+    if (!ok[cid]) continue;
+    int32_t core[64];
+    candidate(d, cid, NULL, core, NULL);
+    sequence_of(d, core, x + (size_t)k * S * 64);
+    ++k;
+  }
+  int rc = ovf_score_lstm(m, weights, x, nv, S, v);
+  k = 0;
+  if (rc == OVF_OK)
+    for (int64_t cid = 0; cid < M; ++cid)
+      if (ok[cid]) sc[cid] = v[k++];
+  free(x); free(v);
+  return rc;
+}
+
 /* ----------------------------------------------------------------- argmin */
 
 /* Inner loop of Algorithm 1 over ids [0, M) (or per consecutive block of `group`
@@ -714,8 +806,9 @@ float ovf_noise(uint64_t seed, int32_t rollout, int32_t stage, int32_t cid) {
 /* ----------------------------------------------------------------- greedy */
 
 /* Algorithm 1 over stages first..last with stages 0..first-1 already committed to
- * cids[0..first-1].  V is the MLP `m` (raw features -> normalise -> network), or the
- * callback `vfun` when it is not NULL.  forced[i] >= 0 (forced may be NULL) replaces
+ * cids[0..first-1].  V is the MLP `m` (raw features -> normalise -> network), the
+ * recurrent network `m` over the state's sequence form (model kind 1 with 64 inputs per
+ * timestep), or the callback `vfun` when it is not NULL.  forced[i] >= 0 (forced may be NULL) replaces
  * the argmin of stage i by that candidate (used to follow a GPU decision that lies
  * inside the tolerance margin); top2[i] receives the second smallest score.
  * On return cids/values/states hold s_1..s_n; a stage with no winner gets -1 / +inf
@@ -726,7 +819,8 @@ static int greedy_impl(const ovf_stage *stages, int S, const ovf_space *sp, cons
                        ovf_state *states, int64_t *n_evals, float eps, uint64_t seed, int32_t rollout) {
   if (!space_ok(sp) || !pipeline_ok(stages, S)) return OVF_EINVAL;
   if (first < 0 || last >= S || first > last + 1) return OVF_EINVAL;
-  if (!vfun && (!mlp_ok(m) || m->dims[0] != sp->F)) return OVF_EINVAL;
+  const int recurrent = !vfun && lstm_ok(m) && m->dims[0] == 64;
+  if (!vfun && !recurrent && (!mlp_ok(m) || m->dims[0] != sp->F)) return OVF_EINVAL;
   const int64_t M = ovf_dense_count(sp);
   const int F = sp->F;
   ovf_state *st = (ovf_state *)calloc((size_t)S, sizeof(ovf_state));
@@ -756,15 +850,20 @@ static int greedy_impl(const ovf_stage *stages, int S, const ovf_space *sp, cons
       if (i + k < S) intrinsic(stages, S, i + k, nb + 144 + 16 * (k - 1));
     }
     /* features of every candidate state, column-per-candidate for the scorer */
+    if (!recurrent) {
 #pragma omp parallel for schedule(static)
-    for (int64_t cid = 0; cid < M; ++cid) {
-      int32_t core[64];
-      ok[cid] = (uint8_t)candidate(&d, cid, NULL, core, NULL);
-      for (int k = 0; k < 64; ++k) xcol[(size_t)k * M + cid] = core[k];
-      if (F == 256)
-        for (int k = 0; k < 192; ++k) xcol[(size_t)(64 + k) * M + cid] = nb[k];
+      for (int64_t cid = 0; cid < M; ++cid) {
+        int32_t core[64];
+        ok[cid] = (uint8_t)candidate(&d, cid, NULL, core, NULL);
+        for (int k = 0; k < 64; ++k) xcol[(size_t)k * M + cid] = core[k];
+        if (F == 256)
+          for (int k = 0; k < 192; ++k) xcol[(size_t)(64 + k) * M + cid] = nb[k];
+      }
     }
-    if (vfun) {
+    if (recurrent) {
+      rc = score_decision_lstm(&d, m, weights, sc, ok);
+      if (rc != OVF_OK) break;
+    } else if (vfun) {
       for (int64_t cid = 0; cid < M; ++cid) {
         if (!ok[cid]) { sc[cid] = INFINITY; continue; }
         int32_t core[64];
@@ -849,8 +948,8 @@ static int beam_item_less(const void *pa, const void *pb) {
   return 0;
 }
 
-/* Beam search guided by V (Sections 3.1 and 4.1 use "a standard beam search" next to
- * the greedy scan): keep the `width` best partial schedules per layer instead of one.
+/* Beam search guided by V (the other search that Sections 3.1 and 4.1 run with the value
+ * function, next to the greedy scan): keep the `width` best partial schedules per layer instead of one.
  * Layer by layer, every kept partial schedule is extended by every valid candidate of
  * the next layer, each extension is scored by V, and the `width` smallest scores
  * survive (ties: lower parent index, then lower candidate id; +inf and NaN never
@@ -861,7 +960,8 @@ int ovf_beam(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_mode
              const float *weights, ovf_vfun vfun, void *user, int width, int32_t *cids,
              float *values, int32_t *n_beams, int64_t *n_evals) {
   if (!space_ok(sp) || !pipeline_ok(stages, S) || width < 1) return OVF_EINVAL;
-  if (!vfun && (!mlp_ok(m) || m->dims[0] != sp->F)) return OVF_EINVAL;
+  const int recurrent = !vfun && lstm_ok(m) && m->dims[0] == 64;
+  if (!vfun && !recurrent && (!mlp_ok(m) || m->dims[0] != sp->F)) return OVF_EINVAL;
   const int64_t M = ovf_dense_count(sp), Mp = ovf_padded_count(sp);
   const int F = sp->F;
   int32_t *cur = (int32_t *)malloc(sizeof(int32_t) * (size_t)width * S);
@@ -890,6 +990,18 @@ int ovf_beam(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_mode
           for (int k = 0; k < 64; ++k) core[k] = feat[(size_t)k * Mp + cid];
           sc[cid] = core[16] ? (float)vfun(user, i, (int32_t)cid, core) : INFINITY;
         }
+      } else if (recurrent) {
+        ovf_state *bst = (ovf_state *)calloc((size_t)(i > 0 ? i : 1), sizeof(ovf_state));
+        int32_t *bcf = (int32_t *)calloc((size_t)(i > 0 ? i : 1) * 64, sizeof(int32_t));
+        uint8_t *bok = (uint8_t *)malloc((size_t)M);
+        if (!bst || !bcf || !bok) rc = OVF_ENOMEM;
+        if (rc == OVF_OK) rc = replay(stages, S, sp, cur + (size_t)b * S, i, bst, bcf);
+        if (rc == OVF_OK) {
+          decision d = { stages, S, sp, i, bst, bcf };
+          rc = score_decision_lstm(&d, m, weights, sc, bok);
+        }
+        free(bst); free(bcf); free(bok);
+        if (rc != OVF_OK) break;
       } else {
         rc = ovf_score_mlp(m, weights, feat, Mp, M, sc);
         if (rc != OVF_OK) break;

@@ -166,7 +166,7 @@ __global__ __launch_bounds__(64) void k_commit(Tables t, int stage, int nparts, 
 
 // ------------------------------------------------------------ beam search
 //
-// Secs. 3.1 and 4.1 run "a standard beam search" guided by V next to the greedy scan.
+// Secs. 3.1 and 4.1 also search with a beam guided by V, next to the greedy scan.
 // The B problems of the context are the beam slots of one network.  Per layer: every
 // live slot's candidates are scored (masked scores [B][Mpad]); the B smallest of all
 // B*M scores survive, ordered by (score, parent slot, candidate id); survivor j copies
