@@ -112,7 +112,15 @@ int vf_set_pipeline(vf_ctx *ctx, const vf_stage *stages_host, int n_stages, int 
  * matrices (and w_head) to bfloat16, ties to even; biases stay fp32.
  * VF_BF16 needs every MLP width except the last to be a multiple of 32 and at most
  * 1024 (LSTM: F and H multiples of 32, at most 256).  VF_LSTM supports VF_BF16 only.
- * Anything else is VF_EINVAL. */
+ * Anything else is VF_EINVAL.
+ * Which V the search calls (vf_argmin_step, vf_greedy_schedule, vf_beam_search) accept:
+ * an MLP with dims[0] == space.F, applied to the feature column of a candidate state;
+ * or an LSTM with dims[0] == 64, applied to the state as a sequence (Sec. 3.2): one
+ * timestep per stage of the pipeline in scheduling order, a stage that is scheduled in
+ * the state (committed before, or the candidate itself) gives its 64 core features, a
+ * stage that is not gives its intrinsic block (rows 0..15) and zeros, all normalised;
+ * V = the head applied to every timestep's hidden state, summed.  Any other model is
+ * VF_EINVAL there (it can still be used with vf_score). */
 int vf_set_model(vf_ctx *ctx, const vf_model *model_host, const float *weights_dev, size_t n_floats);
 
 /* s_0 = InitialState of Algorithm 1: nothing scheduled. */

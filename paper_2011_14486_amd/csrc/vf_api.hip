@@ -80,6 +80,7 @@ bool model_ok(const vf_model *m, size_t n_floats) {
 }
 
 void free_pipeline(vf_ctx *c) {
+  vfk_seq_free(c);
   void *ps[] = {c->d_stages, c->d_intr, c->d_suffix, c->d_states, c->d_cf, c->d_prefix,
                 c->d_cids,   c->d_vals, c->d_alive,  c->d_forced, c->d_decpack};
   for (void *p : ps)
@@ -129,7 +130,21 @@ int ensure_feat(vf_ctx *c) {
 }
 
 // enumerate + featurize + score + argmin (+ commit) for one stage, all problems
+// V is defined on the states of this context's pipeline: an MLP over the feature rows of
+// the search space, or the recurrent network over 64 values per stage
+bool model_fits(const vf_ctx *c) {
+  return (c->model.kind == VF_MLP && c->model.dims[0] == c->space.F) || vfk_seq_model(c);
+}
+
 int step(vf_ctx *c, int stage, int commit, int32_t *best_cid, float *best_val) {
+  if (vfk_seq_model(c)) {
+    int nparts = 0;
+    int rc = vfk_seq_step(c, stage, nullptr, 0, stage, &nparts);
+    if (rc != VF_OK) return rc;
+    rc = vfk_commit_from_partials(c, stage, nparts, commit, best_cid, best_val);
+    if (rc == VF_OK && commit) rc = vfk_seq_advance(c, stage);
+    return rc;
+  }
   if (vfk_can_fuse_step(c)) {
     // features are produced and consumed inside one kernel and never reach HBM
     int nparts = 0;
@@ -279,6 +294,7 @@ int vf_reset_state(vf_ctx *c) {
   if (!c->has_pipeline) return VF_ESTATE;
   DeviceGuard g(c->device);
   c->n_sched = 0;
+  c->seq_stage = -1;
   return vfk_reset_state(c);
 }
 
@@ -368,7 +384,7 @@ int vf_score(vf_ctx *c, const void *x, int32_t x_kind, int64_t M, int64_t ld, in
 int vf_argmin_step(vf_ctx *c, int stage, int commit, int32_t *best_cid, float *best_val) {
   if (!c) return VF_EINVAL;
   if (!c->has_pipeline || !c->has_model) return VF_ESTATE;
-  if (c->model.kind != VF_MLP || c->model.dims[0] != c->space.F) return VF_EINVAL;
+  if (!model_fits(c)) return VF_EINVAL;
   if (stage < 0 || stage >= c->S) return VF_EINVAL;
   if (stage != c->n_sched) return VF_ESTATE;
   DeviceGuard g(c->device);
@@ -380,7 +396,7 @@ int vf_argmin_step(vf_ctx *c, int stage, int commit, int32_t *best_cid, float *b
 int vf_greedy_schedule(vf_ctx *c, int first, int last, vf_state *out_states, int32_t *out_cids, float *out_vals) {
   if (!c) return VF_EINVAL;
   if (!c->has_pipeline || !c->has_model) return VF_ESTATE;
-  if (c->model.kind != VF_MLP || c->model.dims[0] != c->space.F) return VF_EINVAL;
+  if (!model_fits(c)) return VF_EINVAL;
   if (first < 0 || last >= c->S || first > last + 1) return VF_EINVAL;
   if (first != c->n_sched) return VF_ESTATE;
   DeviceGuard g(c->device);
@@ -415,7 +431,7 @@ int vf_beam_search(vf_ctx *c, int first, int last, vf_state *out_states, int32_t
                    int32_t *n_beams) {
   if (!c) return VF_EINVAL;
   if (!c->has_pipeline || !c->has_model) return VF_ESTATE;
-  if (c->model.kind != VF_MLP || c->model.dims[0] != c->space.F) return VF_EINVAL;
+  if (!model_fits(c)) return VF_EINVAL;
   if (first < 0 || last >= c->S || first > last + 1) return VF_EINVAL;
   if (first != c->n_sched) return VF_ESTATE;
   if ((int64_t)c->B * c->Mpad >= ((int64_t)1 << 31)) return VF_EINVAL;
@@ -433,6 +449,10 @@ int vf_beam_search(vf_ctx *c, int first, int last, vf_state *out_states, int32_t
     if (rc != VF_OK) return rc;
     rc = vfk_beam_select_commit(c, i);
     if (rc != VF_OK) return rc;
+    if (vfk_seq_model(c)) {
+      rc = vfk_seq_advance_beam(c, i);  // survivors continue their parent's recurrence
+      if (rc != VF_OK) return rc;
+    }
     c->n_sched = i + 1;
   }
   const size_t n = (size_t)c->B * c->S;

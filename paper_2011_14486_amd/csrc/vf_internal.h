@@ -69,6 +69,15 @@ struct vf_ctx {
   float *d_tk_val = nullptr; int32_t *d_tk_idx = nullptr; size_t tk_elems = 0;  // chunk partials
   float *d_sel_val = nullptr; int32_t *d_sel_idx = nullptr;  // [B] survivors (value, beam*Mpad+cid)
   int32_t *d_sel_n = nullptr;    // [2]: survivors of this layer, live schedules so far
+  // recurrent value network wired to the search: per-problem tables and prefix state
+  // of the recurrence (two sets: beam search writes the survivors' state into the other)
+  float *d_seq_G = nullptr;                       // [B][S][4H] gate inputs of unscheduled stages
+  float *d_seq_h[2] = {nullptr, nullptr};         // [B][H] h of the last committed stage (bf16 values)
+  float *d_seq_c[2] = {nullptr, nullptr};         // [B][H] its cell state
+  float *d_seq_P[2] = {nullptr, nullptr};         // [B][4H] biases + W_hh h: gates of the next step
+  float *d_seq_hs[2] = {nullptr, nullptr};        // [B] head predictions summed over the committed stages
+  int seq_stage = -1;                             // committed stages folded into the state, -1: none valid
+  int seq_cur = 0;                                // which set is current
   // exploration noise added to the scores in the argmin scan of step / greedy calls
   float noise_eps = 0.0f;
   uint64_t noise_seed = 0;
@@ -156,6 +165,12 @@ int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, i
 // MLPs of uniform hidden width whose input width is the space's F).
 bool vfk_can_fuse_step(const vf_ctx *c);
 bool vfk_can_run_whole(const vf_ctx *c);
+bool vfk_seq_model(const vf_ctx *c);
+void vfk_seq_free(vf_ctx *c);
+int vfk_seq_sync(vf_ctx *c, int stage);
+int vfk_seq_advance(vf_ctx *c, int stage);
+int vfk_seq_advance_beam(vf_ctx *c, int stage);
+int vfk_seq_step(vf_ctx *c, int stage, float *scores, int64_t ld_scores, int noise_stage, int *nparts_out);
 int vfk_greedy_whole(vf_ctx *c, int first, int last);
 int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out);
 // Scores of every candidate of `stage` for all problems into d_scores [B][Mpad]; invalid

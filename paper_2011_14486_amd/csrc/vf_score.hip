@@ -24,30 +24,7 @@ namespace {
 
 #include "vf_sched_dev.h"
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-
-// float -> bfloat16 bits, round to nearest, ties to even
-__device__ __forceinline__ uint32_t bf16_bits(float v) {
-  uint32_t u = __float_as_uint(v);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-  u += 0x7fffu + ((u >> 16) & 1u);
-  return u >> 16;
-}
-__device__ __forceinline__ float bf16_val(float v) { return __uint_as_float(bf16_bits(v) << 16); }
-__device__ __forceinline__ float relu_keep_nan(float v) { return v < 0.0f ? 0.0f : v; }
-
-// (value, id) ordering of the scan: smaller value first, then smaller id; id < 0 = none
-__device__ __forceinline__ void take_min(float &v, int32_t &c, float ov, int32_t oc) {
-  if (oc >= 0 && (ov < v || (ov == v && (c < 0 || oc < c)))) { v = ov; c = oc; }
-}
-__device__ __forceinline__ void wave_min(float &v, int32_t &c) {
-  for (int off = 32; off > 0; off >>= 1) {
-    float ov = __shfl_down(v, off);
-    int32_t oc = __shfl_down(c, off);
-    take_min(v, c, ov, oc);
-  }
-}
+#include "vf_score_dev.h"
 
 // --------------------------------------------------------------- fp32 MLP
 
@@ -794,8 +771,6 @@ __global__ __launch_bounds__(256) void k_lstm_aux(const float *bih, const float 
   else if (i == 5 * H) aux[i] = bh[0];
 }
 
-__device__ __forceinline__ float sigmoid_dev(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
-__device__ __forceinline__ float tanh_dev(float z) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * z)); }
 
 // One workgroup walks NC sequences through all T steps.  Wave w owns hidden units
 // 32w..32w+31: the four gate row tiles of those units for every candidate column.
@@ -1019,6 +994,7 @@ int vfk_ensure_parts(vf_ctx *c, size_t n) {
 }
 
 void vfk_free_model(vf_ctx *c) {
+  vfk_seq_free(c);
   if (c->pm.w_f32) (void)hipFree(c->pm.w_f32);
   if (c->pm.w_pack) (void)hipFree(c->pm.w_pack);
   if (c->pm.w_stream) (void)hipFree(c->pm.w_stream);
@@ -1095,6 +1071,14 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
   // LSTM, bf16
   const int F = m.dims[0], H = m.dims[1];
   size_t npack = (size_t)4 * H * (F + H);
+  {
+    // the blob as it is, for the per-problem prefix recurrence of the wired form
+    const size_t n = npack + (size_t)9 * H + 1;
+    VF_HIP(c, hipMalloc((void **)&pm.w_f32, n * sizeof(float)));
+    pm.n_floats = n;
+    hipLaunchKernelGGL(k_copy_f32, blocks(n), dim3(256), 0, st, wdev, pm.w_f32, n, 0);
+    VF_HIP(c, hipGetLastError());
+  }
   VF_HIP(c, hipMalloc((void **)&pm.w_pack, npack * sizeof(uint16_t)));
   VF_HIP(c, hipMalloc((void **)&pm.aux, (size_t)(5 * H + 1) * sizeof(float)));
   const float *Wih = wdev, *Whh = Wih + (size_t)4 * H * F, *bih = Whh + (size_t)4 * H * H;
@@ -1160,6 +1144,7 @@ int vfk_step_scores(vf_ctx *c, int stage) {
   int rc = grow(c, c->d_scores, c->score_elems, want);
   if (rc != VF_OK) return rc;
   int nparts = 0;
+  if (vfk_seq_model(c)) return vfk_seq_step(c, stage, c->d_scores, c->Mpad, -1, &nparts);
   if (vfk_can_fuse_step(c)) return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, stage, -1, -1, -1);
   // general models: materialise the features, score, mask
   const size_t fwant = (size_t)c->B * c->space.F * c->Mpad;

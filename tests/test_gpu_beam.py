@@ -14,21 +14,34 @@ def vf():
     return pkg.load()
 
 
+def layer_scores(ovf, pipe, sp, model, w, pre, i):
+    """The checker's V of every candidate state of decision i after prefix `pre`:
+    (scores float64 [M], valid [M]) for either kind of value network."""
+    M = ovf.dense_count(sp)
+    if model[0] == I.LSTM:
+        x, valid = ovf.sequences(pipe, sp, list(pre), i)
+        sc = np.full(M, np.inf)
+        ids = np.flatnonzero(valid)
+        if len(ids):
+            sc[ids] = ovf.score_lstm(model, w, x[ids])
+        return sc, valid.astype(bool)
+    feat = ovf.featurize(pipe, sp, list(pre), i)
+    return ovf.score_mlp(model, w, feat, M=M).astype(np.float64), feat[16, :M] != 0
+
+
 def check_beam(ovf, pipe, sp, model, w, run, K, tol):
     """Layer by layer (run(last) = the GPU search stopped after layer `last`): the checker
     scores every extension of the GPU's survivors of the layer before; the GPU's survivors
     of this layer must be the smallest ones (up to the score tolerance at the cut), in
     order, with matching values and state records."""
     S = len(pipe)
-    M = ovf.dense_count(sp)
     prev, vals_prev = [()], [np.zeros(0, np.float32)]
     for i in range(S):
         cids, vals, states, n_beams = run(i)
         items = []
         for b, pre in enumerate(prev):
-            feat = ovf.featurize(pipe, sp, list(pre), i)
-            sc = ovf.score_mlp(model, w, feat, M=M).astype(np.float64)
-            for c in np.flatnonzero(feat[16, :M]):
+            sc, valid = layer_scores(ovf, pipe, sp, model, w, pre, i)
+            for c in np.flatnonzero(valid):
                 if sc[c] < np.inf:
                     items.append((sc[c], b, int(c)))
         items.sort()
