@@ -76,6 +76,7 @@ struct vf_ctx {
   float *d_seq_c[2] = {nullptr, nullptr};         // [B][H] its cell state
   float *d_seq_P[2] = {nullptr, nullptr};         // [B][4H] biases + W_hh h: gates of the next step
   float *d_seq_hs[2] = {nullptr, nullptr};        // [B] head predictions summed over the committed stages
+  int32_t *d_seq_list = nullptr, *d_seq_count = nullptr;  // [B][Mpad] valid ids of the decision, [B] their number
   int seq_stage = -1;                             // committed stages folded into the state, -1: none valid
   int seq_cur = 0;                                // which set is current
   // exploration noise added to the scores in the argmin scan of step / greedy calls

@@ -114,6 +114,45 @@ __global__ __launch_bounds__(256) void k_seq_advance(Tables t, int stage, SeqWei
   }
 }
 
+// The valid candidates of decision (problem b, stage), in ascending id order:
+// list[b][0..count[b]).  The recurrent network costs one cell step per remaining stage and
+// candidate, so the scoring kernel works on this dense list instead of the id range, where
+// valid and invalid ids are interleaved.  Also fills the masked score array (nullable)
+// with +inf: the scorer then only writes the candidates' entries.
+__global__ __launch_bounds__(1024) void k_seq_compact(const uint32_t *decpack, uint32_t M, int64_t Mpad, int32_t *list,
+                                                      int32_t *count, float *scores) {
+  __shared__ DecPack pk;
+  __shared__ int wsum[16];
+  __shared__ int base;
+  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  if (tid < VF_DECPACK_DWORDS) reinterpret_cast<uint32_t *>(&pk)[tid] = decpack[(size_t)b * VF_DECPACK_DWORDS + tid];
+  if (tid == 0) base = 0;
+  __syncthreads();
+  for (uint32_t c0 = 0; c0 < (uint32_t)Mpad; c0 += 1024u) {
+    const uint32_t cid = c0 + tid;
+    bool ok = false;
+    if (cid < M && !range_closed(pk.d, pk.sp, c0, c0 + 1024u < M ? c0 + 1024u : M)) {
+      uint32_t dec;
+      ok = eval_candidate<false>(pk.d, pk.sp, cid, dec, nullptr);
+    }
+    if (scores && cid < (uint32_t)Mpad) scores[(size_t)b * Mpad + cid] = __builtin_inff();
+    const unsigned long long m = __ballot(ok);
+    if (lane == 0) wsum[w] = __popcll(m);
+    __syncthreads();
+    int off = base;
+    for (int k = 0; k < w; ++k) off += wsum[k];
+    if (ok) list[(size_t)b * Mpad + off + __popcll(m & ((1ull << lane) - 1ull))] = (int32_t)cid;
+    __syncthreads();
+    if (tid == 0) {
+      int tot = 0;
+      for (int k = 0; k < 16; ++k) tot += wsum[k];
+      base += tot;
+    }
+    __syncthreads();
+  }
+  if (tid == 0) count[b] = base;
+}
+
 struct SeqDev {
   int H, S;
   const uint16_t *w_pack;  // [unit tile][k step][gate][lane][8]; 4 k-steps of x, then H/16 of h
@@ -123,11 +162,14 @@ struct SeqDev {
   const float *cpre;       // [B][H]
   const float *hsum;       // [B]
   const uint32_t *decpack; // [B][VF_DECPACK_DWORDS]
+  const int32_t *list;     // [B][Mpad] valid candidate ids of the decision, ascending
+  const int32_t *count;    // [B]
+  int64_t Mpad;
   unsigned long long *stat;
 };
 
-// Workgroup = NC candidates of decision `stage` of problem blockIdx.y: enumerate and
-// featurize them, one cell step on their features from the problem's prefix state, one
+// Workgroup = NC consecutive entries of the valid-candidate list of decision `stage` of
+// problem blockIdx.y: featurize them, one cell step on their features from the problem's prefix state, one
 // step per later stage, the head's sum, the tile's first minimum.  Wave w owns hidden
 // units 32w..32w+31 (their four gate row tiles); c lives in registers, h goes through
 // LDS as bf16, double-buffered; the weight fragments of a step are one contiguous stream
@@ -146,6 +188,7 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
   float *red = gls + 2 * H4;                                            // [8][NC]
   float *whs = red + 8 * NC;                                            // [H]
   int32_t *okf = reinterpret_cast<int32_t *>(whs + H);                  // [NC]
+  int32_t *cids = okf + NC;                                             // [NC] candidate id of each column
   __shared__ DecPack pk;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -158,59 +201,54 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
     reinterpret_cast<uint32_t *>(&pk)[tid] = md.decpack[(size_t)b * VF_DECPACK_DWORDS + tid];
   __syncthreads();
 
-  const int64_t nend = (n0 + NC < M) ? n0 + NC : M;
-  const bool closed = range_closed(pk.d, pk.sp, (uint32_t)n0, (uint32_t)(nend > n0 ? nend : n0));
-  int any_valid = 0;
-  if (!closed) {
-    // four threads per candidate, each producing 16 of the 64 core rows
-    bool valid = false;
-    if (tid < 4 * NC) {
-      const int n = tid % NC, part = tid / NC;
-      const uint32_t cid = (uint32_t)(n0 + n);
-      const bool inb = (int64_t)cid < M;
-      int32_t core[64];
-      uint32_t dec;
-      // the parts a thread does not store are dead code in its copy of the evaluation
-      auto put = [&](const int32_t *v, int row0) {
-        uint4 q0, q1;
-        q0.x = pack_bf16(plog2_dev(v[0]), plog2_dev(v[1]));
-        q0.y = pack_bf16(plog2_dev(v[2]), plog2_dev(v[3]));
-        q0.z = pack_bf16(plog2_dev(v[4]), plog2_dev(v[5]));
-        q0.w = pack_bf16(plog2_dev(v[6]), plog2_dev(v[7]));
-        q1.x = pack_bf16(plog2_dev(v[8]), plog2_dev(v[9]));
-        q1.y = pack_bf16(plog2_dev(v[10]), plog2_dev(v[11]));
-        q1.z = pack_bf16(plog2_dev(v[12]), plog2_dev(v[13]));
-        q1.w = pack_bf16(plog2_dev(v[14]), plog2_dev(v[15]));
-        if (!inb) q0 = q1 = make_uint4(0u, 0u, 0u, 0u);
-        uint4 *dst = reinterpret_cast<uint4 *>(xs + (size_t)n * XLD + row0);
-        dst[0] = q0;
-        dst[1] = q1;
-      };
-      if (part == 0) {
-        valid = inb && eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
-        okf[n] = valid;
-        put(core, 0);
-      } else if (part == 1) {
-        eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
-        put(core + 16, 16);
-      } else if (part == 2) {
-        eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
-        put(core + 32, 32);
-      } else {
-        eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
-        put(core + 48, 48);
-      }
-    }
-    any_valid = __syncthreads_or(valid ? 1 : 0);
-  }
-  if (!any_valid) {
-    // no candidate here: nothing for the network to do
-    if (scores && tid < NC && (n0 + tid) < ld_scores) scores[(size_t)b * ld_scores + n0 + tid] = __builtin_inff();
+  const int nvalid = md.count[b];
+  if (n0 >= nvalid) {
+    // past the end of the list: nothing for the network to do
     if (tid == 0) {
       pval[slot] = __builtin_inff();
       pidx[slot] = -1;
     }
     return;
+  }
+  // four threads per candidate, each producing 16 of the 64 core rows
+  if (tid < NC) cids[tid] = (n0 + tid) < nvalid ? md.list[(size_t)b * md.Mpad + n0 + tid] : -1;
+  if (tid < 4 * NC) {
+    const int n = tid % NC, part = tid / NC;
+    const bool inb = (n0 + n) < nvalid;
+    const uint32_t cid = inb ? (uint32_t)md.list[(size_t)b * md.Mpad + n0 + n] : 0u;
+    int32_t core[64];
+    uint32_t dec;
+    // the parts a thread does not store are dead code in its copy of the evaluation
+    auto put = [&](const int32_t *v, int row0) {
+      uint4 q0, q1;
+      q0.x = pack_bf16(plog2_dev(v[0]), plog2_dev(v[1]));
+      q0.y = pack_bf16(plog2_dev(v[2]), plog2_dev(v[3]));
+      q0.z = pack_bf16(plog2_dev(v[4]), plog2_dev(v[5]));
+      q0.w = pack_bf16(plog2_dev(v[6]), plog2_dev(v[7]));
+      q1.x = pack_bf16(plog2_dev(v[8]), plog2_dev(v[9]));
+      q1.y = pack_bf16(plog2_dev(v[10]), plog2_dev(v[11]));
+      q1.z = pack_bf16(plog2_dev(v[12]), plog2_dev(v[13]));
+      q1.w = pack_bf16(plog2_dev(v[14]), plog2_dev(v[15]));
+      if (!inb) q0 = q1 = make_uint4(0u, 0u, 0u, 0u);
+      uint4 *dst = reinterpret_cast<uint4 *>(xs + (size_t)n * XLD + row0);
+      dst[0] = q0;
+      dst[1] = q1;
+    };
+    if (part == 0) {
+      // evaluated for padding columns too: core must be defined before put reads it
+      const bool okc = eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
+      okf[n] = inb && okc;
+      put(core, 0);
+    } else if (part == 1) {
+      eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
+      put(core + 16, 16);
+    } else if (part == 2) {
+      eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
+      put(core + 32, 32);
+    } else {
+      eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
+      put(core + 48, 48);
+    }
   }
 
   const bool active = w < H / 32;
@@ -345,18 +383,18 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
 #pragma unroll
     for (int g = 0; g < 8; ++g) s += red[g * NC + tid];
     const bool ok = okf[tid] != 0;
-    if (scores && (n0 + tid) < ld_scores) scores[(size_t)b * ld_scores + n0 + tid] = ok ? s : __builtin_inff();
-    if (na.eps != 0.0f) s = add_noise(na, s, b, (int32_t)(n0 + tid));
+    const int32_t cid = cids[tid];
+    if (scores && ok) scores[(size_t)b * ld_scores + cid] = s;
+    if (na.eps != 0.0f) s = add_noise(na, s, b, cid);
     float v = __builtin_inff();
     int32_t c = -1;
-    if (ok && s < v) { v = s; c = (int32_t)(n0 + tid); }
+    if (ok && s < v) { v = s; c = cid; }
     wave_min(v, c);
     if (md.stat) {
-      const int nvalid = __popcll(__ballot(ok));
-      const int nin = __popcll(__ballot((n0 + tid) < M));
+      const int nok = __popcll(__ballot(ok));
       if (lane == 0) {
-        atomicAdd(&md.stat[0], (unsigned long long)nin);
-        atomicAdd(&md.stat[1], (unsigned long long)nvalid);
+        atomicAdd(&md.stat[0], (unsigned long long)nok);
+        atomicAdd(&md.stat[1], (unsigned long long)nok);
       }
     }
     if (tid == 0) {
@@ -394,10 +432,12 @@ bool vfk_seq_model(const vf_ctx *c) {
 
 void vfk_seq_free(vf_ctx *c) {
   void *ps[] = {c->d_seq_G, c->d_seq_h[0], c->d_seq_h[1], c->d_seq_c[0], c->d_seq_c[1],
-                c->d_seq_P[0], c->d_seq_P[1], c->d_seq_hs[0], c->d_seq_hs[1]};
+                c->d_seq_P[0], c->d_seq_P[1], c->d_seq_hs[0], c->d_seq_hs[1], c->d_seq_list, c->d_seq_count};
   for (void *p : ps)
     if (p) (void)hipFree(p);
   c->d_seq_G = nullptr;
+  c->d_seq_list = nullptr;
+  c->d_seq_count = nullptr;
   for (int k = 0; k < 2; ++k) c->d_seq_h[k] = c->d_seq_c[k] = c->d_seq_P[k] = c->d_seq_hs[k] = nullptr;
   c->seq_stage = -1;
   c->seq_cur = 0;
@@ -416,12 +456,15 @@ int vfk_seq_sync(vf_ctx *c, int stage) {
         {&c->d_seq_c[0], (size_t)B * H}, {&c->d_seq_c[1], (size_t)B * H},
         {&c->d_seq_P[0], (size_t)B * 4 * H}, {&c->d_seq_P[1], (size_t)B * 4 * H},
         {&c->d_seq_hs[0], (size_t)B}, {&c->d_seq_hs[1], (size_t)B}};
-    for (auto &wt : want)
-      if (hipMalloc((void **)wt.p, wt.n * sizeof(float)) != hipSuccess) {
-        (void)hipGetLastError();
-        vfk_seq_free(c);
-        return VF_ENOMEM;
-      }
+    bool ok = true;
+    for (auto &wt : want) ok = ok && hipMalloc((void **)wt.p, wt.n * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->d_seq_list, (size_t)B * c->Mpad * 4) == hipSuccess;
+    ok = ok && hipMalloc((void **)&c->d_seq_count, (size_t)B * 4) == hipSuccess;
+    if (!ok) {
+      (void)hipGetLastError();
+      vfk_seq_free(c);
+      return VF_ENOMEM;
+    }
     const size_t n = (size_t)B * S * 4 * H;
     hipLaunchKernelGGL(k_seq_tables, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, c->d_intr, sw,
                        (size_t)B * S, c->d_seq_G);
@@ -484,14 +527,18 @@ int vfk_seq_step(vf_ctx *c, int stage, float *scores, int64_t ld_scores, int noi
   md.H = H; md.S = c->S; md.w_pack = c->pm.w_pack; md.aux = c->pm.aux;
   md.G = c->d_seq_G; md.P = s.P; md.cpre = s.cpre; md.hsum = s.hsum;
   md.decpack = c->d_decpack;
+  md.list = c->d_seq_list; md.count = c->d_seq_count; md.Mpad = c->Mpad;
   md.stat = c->profiling ? c->d_stat : nullptr;
+  hipLaunchKernelGGL(k_seq_compact, dim3((unsigned)c->B), dim3(1024), 0, c->stream, c->d_decpack, (uint32_t)c->M,
+                     (int64_t)c->Mpad, c->d_seq_list, c->d_seq_count, scores);
+  VF_HIP(c, hipGetLastError());
   NoiseArgs na;
   na.eps = noise_stage >= 0 ? c->noise_eps : 0.0f;
   na.k0 = (uint32_t)c->noise_seed; na.k1 = (uint32_t)(c->noise_seed >> 32);
   na.stage = noise_stage; na.first_rollout = c->noise_first;
   const int hld = H + 8;
   const size_t smem = (size_t)NC * 72 * 2 + (size_t)2 * NC * hld * 2 + (size_t)2 * 4 * H * 4 + (size_t)8 * NC * 4 +
-                      (size_t)H * 4 + (size_t)NC * 4;
+                      (size_t)H * 4 + (size_t)2 * NC * 4;
   {
     vf_prof_scope prof(c, VF_PROF_SCORE);
     void (*kern)(SeqDev, int, int64_t, float *, int64_t, float *, int32_t *, NoiseArgs) = k_seq_step<NC, 2>;

@@ -520,8 +520,9 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
         dst[1] = q1;
       };
       if (part == 0) {
-        const bool valid = inb && eval_candidate<true>(dctx, sp, cid, dec, core);
-        okf[n] = valid;
+        // evaluated for padding ids too: core must be defined before put reads it
+        const bool valid = eval_candidate<true>(dctx, sp, cid, dec, core);
+        okf[n] = inb && valid;
         put(core, 0);
       } else if (part == 1) {
         eval_candidate<true>(dctx, sp, cid, dec, core);
