@@ -30,6 +30,11 @@ struct vf_packed_model {
   uint16_t *w_stream = nullptr;
   size_t wave_stride = 0;          // 16-byte units between the streams of two waves
   int fast_rt = 0;
+  // 256 input rows: rows 64..255 do not depend on the candidate.  The stream with the
+  // first layer cut to the 64 core rows, and the other 192 rows' first-layer weights
+  uint16_t *w_stream_fold = nullptr;
+  size_t wave_stride_fold = 0;
+  uint32_t *w1_fold = nullptr;     // [96][dims[1]] bf16 pairs
 };
 
 struct vf_ctx {

@@ -350,7 +350,7 @@ static_assert(sizeof(DecPack) == VF_DECPACK_DWORDS * 4, "DecPack size");
 // the decision for `stage` - its derived loop structure, its 64 core features, the
 // running sums - or, when there is no valid winner, ends that problem's schedule.
 // d / sp are the decision context of (b, stage).
-[[maybe_unused]] __device__ __attribute__((noinline)) void commit_winner(const Tables &t, const Dec &d, const vf_space &sp, int b, int stage,
+[[maybe_unused]] __device__ __forceinline__ void commit_winner(const Tables &t, const Dec &d, const vf_space &sp, int b, int stage,
                                                int32_t c, float v, uint32_t M, bool forced) {
   const int S = t.S;
   const size_t row = (size_t)b * S + stage;
@@ -382,6 +382,14 @@ static_assert(sizeof(DecPack) == VF_DECPACK_DWORDS * 4, "DecPack size");
     pre[2] = sadd((uint32_t)pre[0], (uint32_t)core[40]);
     pre[3] = sadd((uint32_t)pre[1], (uint32_t)core[50]);
   }
+}
+
+// The same as a real call, for kernels whose main loop should not carry the registers of
+// an inlined copy.
+[[maybe_unused]] __device__ __attribute__((noinline)) void commit_winner_call(const Tables &t, const Dec &d,
+                                                                            const vf_space &sp, int b, int stage,
+                                                                            int32_t c, float v, uint32_t M) {
+  commit_winner(t, d, sp, b, stage, c, v, M, false);
 }
 
 // Builds the pack for (problem b, stage) in LDS and copies it to out[b].

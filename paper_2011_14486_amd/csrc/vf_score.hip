@@ -355,6 +355,8 @@ struct FastDev {
   int naux;                // floats in aux (biases of all layers, output vector)
   size_t bias_off[8];
   size_t wl_off;
+  int k0;                  // k-steps of the first layer present in w_stream
+  const uint32_t *w1_fold; // nullable: first-layer weights of input rows 64..255 as bf16 pairs [96][dims[1]]
 };
 
 // Stream order for k_mlp_fast: wave w's fragments of all hidden layers back to back,
@@ -362,6 +364,7 @@ struct FastDev {
 // w + 8 r; `pad` zero steps follow so that the prefetch never leaves the buffer.
 __global__ __launch_bounds__(256) void k_pack_stream(const float *blob, FastDev md, int RT, int steps_total,
                                                      int pad, uint16_t *out) {
+  // md.k0: only the first md.k0 k-steps of the first layer are packed
   const size_t per_wave = (size_t)(steps_total + pad) * RT * 512;
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= per_wave * 8) return;
@@ -375,7 +378,7 @@ __global__ __launch_bounds__(256) void k_pack_stream(const float *blob, FastDev 
   if (step < steps_total) {
     size_t off = 0;
     for (int l = 0; l < md.L - 1; ++l) {
-      const int K = md.dims[l], N = md.dims[l + 1], ksteps = K / 16;
+      const int K = md.dims[l], N = md.dims[l + 1], ksteps = l == 0 ? md.k0 : K / 16;
       if (step < ksteps) {
         const int row = (w + 8 * r) * 32 + (lane & 31), k = step * 16 + 8 * (lane >> 5) + e;
         v = (uint16_t)bf16_bits(blob[off + (size_t)row * K + k]);
@@ -386,6 +389,16 @@ __global__ __launch_bounds__(256) void k_pack_stream(const float *blob, FastDev 
     }
   }
   out[i] = v;
+}
+
+// First-layer weights of the input rows that are the same for every candidate of a
+// decision (rows 64..255: the neighbour stages), as bf16 pairs, input-row-major, so that
+// one thread per output unit reads them coalesced: out[q][r] = (W[r][64+2q], W[r][65+2q]).
+__global__ __launch_bounds__(256) void k_pack_fold(const float *W, int K, int N, uint32_t *out) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= 96 * N) return;
+  const int q = i / N, r = i % N;
+  out[i] = bf16_bits(W[(size_t)r * K + 64 + 2 * q]) | (bf16_bits(W[(size_t)r * K + 65 + 2 * q]) << 16);
 }
 
 // Fused MLP for hidden layers of exactly 256*RT units: every wave owns RT row tiles
@@ -424,7 +437,13 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   float *red = reinterpret_cast<float *>(smem + (size_t)NC * ks * 2);   // [8][NC]
   int32_t *okf = reinterpret_cast<int32_t *>(red + 8 * NC);             // [NC]
   float *auxs = reinterpret_cast<float *>(okf + NC);                    // [naux] biases, output vector
+  float *b1s = auxs + ((md.naux + 3) & ~3);                             // [dims[1]] folded first-layer bias
   __shared__ DecPack pk;
+  // GEN with 256 input rows: rows 64..255 are the same for all candidates of a decision
+  // (neighbour stages), so their part of the first layer is a per-decision bias and the
+  // contraction runs over the 64 core rows only
+  const bool fold = GEN && md.w1_fold != nullptr;
+  int b1_p = -1;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -462,6 +481,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   if (WHOLE) {
     fill_decpack(pk, wa.t, unit, stage);
     cur_p = unit;
+    b1_p = -1;
     t_begin = unit * nparts;
     t_end = t_begin + nparts;
     na.stage = stage;
@@ -490,6 +510,20 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       }
       __syncthreads();  // the next tile may bring another problem's context
       continue;
+    }
+    if (fold && b1_p != p) {
+      const int N1 = md.dims[1];
+      for (int r = tid; r < N1; r += 512) {
+        float acc = auxs[md.bias_off[0] + r];
+#pragma unroll 8
+        for (int q = 0; q < 96; ++q) {
+          const uint32_t wv = md.w1_fold[(size_t)q * N1 + r], xv = pk.nbh[q];
+          acc = fmaf(__uint_as_float(wv << 16), __uint_as_float(xv << 16), acc);
+          acc = fmaf(__uint_as_float(wv & 0xffff0000u), __uint_as_float(xv & 0xffff0000u), acc);
+        }
+        b1s[r] = acc;
+      }
+      b1_p = p;
     }
     // ---- enumerate + featurize the tile: thread n < NC owns candidate n0 + n
     const Dec &dctx = pk.d;
@@ -535,7 +569,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
         put(core + 48, 48);
       }
     }
-    if (F == 256) {
+    if (F == 256 && !fold) {
       // the 192 neighbour rows are the same for every candidate id below M
       const int n = tid % NC, part = tid / NC;
       const bool inb = (n0 + n) < M;
@@ -586,9 +620,9 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
   const uint16_t *brow = act + (size_t)(lane & 31) * ks + 8 * (lane >> 5);
   for (int l = 0; l < NH; ++l) {
-    const int ksteps = md.dims[l] / 16;
+    const int ksteps = l == 0 ? md.k0 : md.dims[l] / 16;
     // the accumulators start from the bias of their output row
-    const float *bias = auxs + md.bias_off[l];
+    const float *bias = (l == 0 && fold) ? b1s : auxs + md.bias_off[l];
     floatx16 acc[RT][CT];
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
@@ -732,7 +766,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   if (WHOLE) {
     // s_i := the winner; the tables it updates are read back by this same workgroup
     // when it builds the next stage's context
-    if (tid == 0) commit_winner(wa.t, pk.d, pk.sp, unit, stage, run_c, run_v, (uint32_t)M, false);
+    if (tid == 0) commit_winner_call(wa.t, pk.d, pk.sp, unit, stage, run_c, run_v, (uint32_t)M);
     __threadfence();
     __syncthreads();
   }
@@ -999,6 +1033,8 @@ void vfk_free_model(vf_ctx *c) {
   if (c->pm.w_f32) (void)hipFree(c->pm.w_f32);
   if (c->pm.w_pack) (void)hipFree(c->pm.w_pack);
   if (c->pm.w_stream) (void)hipFree(c->pm.w_stream);
+  if (c->pm.w_stream_fold) (void)hipFree(c->pm.w_stream_fold);
+  if (c->pm.w1_fold) (void)hipFree(c->pm.w1_fold);
   if (c->pm.aux) (void)hipFree(c->pm.aux);
   c->pm = vf_packed_model();
 }
@@ -1062,10 +1098,27 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
       FastDev fd;
       fd.L = L;
       for (int l = 0; l < 8; ++l) fd.dims[l] = m.dims[l];
+      fd.k0 = m.dims[0] / 16;
       hipLaunchKernelGGL(k_pack_stream, blocks(per_wave * 8), dim3(256), 0, st, wdev, fd, rt, steps, pad, pm.w_stream);
       VF_HIP(c, hipGetLastError());
       pm.wave_stride = per_wave / 8;
       pm.fast_rt = rt;
+      if (m.dims[0] == 256) {
+        // the same stream with the first layer cut down to the 64 core rows, and the rest of
+        // the first layer on its own, for the scorer that generates its candidates
+        const int fsteps = steps - (m.dims[0] / 16 - 4);
+        const size_t per_wave_f = (size_t)(fsteps + pad) * rt * 512;
+        VF_HIP(c, hipMalloc((void **)&pm.w_stream_fold, per_wave_f * 8 * sizeof(uint16_t)));
+        fd.k0 = 4;
+        hipLaunchKernelGGL(k_pack_stream, blocks(per_wave_f * 8), dim3(256), 0, st, wdev, fd, rt, fsteps, pad,
+                           pm.w_stream_fold);
+        VF_HIP(c, hipGetLastError());
+        pm.wave_stride_fold = per_wave_f / 8;
+        VF_HIP(c, hipMalloc((void **)&pm.w1_fold, (size_t)96 * m.dims[1] * sizeof(uint32_t)));
+        hipLaunchKernelGGL(k_pack_fold, blocks((size_t)96 * m.dims[1]), dim3(256), 0, st, wdev, m.dims[0], m.dims[1],
+                           pm.w1_fold);
+        VF_HIP(c, hipGetLastError());
+      }
     }
     return VF_OK;
   }
@@ -1242,7 +1295,16 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     fd.w_stream = reinterpret_cast<const uint4 *>(c->pm.w_stream);
     fd.wave_stride = c->pm.wave_stride; fd.aux = c->pm.aux; fd.wl_off = c->pm.aux_off[7];
     fd.naux = (int)(c->pm.aux_off[7] + m.dims[L - 1]);
-    const size_t smem_fast = smem + (size_t)fd.naux * 4;
+    fd.k0 = m.dims[0] / 16;
+    fd.w1_fold = nullptr;
+    size_t smem_fast = smem + (size_t)fd.naux * 4;
+    if (gen_stage >= 0 && c->pm.w_stream_fold) {
+      fd.w_stream = reinterpret_cast<const uint4 *>(c->pm.w_stream_fold);
+      fd.wave_stride = c->pm.wave_stride_fold;
+      fd.k0 = 4;
+      fd.w1_fold = c->pm.w1_fold;
+      smem_fast = smem + (size_t)((fd.naux + 3) & ~3) * 4 + (size_t)m.dims[1] * 4;
+    }
     // persistent: at most one workgroup per CU, each walking its share of the tiles
     int ncu = 256;
     (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
