@@ -289,13 +289,20 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
     float4 gnext = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     if (fetch_g) gnext = reinterpret_cast<const float4 *>(md.G + ((size_t)b * S + t + 1) * H4)[tid];
 
+    // the accumulators start from the step's gate biases (staged in LDS one step ahead)
+    const float *bias = gls + (size_t)(k & 1) * H4;
     floatx16 acc[4][CT];
 #pragma unroll
     for (int g = 0; g < 4; ++g)
 #pragma unroll
-      for (int c = 0; c < CT; ++c)
+      for (int q = 0; q < 4; ++q) {
+        const float4 bv = *reinterpret_cast<const float4 *>(bias + g * H + wu * 32 + 4 * (lane >> 5) + 8 * q);
 #pragma unroll
-        for (int j = 0; j < 16; ++j) acc[g][c][j] = 0.0f;
+        for (int c = 0; c < CT; ++c) {
+          acc[g][c][4 * q + 0] = bv.x; acc[g][c][4 * q + 1] = bv.y;
+          acc[g][c][4 * q + 2] = bv.z; acc[g][c][4 * q + 3] = bv.w;
+        }
+      }
 
     const uint16_t *src = (k == 0) ? xs : hs + (size_t)(k & 1) * NC * hld;
     const int ld = (k == 0) ? XLD : hld;
@@ -333,29 +340,22 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
     }
     if (fetch_g) reinterpret_cast<float4 *>(gls + (size_t)((k + 1) & 1) * H4)[tid] = gnext;
 
-    const float *bias = gls + (size_t)(k & 1) * H4;
     uint16_t *hout = hs + (size_t)((k + 1) & 1) * NC * hld;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int u0 = wu * 32 + 4 * (lane >> 5) + 8 * q;
       const float4 whv = *reinterpret_cast<const float4 *>(whs + u0);
-      const float4 bi = *reinterpret_cast<const float4 *>(bias + u0);
-      const float4 bf = *reinterpret_cast<const float4 *>(bias + H + u0);
-      const float4 bg = *reinterpret_cast<const float4 *>(bias + 2 * H + u0);
-      const float4 bo = *reinterpret_cast<const float4 *>(bias + 3 * H + u0);
       const float whq[4] = {whv.x, whv.y, whv.z, whv.w};
-      const float biq[4] = {bi.x, bi.y, bi.z, bi.w}, bfq[4] = {bf.x, bf.y, bf.z, bf.w};
-      const float bgq[4] = {bg.x, bg.y, bg.z, bg.w}, boq[4] = {bo.x, bo.y, bo.z, bo.w};
 #pragma unroll
       for (int c = 0; c < CT; ++c) {
         float hv[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int j = 4 * q + e;
-          const float ig = sigmoid_dev(acc[0][c][j] + biq[e]);
-          const float fg = sigmoid_dev(acc[1][c][j] + bfq[e]);
-          const float gg = tanh_dev(acc[2][c][j] + bgq[e]);
-          const float og = sigmoid_dev(acc[3][c][j] + boq[e]);
+          const float ig = sigmoid_dev(acc[0][c][j]);
+          const float fg = sigmoid_dev(acc[1][c][j]);
+          const float gg = tanh_dev(acc[2][c][j]);
+          const float og = sigmoid_dev(acc[3][c][j]);
           const float cn = fg * cst[c][j] + ig * gg;
           cst[c][j] = cn;
           hv[e] = og * tanh_dev(cn);
