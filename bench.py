@@ -22,8 +22,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at batch 256, scaled by a
 # plain 1 GiB copy (profiles/*_hbm_counters.txt); only valid for the default batch, and to be
 # set to None whenever the kernel changes without the counters being taken again
-TRAFFIC_SCORE_BYTES = {}
-TRAFFIC_FEATURIZE_BYTES = {256: 4.49e6 + 1073741824.0}
+TRAFFIC_SCORE_BYTES = {256: 6118.2 * 1024 * 2.0 + 26834.3 * 1024}
+TRAFFIC_FEATURIZE_BYTES = {256: 2202.1 * 1024 * 2.0 + 1073741824.0}
 
 
 def mlp_flops(dims):
@@ -137,7 +137,7 @@ def main():
     flops_per_launch = fused_mlp_flops(dims) * scored / max(n_score, 1)
     score_ms = ms_score / max(n_score, 1)
     achieved = flops_per_launch / (score_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_mlp_fast<128,2,4,gen> (enumerate+featurize+MLP+argmin fused)", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+    roofline = {"bound": "mfma", "kernel": "k_mlp_fast<128,2,4,gen,whole> (Algorithm 1 per problem in one workgroup: enumerate+featurize+MLP+argmin+commit)", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_SCORE_BYTES.get(B),
                 "flops_per_candidate_executed": fused_mlp_flops(dims), "flops_per_candidate_model": mlp_flops(dims),
                 "launch_ms": score_ms, "launches": n_score}
@@ -195,6 +195,36 @@ def main():
         mb_ms = (time.perf_counter() - t1) / 5 * 1e3
         vf.vf_destroy(ctx5)
 
+    # the paper's own kind of V (Sec. 3.2): LSTM 64 -> 256 over one timestep per stage, head
+    # summed, guiding the same greedy scan on a smaller batch of the same pipelines
+    lstm = None
+    if not args.no_latency:
+        Bl, H = min(B, 64), 256
+        ctxl = vf.vf_create(0)
+        vf.vf_set_space(ctxl, space); vf.vf_set_pipeline(ctxl, pipes[:Bl])
+        vf.vf_set_model(ctxl, I.model_record(I.LSTM, [64, H, 1], I.BF16), I.lstm_weights(64, H, 0))
+        vf.vf_profile_enable(ctxl, True); vf.vf_profile_counts(ctxl)
+        flops_l, valid_l = 0, 0
+        for i in range(S):     # per-layer counts: a candidate of layer i costs S - i cell steps
+            vf.vf_argmin_step(ctxl, i, True)
+            sc_i, va_i = vf.vf_profile_counts(ctxl)
+            flops_l += sc_i * (2 * 4 * H * 64 + (S - 1 - i) * 2 * 4 * H * H)
+            valid_l += va_i
+        vf.vf_profile_enable(ctxl, False)
+        for k in (0, 1, 2):
+            vf.vf_profile_read(ctxl, k)
+        vf.vf_reset_state(ctxl); vf.vf_greedy_schedule(ctxl)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(3):
+            vf.vf_reset_state(ctxl); vf.vf_greedy_schedule(ctxl)
+        torch.cuda.synchronize()
+        dtl = (time.perf_counter() - t1) / 3
+        lstm = {"model": f"LSTM 64-{H}-1 bf16 over {S} timesteps", "batch": Bl, "ms_per_step": dtl * 1e3,
+                "valid_candidates_per_s": valid_l / dtl, "mfma_tflops": flops_l / dtl / 1e12,
+                "mfma_frac": flops_l / dtl / 1e12 / PEAK_BF16_TFLOPS}
+        vf.vf_destroy(ctxl)
+
     line = {
         "metric": "candidate schedules scored/sec (V(s) eval) + end-to-end greedy schedule ms",
         "value": value, "unit": "candidates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -209,6 +239,7 @@ def main():
         "candidate_ids_per_s": ids_per_step * args.steps / dt,
         "greedy_ms_single_pipeline": single_ms,
         "greedy_ms_mobilenetv2_100_stages_16384_candidates": mb_ms,
+        "greedy_with_recurrent_network": lstm,
         "kernel_ms_per_step": {"featurize": ms_feat / args.steps, "score": ms_score / args.steps,
                                "commit": ms_commit / args.steps},
         "roofline": roofline,

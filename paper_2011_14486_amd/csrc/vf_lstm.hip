@@ -86,9 +86,19 @@ __global__ __launch_bounds__(256) void k_seq_advance(Tables t, int stage, SeqWei
   }
   if (tid < 64) x[tid] = bf16_val(plog2_dev(t.cf[((size_t)b * S + stage) * 64 + tid]));
   __syncthreads();
-  for (int r = w; r < H4; r += 4) {
-    float v = wave_sum(bf16_val(sw.Wih[(size_t)r * 64 + lane]) * x[lane]);
-    if (lane == 0) z[r] = src.P[(size_t)from * H4 + r] + v;
+  // a wave takes eight rows at a time so that their loads are in flight together
+  for (int r0 = w * 8; r0 < H4; r0 += 32) {
+    float v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = sw.Wih[(size_t)(r0 + q) * 64 + lane];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = wave_sum(bf16_val(v[q]) * x[lane]);
+    if (lane < 8) {
+      float mine = v[0];
+#pragma unroll
+      for (int q = 1; q < 8; ++q) mine = lane == q ? v[q] : mine;
+      z[r0 + lane] = src.P[(size_t)from * H4 + r0 + lane] + mine;
+    }
   }
   __syncthreads();
   float head = 0.0f;
@@ -106,11 +116,26 @@ __global__ __launch_bounds__(256) void k_seq_advance(Tables t, int stage, SeqWei
   if (lane == 0) part[w] = head;
   __syncthreads();
   if (tid == 0) dst.hsum[b] = src.hsum[from] + (part[0] + part[1] + part[2] + part[3]) + sw.bh[0];
-  for (int r = w; r < H4; r += 4) {
-    float v = 0.0f;
-    for (int k = lane; k < H; k += 64) v = fmaf(bf16_val(sw.Whh[(size_t)r * H + k]), hn[k], v);
-    v = wave_sum(v);
-    if (lane == 0) dst.P[(size_t)b * H4 + r] = sw.bih[r] + sw.bhh[r] + v;
+  for (int r0 = w * 8; r0 < H4; r0 += 32) {
+    float v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = 0.0f;
+    for (int k = lane; k < H; k += 64) {
+      float wv[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) wv[q] = sw.Whh[(size_t)(r0 + q) * H + k];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) v[q] = fmaf(bf16_val(wv[q]), hn[k], v[q]);
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = wave_sum(v[q]);
+    if (lane < 8) {
+      float mine = v[0];
+#pragma unroll
+      for (int q = 1; q < 8; ++q) mine = lane == q ? v[q] : mine;
+      const int r = r0 + lane;
+      dst.P[(size_t)b * H4 + r] = sw.bih[r] + sw.bhh[r] + mine;
+    }
   }
 }
 
