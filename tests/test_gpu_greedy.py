@@ -288,3 +288,29 @@ def test_whole_schedule_launch_equals_layer_by_layer(vf, ovf):
     ref = ovf.greedy(pipes[7], sp, model, w)
     assert ref["cids"][1] >= 0 and ref["cids"][2] == -1
     vf.vf_destroy(ctx)
+
+
+def test_wide_network_two_problems_per_workgroup(vf, ovf):
+    """Hidden width 1024 (tiles of 64 candidates, four row tiles per wave, the first-layer fold
+    at that width) with twice as many problems as compute units, so that every workgroup of the
+    whole-schedule launch runs two problems one after the other; against the per-layer path
+    and, for some problems, the checker."""
+    B, S = 512, 4
+    sp = I.make_space([1, 2, 4], [1, 4], [4, 8], [(0, 1, 2), (2, 1, 0)], 2, 2,
+                      [I.ROOT, I.L1, I.L2, I.INLINE], 2, 256)
+    pipes = np.stack([I.random_pipeline(S, 1000 + k, max_hw=20, max_c=24) for k in range(B)])
+    dims = [256, 1024, 1024, 1]
+    w = I.mlp_weights(dims, 7, bias_std=0.1)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipes); vf.vf_set_model(ctx, model, w)
+    whole = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
+    vf.vf_reset_state(ctx)
+    for i in range(S):
+        vf.vf_argmin_step(ctx, i, True)
+    steps = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=S)]
+    for a, b in zip(whole, steps):
+        assert np.array_equal(a, b)
+    for b in (0, 255, 256, 511):
+        compare_schedule(ovf, pipes[b], sp, model, w, whole[1][b], whole[2][b], whole[0][b], TOL[1])
+    vf.vf_destroy(ctx)
