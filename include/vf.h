@@ -199,7 +199,8 @@ int vf_set_noise(vf_ctx *ctx, float eps, uint64_t seed, int32_t first_rollout);
 /* Beam search guided by V (Secs. 3.1 and 4.1 search with a beam as well, next to the
  * greedy scan; Algorithm 2 completes prefixes with it).  The context's `batch` problems
  * are the beam slots of ONE network: every slot must hold the same pipeline (else
- * VF_EINVAL) and the beam width is `batch`.  Starts from problem 0's current schedule
+ * VF_EINVAL) and the beam width is `batch` (at most 1024; batch * padded id count must stay
+ * below 2^31).  Starts from problem 0's current schedule
  * (first_stage == vf_n_scheduled(); after vf_reset_state that is s_0); the other slots'
  * schedules are discarded.  Per layer every surviving partial schedule is extended by
  * every valid candidate, all extensions are scored, and the `batch` smallest scores

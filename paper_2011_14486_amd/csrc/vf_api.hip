@@ -434,7 +434,7 @@ int vf_beam_search(vf_ctx *c, int first, int last, vf_state *out_states, int32_t
   if (!model_fits(c)) return VF_EINVAL;
   if (first < 0 || last >= c->S || first > last + 1) return VF_EINVAL;
   if (first != c->n_sched) return VF_ESTATE;
-  if ((int64_t)c->B * c->Mpad >= ((int64_t)1 << 31)) return VF_EINVAL;
+  if ((int64_t)c->B * c->Mpad >= ((int64_t)1 << 31) || c->B > 1024) return VF_EINVAL;  // a selection pass keeps B of 2048
   if (!c->beam_checked) {
     for (int b = 1; b < c->B; ++b)
       if (memcmp(c->h_stages.data(), c->h_stages.data() + (size_t)b * c->S, sizeof(vf_stage) * (size_t)c->S) != 0)

@@ -196,11 +196,9 @@ __device__ void block_min(float &v, int32_t &c, float *sv, int32_t *sc) {
   for (int k = 1; k < nw; ++k) take_min_u(v, c, sv[k], sc[k]);
 }
 
-// One selection pass: every block reduces 2048 (value, index) pairs to its k smallest,
-// ordered by (value, index).  First pass (idx_in == nullptr): values are the masked
-// scores, index = slot * Mpad + candidate id, columns >= M are skipped.  Later passes
-// read the pairs of the pass before.  The last pass (one block) also counts.
-__global__ __launch_bounds__(256) void k_topk_pass(const float *val_in, const int32_t *idx_in, uint32_t n,
+// The same selection pass for a few survivors: k rounds of a block-wide first minimum
+// (cheaper than sorting while k is small).
+__global__ __launch_bounds__(256) void k_topk_pass_few(const float *val_in, const int32_t *idx_in, uint32_t n,
                                                    uint32_t M, uint32_t Mpad, int k, float *val_out,
                                                    int32_t *idx_out, int32_t *sel_n) {
   __shared__ float sv[4];
@@ -245,6 +243,72 @@ __global__ __launch_bounds__(256) void k_topk_pass(const float *val_in, const in
     }
   }
   if (sel_n && threadIdx.x == 0) {
+    sel_n[0] = found;
+    if (found > 0) sel_n[1] = found;
+  }
+}
+
+// (value, index) as one sortable key: floats map to unsigned integers in their own order
+// (-0 counts as +0, as in a comparison), the index breaks ties.  ~0 = no entry.
+__device__ __forceinline__ unsigned long long topk_key(float v, int32_t idx) {
+  uint32_t u = __float_as_uint(v == 0.0f ? 0.0f : v);
+  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+  return ((unsigned long long)u << 32) | (uint32_t)idx;
+}
+__device__ __forceinline__ float topk_value(unsigned long long key) {
+  uint32_t u = (uint32_t)(key >> 32);
+  u = (u & 0x80000000u) ? (u & 0x7fffffffu) : ~u;
+  return __uint_as_float(u);
+}
+
+// One selection pass: every block reduces 2048 (value, index) pairs to its k smallest,
+// ordered by (value, index), with a bitonic sort of the keys in LDS.  First pass
+// (idx_in == nullptr): values are the masked scores, index = slot * Mpad + candidate id,
+// columns >= M are skipped.  Later passes read the pairs of the pass before.  The last
+// pass (one block) also counts.  +inf and NaN never survive.
+__global__ __launch_bounds__(256) void k_topk_pass(const float *val_in, const int32_t *idx_in, uint32_t n,
+                                                   uint32_t M, uint32_t Mpad, int k, float *val_out,
+                                                   int32_t *idx_out, int32_t *sel_n) {
+  constexpr unsigned long long NONE = ~0ull;
+  __shared__ unsigned long long keys[2048];
+  const uint32_t base = blockIdx.x * 2048u;
+  const int tid = threadIdx.x;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t i = base + tid + e * 256u;
+    unsigned long long key = NONE;
+    if (i < n) {
+      if (idx_in) {
+        const int32_t ix = idx_in[i];
+        if (ix >= 0) key = topk_key(val_in[i], ix);
+      } else if ((i % Mpad) < M) {
+        const float t = val_in[i];
+        if (t < __builtin_inff()) key = topk_key(t, (int32_t)i);
+      }
+    }
+    keys[tid + e * 256] = key;
+  }
+  for (int size = 2; size <= 2048; size <<= 1)
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      __syncthreads();
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const int t = tid + e * 256;
+        const int lo = 2 * t - (t & (stride - 1)), hi = lo + stride;
+        const bool up = (lo & size) == 0;
+        const unsigned long long a = keys[lo], b = keys[hi];
+        if ((a > b) == up) { keys[lo] = b; keys[hi] = a; }
+      }
+    }
+  __syncthreads();
+  for (int r = tid; r < k; r += 256) {
+    const unsigned long long key = keys[r];
+    val_out[(size_t)blockIdx.x * k + r] = key == NONE ? __builtin_inff() : topk_value(key);
+    idx_out[(size_t)blockIdx.x * k + r] = key == NONE ? -1 : (int32_t)(uint32_t)key;
+  }
+  if (sel_n && tid == 0) {
+    int found = 0;
+    for (int r = 0; r < k; ++r) found += keys[r] != NONE;
     sel_n[0] = found;
     if (found > 0) sel_n[1] = found;
   }
@@ -459,7 +523,7 @@ int vfk_beam_select_commit(vf_ctx *c, int stage) {
   for (;;) {
     const int blocks = (int)((n + 2047u) / 2048u);
     const bool last_pass = blocks == 1;
-    hipLaunchKernelGGL(k_topk_pass, dim3(blocks), dim3(256), 0, c->stream, vin, iin, n, (uint32_t)c->M,
+    hipLaunchKernelGGL(k <= 16 ? k_topk_pass_few : k_topk_pass, dim3(blocks), dim3(256), 0, c->stream, vin, iin, n, (uint32_t)c->M,
                        (uint32_t)c->Mpad, k, last_pass ? c->d_sel_val : va, last_pass ? c->d_sel_idx : ia,
                        last_pass ? c->d_sel_n : (int32_t *)nullptr);
     VF_HIP(c, hipGetLastError());

@@ -94,7 +94,7 @@ def make_ctx(vf, pipe, sp, model, w, K):
     return ctx, run
 
 
-@pytest.mark.parametrize("K", [1, 4, 16])
+@pytest.mark.parametrize("K", [1, 4, 16, 40])
 def test_beam_fused_bf16(vf, ovf, K):
     sp = I.make_space([1, 2, 3, 8], [1, 2, 5], [1, 4, 16], [(0, 1, 2), (2, 1, 0), (1, 0, 2)], 2, 2,
                       [I.ROOT, I.L1, I.L2, I.INLINE], 2, 256)
@@ -113,17 +113,19 @@ def test_beam_fused_bf16(vf, ovf, K):
     vf.vf_destroy(ctx)
 
 
-def test_beam_fp32_tiny_config_with_ties(vf, ovf):
+@pytest.mark.parametrize("K", [6, 24])
+def test_beam_fp32_tiny_config_with_ties(vf, ovf, K):
     """The tiny conv+ReLU config has candidates with identical features, hence exactly
-    equal scores: the (score, parent, candidate id) order decides, as in the checker."""
+    equal scores: the (score, parent, candidate id) order decides, as in the checker
+    (few survivors: rounds of block minima; more: sorted keys)."""
     pipe, sp = I.tiny_conv_relu(), I.tiny_space()
     dims = [64, 128, 128, 1]
     w = I.mlp_weights(dims, 0)
     model = I.model_record(I.MLP, dims, I.FP32)
-    ctx, run = make_ctx(vf, pipe, sp, model, w, 6)
-    check_beam(ovf, pipe, sp, model, w, run, 6, TOL[0])
+    ctx, run = make_ctx(vf, pipe, sp, model, w, K)
+    check_beam(ovf, pipe, sp, model, w, run, K, TOL[0])
     cids, vals, st, nb = run(1)
-    ref = ovf.beam(pipe, sp, 6, model, w)
+    ref = ovf.beam(pipe, sp, K, model, w)
     assert np.array_equal(ref["cids"], cids) and ref["n_beams"] == nb
     vf.vf_destroy(ctx)
 
