@@ -208,7 +208,7 @@ void vf_destroy(vf_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   free_pipeline(c);
   vfk_free_model(c);
-  void *ps[] = {c->d_space, c->d_err,  c->d_stat, c->d_feat,   c->d_act[0], c->d_act[1],
+  void *ps[] = {c->d_space, c->d_err,  c->d_stat, c->d_wlist, c->d_feat,   c->d_act[0], c->d_act[1],
                 c->d_pval,  c->d_pidx, c->d_scores, c->d_tk_val, c->d_tk_idx};
   for (void *p : ps)
     if (p) (void)hipFree(p);

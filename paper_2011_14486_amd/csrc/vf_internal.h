@@ -98,6 +98,7 @@ struct vf_ctx {
   int32_t *d_feat = nullptr; size_t feat_elems = 0;
   float *d_act[2] = {nullptr, nullptr}; size_t act_elems = 0;
   float *d_pval = nullptr; int32_t *d_pidx = nullptr; size_t part_elems = 0;
+  int32_t *d_wlist = nullptr; size_t wlist_elems = 0;  // [B][Mpad] id lists of the whole-schedule launch
 
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
 

@@ -419,9 +419,14 @@ struct GenArgs {
 // them from stage wa.first to wa.last by itself - decision context, all tiles of the
 // stage, the scan's running minimum, the commit - so that a schedule costs one launch
 // instead of two per layer.  Pays when there are about as many problems as compute units.
+// The valid candidates of a decision are first compacted into an id list (ascending), so
+// that every tile is full of candidates: ids that break a validity rule never reach the
+// network, and no tile has to be tested for being closed.
 struct WholeArgs {
   Tables t;
   int first, last;
+  int32_t *list;   // [nprob][Mpad] scratch for the id lists
+  int64_t Mpad;
 };
 
 template <int NC, int RT, int PD, bool GEN, bool WHOLE>
@@ -474,21 +479,79 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   int t_begin = (int)((int64_t)blockIdx.x * T / gridDim.x);
   int t_end = (int)((int64_t)(blockIdx.x + 1) * T / gridDim.x);
   int cur_p = -1;
+  int ntile_cand = 0;  // WHOLE: entries of the current decision's id list
   for (int unit = WHOLE ? (int)blockIdx.x : 0; unit < (WHOLE ? nprob : 1); unit += WHOLE ? (int)gridDim.x : 1)
   for (int stage = WHOLE ? wa.first : 0; stage <= (WHOLE ? wa.last : 0); ++stage) {
   float run_v = __builtin_inff();  // thread 0: the scan's incumbent over the tiles of this stage
   int32_t run_c = -1;
+  int32_t *const idlist = WHOLE ? wa.list + (size_t)unit * wa.Mpad : nullptr;
   if (WHOLE) {
     fill_decpack(pk, wa.t, unit, stage);
     cur_p = unit;
     b1_p = -1;
-    t_begin = unit * nparts;
-    t_end = t_begin + nparts;
     na.stage = stage;
+    // Ordered list of the decision's valid ids, written down directly from the validity
+    // rules: per (compute_at, store_at) digit pair that is open - the level is offered and
+    // the hoist does not exceed it - the valid ids are the products of the split factors
+    // that fit the level's region with every loop order / vectorize / parallel choice;
+    // an inlining pair has the single id with every other digit zero.
+    __shared__ int ncand, g_npairs;
+    __shared__ int g_pos[13], g_base[12], g_cat[12];
+    __shared__ int g_nok[3][3], g_ok[3][3][8];
+    if (tid < 9) {
+      const int lvl = tid / 3, dd = tid % 3;
+      int cnt = 0;
+      for (int k = 0; k < pk.sp.nf[dd]; ++k)
+        if ((uint32_t)pk.sp.fac[dd][k] <= pk.d.E[lvl][dd]) g_ok[lvl][dd][cnt++] = k;
+      g_nok[lvl][dd] = cnt;
+    }
+    __syncthreads();
+    const int rest_n = pk.sp.nperm * pk.sp.nvec * pk.sp.npar;
+    const int run_n = pk.sp.nf[0] * pk.sp.nf[1] * pk.sp.nf[2] * rest_n;
+    if (tid == 0) {
+      int np = 0, pos = 0;
+      for (int isat = 0; isat < pk.sp.nsat; ++isat)
+        for (int icat = 0; icat < pk.sp.ncat; ++icat) {
+          const int cat = pk.sp.cat[icat];
+          if (pk.d.lvl_ok[cat] == 0) continue;
+          int cnt = 0;
+          if (cat == VF_INLINE) cnt = isat == 0 ? 1 : 0;
+          else if (isat <= cat) cnt = g_nok[cat][0] * g_nok[cat][1] * g_nok[cat][2] * rest_n;
+          if (cnt == 0) continue;
+          g_pos[np] = pos;
+          g_base[np] = (icat + pk.sp.ncat * isat) * run_n;
+          g_cat[np] = cat;
+          pos += cnt;
+          ++np;
+        }
+      g_pos[np] = pos;
+      g_npairs = np;
+      ncand = pos;
+    }
+    __syncthreads();
+    for (int k = tid; k < ncand; k += 512) {
+      int q = 0;
+      while (q + 1 < g_npairs && k >= g_pos[q + 1]) ++q;
+      const int cat = g_cat[q];
+      int cid = g_base[q];
+      if (cat != VF_INLINE) {
+        int r = k - g_pos[q];
+        const int nx = g_nok[cat][0], ny = g_nok[cat][1], nc = g_nok[cat][2];
+        const int jx = r % nx; r /= nx;
+        const int jy = r % ny; r /= ny;
+        const int jc = r % nc; r /= nc;
+        cid += g_ok[cat][0][jx] + pk.sp.nf[0] * (g_ok[cat][1][jy] + pk.sp.nf[1] * (g_ok[cat][2][jc] + pk.sp.nf[2] * r));
+      }
+      idlist[k] = cid;
+    }
+    __syncthreads();
+    t_begin = 0;
+    t_end = (ncand + NC - 1) / NC;  // tiles of the list
+    ntile_cand = ncand;
   }
   for (int t = t_begin; t < t_end; ++t) {
-  const int p = t / nparts;
-  const int64_t n0 = (int64_t)(t - p * nparts) * NC;
+  const int p = WHOLE ? unit : t / nparts;
+  const int64_t n0 = WHOLE ? (int64_t)t * NC : (int64_t)(t - p * nparts) * NC;
   const int32_t *xp = x + (size_t)p * prob_stride;
   if (GEN && p != cur_p) {
     if (tid < VF_DECPACK_DWORDS)
@@ -502,7 +565,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     // stages whole compute_at levels are closed, and that digit is the most significant
     // but one, so such ids come in runs much longer than a tile.
     const int64_t nend = (n0 + NC < M) ? n0 + NC : M;
-    if (range_closed(pk.d, pk.sp, (uint32_t)n0, (uint32_t)(nend > n0 ? nend : n0))) {
+    if (!WHOLE && range_closed(pk.d, pk.sp, (uint32_t)n0, (uint32_t)(nend > n0 ? nend : n0))) {
       if (scores && tid < NC && (n0 + tid) < ld_scores) scores[(size_t)p * ld_scores + n0 + tid] = __builtin_inff();
       if (!WHOLE && tid == 0) {
         pval[(size_t)t] = __builtin_inff();
@@ -534,8 +597,9 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     // thread does not store are dead code in its copy of the evaluation
     {
       const int n = tid % NC, part = tid / NC;
-      const uint32_t cid = (uint32_t)(n0 + n);
-      const bool inb = (int64_t)cid < M;
+      // WHOLE: column n is entry n0 + n of the id list (padding columns evaluate id 0)
+      const bool inb = WHOLE ? (n0 + n) < ntile_cand : (n0 + n) < M;
+      const uint32_t cid = WHOLE ? (inb ? (uint32_t)idlist[n0 + n] : 0u) : (uint32_t)(n0 + n);
       int32_t core[64];
       uint32_t dec;
       auto put = [&](const int32_t *v, int row0) {
@@ -726,12 +790,14 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       // scores of a generated tile are masked: invalid candidates and padding read +inf
       if (scores && (GEN ? (n0 + tid) < ld_scores : (n0 + tid) < M))
         scores[(size_t)p * ld_scores + n0 + tid] = (GEN && okf[tid] == 0) ? __builtin_inff() : s;
-      if (na.eps != 0.0f) s = add_noise(na, s, p, (int32_t)(n0 + tid));
-      if (okf[tid] != 0 && s < v) { v = s; c = (int32_t)(n0 + tid); }
+      // the candidate id of this column (WHOLE: from the decision's id list)
+      const int32_t colid = (WHOLE && okf[tid] != 0) ? idlist[n0 + tid] : (int32_t)(n0 + tid);
+      if (na.eps != 0.0f) s = add_noise(na, s, p, colid);
+      if (okf[tid] != 0 && s < v) { v = s; c = colid; }
       wave_min(v, c);
       if (GEN && ga.stat) {
         const int nvalid = __popcll(__ballot(okf[tid] != 0));
-        const int nin = __popcll(__ballot((n0 + tid) < M));
+        const int nin = __popcll(__ballot(WHOLE ? (n0 + tid) < ntile_cand : (n0 + tid) < M));
         if (lane == 0) {
           atomicAdd(&ga.stat[0], (unsigned long long)nin);
           atomicAdd(&ga.stat[1], (unsigned long long)nvalid);
@@ -1175,6 +1241,13 @@ bool vfk_can_run_whole(const vf_ctx *c) {
 // Algorithm 1 over stages first..last for every problem of the batch, one launch.
 int vfk_greedy_whole(vf_ctx *c, int first, int last) {
   int nparts = 0;
+  const size_t want = (size_t)c->B * c->Mpad;
+  if (want > c->wlist_elems) {
+    if (c->d_wlist) { VF_HIP(c, hipStreamSynchronize(c->stream)); (void)hipFree(c->d_wlist); c->d_wlist = nullptr; }
+    c->wlist_elems = 0;
+    if (hipMalloc((void **)&c->d_wlist, want * 4) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
+    c->wlist_elems = want;
+  }
   int rc = score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, &nparts, first, first, first, last);
   c->dec_stage = -1;
   return rc;
@@ -1318,6 +1391,7 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     WholeArgs wa;
     wa.t = tables_of(c);
     wa.first = whole_first; wa.last = whole_last;
+    wa.list = c->d_wlist; wa.Mpad = c->Mpad;
     const bool whole = whole_first >= 0;
     if (gen_stage >= 0 && !whole) {
       int rc2 = vfk_prepare(c, gen_stage);

@@ -273,9 +273,16 @@ def test_whole_schedule_launch_equals_layer_by_layer(vf, ovf):
     for eps in (0.0, 0.05):
         vf.vf_set_noise(ctx, eps, seed=11, first_rollout=2)
         vf.vf_reset_state(ctx)
+        vf.vf_profile_enable(ctx, True); vf.vf_profile_counts(ctx)
         whole = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
+        scored_w, valid_w = vf.vf_profile_counts(ctx)
         vf.vf_reset_state(ctx)
         steps = layer_by_layer()
+        scored_s, valid_s = vf.vf_profile_counts(ctx)
+        vf.vf_profile_enable(ctx, False)
+        # the whole-schedule launch writes its candidate lists down from the validity rules:
+        # they must hold exactly the ids that the per-candidate test accepts
+        assert valid_w == valid_s == scored_w <= scored_s
         for a, b in zip(whole, steps):
             assert np.array_equal(a, b)
         assert whole[1][7, 1] >= 0 and (whole[1][7, 2:] == -1).all() and (whole[1][6] >= 0).all()
