@@ -617,20 +617,33 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
         dst[0] = q0;
         dst[1] = q1;
       };
+      // eight rows at a time; the row groups are dealt out so that the four copies cost
+      // about the same (rows 0..15 and 56..63 are copies of the context, 48..55 the dearest)
+      auto put8 = [&](const int32_t *v, int row0) {
+        uint4 q;
+        q.x = pack_bf16(plog2_dev(v[0]), plog2_dev(v[1]));
+        q.y = pack_bf16(plog2_dev(v[2]), plog2_dev(v[3]));
+        q.z = pack_bf16(plog2_dev(v[4]), plog2_dev(v[5]));
+        q.w = pack_bf16(plog2_dev(v[6]), plog2_dev(v[7]));
+        if (!inb) q = make_uint4(0u, 0u, 0u, 0u);
+        *reinterpret_cast<uint4 *>(act + (size_t)n * ks + row0) = q;
+      };
       if (part == 0) {
         // evaluated for padding ids too: core must be defined before put reads it
         const bool valid = eval_candidate<true>(dctx, sp, cid, dec, core);
         okf[n] = inb && valid;
         put(core, 0);
+        put8(core + 40, 40);
       } else if (part == 1) {
         eval_candidate<true>(dctx, sp, cid, dec, core);
         put(core + 16, 16);
       } else if (part == 2) {
         eval_candidate<true>(dctx, sp, cid, dec, core);
-        put(core + 32, 32);
+        put8(core + 32, 32);
+        put8(core + 56, 56);
       } else if (part == 3) {
         eval_candidate<true>(dctx, sp, cid, dec, core);
-        put(core + 48, 48);
+        put8(core + 48, 48);
       }
     }
     if (F == 256 && !fold) {
