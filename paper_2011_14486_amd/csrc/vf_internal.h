@@ -35,6 +35,8 @@ struct vf_packed_model {
   uint16_t *w_stream_fold = nullptr;
   size_t wave_stride_fold = 0;
   uint32_t *w1_fold = nullptr;     // [96][dims[1]] bf16 pairs
+  // recurrent network wired to the search: [W_ih | W_hh] transposed, bf16 values as fp32, [64+H][4H]
+  float *w_seqT = nullptr;
 };
 
 struct vf_ctx {

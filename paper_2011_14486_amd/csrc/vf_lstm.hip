@@ -62,79 +62,107 @@ struct SeqState {
   float *hfb, *cpre, *P, *hsum;  // [B][H] (bf16 values), [B][H], [B][4H], [B]
 };
 
-__global__ __launch_bounds__(256) void k_seq_advance(Tables t, int stage, SeqWeights sw, SeqState src, SeqState dst,
-                                                     const int32_t *sel_idx, const int32_t *sel_n, int64_t Mpad) {
-  __shared__ float x[64], z[1024], hn[256], part[4];
-  const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+constexpr int SEQ_PB = 4;  // problems per workgroup of k_seq_advance: they share the weight reads
+
+// [W_ih | W_hh] transposed and rounded: WT[k][r], k over the 64 inputs then the H hidden
+// units, r over the 4H gate rows, so that thread r of a block reads its row coalesced.
+__global__ __launch_bounds__(256) void k_pack_seqT(SeqWeights sw, float *WT) {
+  const int H = sw.H, H4 = 4 * H;
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)(64 + H) * H4) return;
+  const int k = (int)(i / H4), r = (int)(i % H4);
+  WT[i] = bf16_val(k < 64 ? sw.Wih[(size_t)r * 64 + k] : sw.Whh[(size_t)r * H + (k - 64)]);
+}
+
+__global__ __launch_bounds__(1024) void k_seq_advance(Tables t, int stage, SeqWeights sw, const float *WT, SeqState src,
+                                                      SeqState dst, const int32_t *sel_idx, const int32_t *sel_n,
+                                                      int64_t Mpad, int B) {
+  __shared__ float x[SEQ_PB][64], z[SEQ_PB][1024], hn[SEQ_PB][256], hraw[SEQ_PB][256];
+  __shared__ int from_s[SEQ_PB], mode_s[SEQ_PB];  // 0: leave alone, 1: carry the state over, 2: one cell step
+  const int tid = threadIdx.x, lane = tid & 63;
   const int H = sw.H, H4 = 4 * H, S = t.S;
-  int from = b;
-  if (sel_idx) {
-    if (b >= sel_n[0]) return;  // not a survivor: the slot is dead
-    from = (int)((int64_t)sel_idx[b] / Mpad);
-  }
-  const bool live = t.cids[(size_t)b * S + stage] >= 0;
-  if (!live) {
-    if (src.cpre != dst.cpre) {
-      for (int k = tid; k < H; k += 256) {
-        dst.hfb[(size_t)b * H + k] = src.hfb[(size_t)from * H + k];
-        dst.cpre[(size_t)b * H + k] = src.cpre[(size_t)from * H + k];
+  const int b0 = blockIdx.x * SEQ_PB;
+  if (tid < SEQ_PB) {
+    const int b = b0 + tid;
+    int mode = 0, from = b;
+    if (b < B) {
+      const bool survivor = !sel_idx || b < sel_n[0];  // beam search: slots past the survivors are dead
+      if (survivor) {
+        if (sel_idx) from = (int)((int64_t)sel_idx[b] / Mpad);
+        const bool live = t.cids[(size_t)b * S + stage] >= 0;
+        mode = live ? 2 : (src.cpre != dst.cpre ? 1 : 0);
       }
-      for (int r = tid; r < H4; r += 256) dst.P[(size_t)b * H4 + r] = src.P[(size_t)from * H4 + r];
-      if (tid == 0) dst.hsum[b] = src.hsum[from];
     }
-    return;
-  }
-  if (tid < 64) x[tid] = bf16_val(plog2_dev(t.cf[((size_t)b * S + stage) * 64 + tid]));
-  __syncthreads();
-  // a wave takes eight rows at a time so that their loads are in flight together
-  for (int r0 = w * 8; r0 < H4; r0 += 32) {
-    float v[8];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) v[q] = sw.Wih[(size_t)(r0 + q) * 64 + lane];
-#pragma unroll
-    for (int q = 0; q < 8; ++q) v[q] = wave_sum(bf16_val(v[q]) * x[lane]);
-    if (lane < 8) {
-      float mine = v[0];
-#pragma unroll
-      for (int q = 1; q < 8; ++q) mine = lane == q ? v[q] : mine;
-      z[r0 + lane] = src.P[(size_t)from * H4 + r0 + lane] + mine;
-    }
+    from_s[tid] = from;
+    mode_s[tid] = mode;
   }
   __syncthreads();
-  float head = 0.0f;
-  if (tid < H) {
-    const float ig = sigmoid_dev(z[tid]), fg = sigmoid_dev(z[H + tid]);
-    const float gg = tanh_dev(z[2 * H + tid]), og = sigmoid_dev(z[3 * H + tid]);
-    const float cn = fg * src.cpre[(size_t)from * H + tid] + ig * gg;
-    const float h = og * tanh_dev(cn);
-    dst.cpre[(size_t)b * H + tid] = cn;
-    hn[tid] = bf16_val(h);
-    dst.hfb[(size_t)b * H + tid] = hn[tid];
-    head = bf16_val(sw.wh[tid]) * h;
+  for (int i = tid; i < SEQ_PB * 64; i += 1024) {
+    const int pb = i / 64, k = i % 64;
+    x[pb][k] = mode_s[pb] == 2 ? bf16_val(plog2_dev(t.cf[((size_t)(b0 + pb) * S + stage) * 64 + k])) : 0.0f;
   }
-  head = wave_sum(head);
-  if (lane == 0) part[w] = head;
   __syncthreads();
-  if (tid == 0) dst.hsum[b] = src.hsum[from] + (part[0] + part[1] + part[2] + part[3]) + sw.bh[0];
-  for (int r0 = w * 8; r0 < H4; r0 += 32) {
-    float v[8];
+  // gate pre-activations: thread r owns row r for the block's problems
+  if (tid < H4) {
+    float acc[SEQ_PB];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) v[q] = 0.0f;
-    for (int k = lane; k < H; k += 64) {
-      float wv[8];
+    for (int pb = 0; pb < SEQ_PB; ++pb) acc[pb] = 0.0f;
+#pragma unroll 16
+    for (int k = 0; k < 64; ++k) {
+      const float wv = WT[(size_t)k * H4 + tid];
 #pragma unroll
-      for (int q = 0; q < 8; ++q) wv[q] = sw.Whh[(size_t)(r0 + q) * H + k];
-#pragma unroll
-      for (int q = 0; q < 8; ++q) v[q] = fmaf(bf16_val(wv[q]), hn[k], v[q]);
+      for (int pb = 0; pb < SEQ_PB; ++pb) acc[pb] = fmaf(wv, x[pb][k], acc[pb]);
     }
 #pragma unroll
-    for (int q = 0; q < 8; ++q) v[q] = wave_sum(v[q]);
-    if (lane < 8) {
-      float mine = v[0];
+    for (int pb = 0; pb < SEQ_PB; ++pb)
+      if (mode_s[pb] == 2) z[pb][tid] = src.P[(size_t)from_s[pb] * H4 + tid] + acc[pb];
+  }
+  __syncthreads();
+  for (int i = tid; i < SEQ_PB * H; i += 1024) {
+    const int pb = i / H, u = i % H, b = b0 + pb, from = from_s[pb];
+    if (mode_s[pb] == 2) {
+      const float ig = sigmoid_dev(z[pb][u]), fg = sigmoid_dev(z[pb][H + u]);
+      const float gg = tanh_dev(z[pb][2 * H + u]), og = sigmoid_dev(z[pb][3 * H + u]);
+      const float cn = fg * src.cpre[(size_t)from * H + u] + ig * gg;
+      const float h = og * tanh_dev(cn);
+      dst.cpre[(size_t)b * H + u] = cn;
+      hraw[pb][u] = h;
+      hn[pb][u] = bf16_val(h);
+      dst.hfb[(size_t)b * H + u] = hn[pb][u];
+    } else if (mode_s[pb] == 1) {
+      dst.cpre[(size_t)b * H + u] = src.cpre[(size_t)from * H + u];
+      dst.hfb[(size_t)b * H + u] = src.hfb[(size_t)from * H + u];
+    }
+  }
+  __syncthreads();
+  // the head's prediction for this timestep: one wave per problem, fixed order
+  if (tid < SEQ_PB * 64) {
+    const int pb = tid / 64;
+    if (mode_s[pb] == 2) {
+      float v = 0.0f;
+      for (int u = lane; u < H; u += 64) v = fmaf(bf16_val(sw.wh[u]), hraw[pb][u], v);
+      v = wave_sum(v);
+      if (lane == 0) dst.hsum[b0 + pb] = src.hsum[from_s[pb]] + v + sw.bh[0];
+    } else if (mode_s[pb] == 1 && lane == 0) {
+      dst.hsum[b0 + pb] = src.hsum[from_s[pb]];
+    }
+  }
+  // the h part of the next step's gates
+  if (tid < H4) {
+    float acc[SEQ_PB];
 #pragma unroll
-      for (int q = 1; q < 8; ++q) mine = lane == q ? v[q] : mine;
-      const int r = r0 + lane;
-      dst.P[(size_t)b * H4 + r] = sw.bih[r] + sw.bhh[r] + mine;
+    for (int pb = 0; pb < SEQ_PB; ++pb) acc[pb] = 0.0f;
+#pragma unroll 16
+    for (int k = 0; k < H; ++k) {
+      const float wv = WT[(size_t)(64 + k) * H4 + tid];
+#pragma unroll
+      for (int pb = 0; pb < SEQ_PB; ++pb) acc[pb] = fmaf(wv, hn[pb][k], acc[pb]);
+    }
+    const float bias = sw.bih[tid] + sw.bhh[tid];
+#pragma unroll
+    for (int pb = 0; pb < SEQ_PB; ++pb) {
+      if (mode_s[pb] == 2) dst.P[(size_t)(b0 + pb) * H4 + tid] = bias + acc[pb];
+      else if (mode_s[pb] == 1) dst.P[(size_t)(b0 + pb) * H4 + tid] = src.P[(size_t)from_s[pb] * H4 + tid];
     }
   }
 }
@@ -494,6 +522,16 @@ int vfk_seq_sync(vf_ctx *c, int stage) {
     hipLaunchKernelGGL(k_seq_tables, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, c->d_intr, sw,
                        (size_t)B * S, c->d_seq_G);
     VF_HIP(c, hipGetLastError());
+    if (!c->pm.w_seqT) {
+      const size_t nw = (size_t)(64 + H) * 4 * H;
+      if (hipMalloc((void **)&c->pm.w_seqT, nw * sizeof(float)) != hipSuccess) {
+        (void)hipGetLastError();
+        vfk_seq_free(c);
+        return VF_ENOMEM;
+      }
+      hipLaunchKernelGGL(k_pack_seqT, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st, sw, c->pm.w_seqT);
+      VF_HIP(c, hipGetLastError());
+    }
     c->seq_stage = -1;
   }
   if (c->seq_stage == stage) return VF_OK;
@@ -504,8 +542,9 @@ int vfk_seq_sync(vf_ctx *c, int stage) {
                      s0.hsum);
   VF_HIP(c, hipGetLastError());
   for (int t = 0; t < stage; ++t) {
-    hipLaunchKernelGGL(k_seq_advance, dim3((unsigned)B), dim3(256), 0, st, tables_of(c), t, sw, s0, s0,
-                       (const int32_t *)nullptr, (const int32_t *)nullptr, (int64_t)c->Mpad);
+    hipLaunchKernelGGL(k_seq_advance, dim3((unsigned)((B + SEQ_PB - 1) / SEQ_PB)), dim3(1024), 0, st, tables_of(c), t, sw,
+                       (const float *)c->pm.w_seqT, s0, s0, (const int32_t *)nullptr, (const int32_t *)nullptr,
+                       (int64_t)c->Mpad, B);
     VF_HIP(c, hipGetLastError());
   }
   c->seq_stage = stage;
@@ -516,8 +555,9 @@ int vfk_seq_sync(vf_ctx *c, int stage) {
 int vfk_seq_advance(vf_ctx *c, int stage) {
   if (c->seq_stage != stage) return VF_OK;  // not in step: rebuilt at the next use
   const SeqState s = state_of(c, c->seq_cur);
-  hipLaunchKernelGGL(k_seq_advance, dim3((unsigned)c->B), dim3(256), 0, c->stream, tables_of(c), stage, weights_of(c),
-                     s, s, (const int32_t *)nullptr, (const int32_t *)nullptr, (int64_t)c->Mpad);
+  hipLaunchKernelGGL(k_seq_advance, dim3((unsigned)((c->B + SEQ_PB - 1) / SEQ_PB)), dim3(1024), 0, c->stream,
+                     tables_of(c), stage, weights_of(c), (const float *)c->pm.w_seqT, s, s, (const int32_t *)nullptr,
+                     (const int32_t *)nullptr, (int64_t)c->Mpad, c->B);
   VF_HIP(c, hipGetLastError());
   c->seq_stage = stage + 1;
   return VF_OK;
@@ -527,8 +567,9 @@ int vfk_seq_advance(vf_ctx *c, int stage) {
 int vfk_seq_advance_beam(vf_ctx *c, int stage) {
   if (c->seq_stage != stage) return VF_OK;
   const SeqState src = state_of(c, c->seq_cur), dst = state_of(c, c->seq_cur ^ 1);
-  hipLaunchKernelGGL(k_seq_advance, dim3((unsigned)c->B), dim3(256), 0, c->stream, tables_of(c), stage, weights_of(c),
-                     src, dst, (const int32_t *)c->d_sel_idx, (const int32_t *)c->d_sel_n, (int64_t)c->Mpad);
+  hipLaunchKernelGGL(k_seq_advance, dim3((unsigned)((c->B + SEQ_PB - 1) / SEQ_PB)), dim3(1024), 0, c->stream,
+                     tables_of(c), stage, weights_of(c), (const float *)c->pm.w_seqT, src, dst,
+                     (const int32_t *)c->d_sel_idx, (const int32_t *)c->d_sel_n, (int64_t)c->Mpad, c->B);
   VF_HIP(c, hipGetLastError());
   c->seq_cur ^= 1;
   c->seq_stage = stage + 1;

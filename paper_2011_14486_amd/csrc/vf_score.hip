@@ -1114,6 +1114,7 @@ void vfk_free_model(vf_ctx *c) {
   if (c->pm.w_stream) (void)hipFree(c->pm.w_stream);
   if (c->pm.w_stream_fold) (void)hipFree(c->pm.w_stream_fold);
   if (c->pm.w1_fold) (void)hipFree(c->pm.w1_fold);
+  if (c->pm.w_seqT) (void)hipFree(c->pm.w_seqT);
   if (c->pm.aux) (void)hipFree(c->pm.aux);
   c->pm = vf_packed_model();
 }
