@@ -321,3 +321,42 @@ def test_wide_network_two_problems_per_workgroup(vf, ovf):
     for b in (0, 255, 256, 511):
         compare_schedule(ovf, pipes[b], sp, model, w, whole[1][b], whole[2][b], whole[0][b], TOL[1])
     vf.vf_destroy(ctx)
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_whole_schedule_candidate_lists_against_the_checker(vf, ovf, seed):
+    """Random search spaces (factor lists, loop orders, subsets of the compute_at levels, hoists)
+    and random pipelines: the number of candidates the whole-schedule launch scores must be the
+    checker's count of valid candidates along the schedules the GPU chose, and every decision
+    must be one of them."""
+    rng = np.random.default_rng(100 + seed)
+    fx = sorted(rng.choice([1, 2, 3, 4, 6, 8, 16], size=int(rng.integers(1, 5)), replace=False).tolist())
+    fy = sorted(rng.choice([1, 2, 4, 5, 8], size=int(rng.integers(1, 4)), replace=False).tolist())
+    fc = sorted(rng.choice([1, 2, 4, 8, 16, 32], size=int(rng.integers(1, 5)), replace=False).tolist())
+    perms = [(0, 1, 2), (2, 1, 0), (1, 0, 2), (0, 2, 1)][:int(rng.integers(1, 5))]
+    cats = [[I.ROOT], [I.ROOT, I.INLINE], [I.ROOT, I.L1, I.L2, I.INLINE], [I.ROOT, I.L2]][int(rng.integers(0, 4))]
+    sp = I.make_space(fx, fy, fc, perms, int(rng.integers(1, 3)), int(rng.integers(1, 3)), cats,
+                      int(rng.integers(1, 4)), 256)
+    B, S = 256, 3
+    pipes = np.stack([I.random_pipeline(S, 5000 + 300 * seed + k, max_hw=20, max_c=24) for k in range(B)])
+    dims = [256, 512, 512, 1]
+    w = I.mlp_weights(dims, seed, bias_std=0.1)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipes); vf.vf_set_model(ctx, model, w)
+    vf.vf_profile_enable(ctx, True); vf.vf_profile_counts(ctx)
+    st, cids, vals = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
+    scored, valid = vf.vf_profile_counts(ctx)
+    want = 0
+    for b in range(B):
+        pre = []
+        for i in range(S):
+            _, ok, n = ovf.enumerate_candidates(pipes[b], sp, pre, i)
+            want += int(n)
+            if n == 0:
+                assert (cids[b, i:] == -1).all()
+                break
+            assert cids[b, i] >= 0 and ok[cids[b, i]]
+            pre.append(int(cids[b, i]))
+    assert scored == valid == want
+    vf.vf_destroy(ctx)
