@@ -31,10 +31,9 @@ struct vf_packed_model {
   size_t wave_stride = 0;          // 16-byte units between the streams of two waves
   int fast_rt = 0;
   // 256 input rows: rows 64..255 do not depend on the candidate.  The stream with the
-  // first layer cut to the 64 core rows, and the other 192 rows' first-layer weights
+  // first layer cut to the 64 core rows
   uint16_t *w_stream_fold = nullptr;
   size_t wave_stride_fold = 0;
-  uint32_t *w1_fold = nullptr;     // [96][dims[1]] bf16 pairs
   // recurrent network wired to the search: [W_ih | W_hh] transposed, bf16 values as fp32, [64+H][4H]
   float *w_seqT = nullptr;
 };

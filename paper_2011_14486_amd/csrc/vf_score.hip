@@ -356,7 +356,8 @@ struct FastDev {
   size_t bias_off[8];
   size_t wl_off;
   int k0;                  // k-steps of the first layer present in w_stream
-  const uint32_t *w1_fold; // nullable: first-layer weights of input rows 64..255 as bf16 pairs [96][dims[1]]
+  const uint4 *w_full;     // nullable (fold): the stream with the whole first layer; its k-steps 4..15 of
+  size_t wave_stride_full; // layer 0 are the weights of input rows 64..255
 };
 
 // Stream order for k_mlp_fast: wave w's fragments of all hidden layers back to back,
@@ -389,16 +390,6 @@ __global__ __launch_bounds__(256) void k_pack_stream(const float *blob, FastDev 
     }
   }
   out[i] = v;
-}
-
-// First-layer weights of the input rows that are the same for every candidate of a
-// decision (rows 64..255: the neighbour stages), as bf16 pairs, input-row-major, so that
-// one thread per output unit reads them coalesced: out[q][r] = (W[r][64+2q], W[r][65+2q]).
-__global__ __launch_bounds__(256) void k_pack_fold(const float *W, int K, int N, uint32_t *out) {
-  const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i >= 96 * N) return;
-  const int q = i / N, r = i % N;
-  out[i] = bf16_bits(W[(size_t)r * K + 64 + 2 * q]) | (bf16_bits(W[(size_t)r * K + 65 + 2 * q]) << 16);
 }
 
 // Fused MLP for hidden layers of exactly 256*RT units: every wave owns RT row tiles
@@ -447,7 +438,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   // GEN with 256 input rows: rows 64..255 are the same for all candidates of a decision
   // (neighbour stages), so their part of the first layer is a per-decision bias and the
   // contraction runs over the 64 core rows only
-  const bool fold = GEN && md.w1_fold != nullptr;
+  const bool fold = GEN && md.w_full != nullptr;
   int b1_p = -1;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -575,16 +566,39 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       continue;
     }
     if (fold && b1_p != p) {
-      const int N1 = md.dims[1];
-      for (int r = tid; r < N1; r += 512) {
-        float acc = auxs[md.bias_off[0] + r];
-#pragma unroll 8
-        for (int q = 0; q < 96; ++q) {
-          const uint32_t wv = md.w1_fold[(size_t)q * N1 + r], xv = pk.nbh[q];
-          acc = fmaf(__uint_as_float(wv << 16), __uint_as_float(xv << 16), acc);
-          acc = fmaf(__uint_as_float(wv & 0xffff0000u), __uint_as_float(xv & 0xffff0000u), acc);
+      // the first layer's product with the 192 rows that all candidates of the decision
+      // share, once per decision: the same contraction with the shared vector in every
+      // column (twelve k-steps, one column tile); column 0 of the result plus the layer's
+      // bias is what the candidates' accumulators start from
+      floatx16 fa[RT];
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) fa[r][q] = 0.0f;
+      const uint4 *wf = md.w_full + (size_t)w * md.wave_stride_full + lane + (size_t)4 * RT * 64;
+#pragma unroll 4
+      for (int sk = 0; sk < 12; ++sk) {
+        uint4 a[RT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) a[r] = wf[((size_t)sk * RT + r) * 64];
+        const uint32_t *xb = pk.nbh + 8 * sk + 4 * (lane >> 5);
+        uint4 bv;
+        bv.x = xb[0]; bv.y = xb[1]; bv.z = xb[2]; bv.w = xb[3];
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+          fa[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[r]),
+                                                         __builtin_bit_cast(bf16x8, bv), fa[r], 0, 0, 0);
+      }
+      if ((lane & 31) == 0) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+          const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              b1s[mbase + 8 * g + e] = auxs[md.bias_off[0] + mbase + 8 * g + e] + fa[r][4 * g + e];
         }
-        b1s[r] = acc;
       }
       b1_p = p;
     }
@@ -1113,7 +1127,6 @@ void vfk_free_model(vf_ctx *c) {
   if (c->pm.w_pack) (void)hipFree(c->pm.w_pack);
   if (c->pm.w_stream) (void)hipFree(c->pm.w_stream);
   if (c->pm.w_stream_fold) (void)hipFree(c->pm.w_stream_fold);
-  if (c->pm.w1_fold) (void)hipFree(c->pm.w1_fold);
   if (c->pm.w_seqT) (void)hipFree(c->pm.w_seqT);
   if (c->pm.aux) (void)hipFree(c->pm.aux);
   c->pm = vf_packed_model();
@@ -1184,8 +1197,8 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
       pm.wave_stride = per_wave / 8;
       pm.fast_rt = rt;
       if (m.dims[0] == 256) {
-        // the same stream with the first layer cut down to the 64 core rows, and the rest of
-        // the first layer on its own, for the scorer that generates its candidates
+        // the same stream with the first layer cut down to the 64 core rows, for the scorer
+        // that generates its candidates (the other rows' weights are read from the whole stream)
         const int fsteps = steps - (m.dims[0] / 16 - 4);
         const size_t per_wave_f = (size_t)(fsteps + pad) * rt * 512;
         VF_HIP(c, hipMalloc((void **)&pm.w_stream_fold, per_wave_f * 8 * sizeof(uint16_t)));
@@ -1194,10 +1207,6 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
                            pm.w_stream_fold);
         VF_HIP(c, hipGetLastError());
         pm.wave_stride_fold = per_wave_f / 8;
-        VF_HIP(c, hipMalloc((void **)&pm.w1_fold, (size_t)96 * m.dims[1] * sizeof(uint32_t)));
-        hipLaunchKernelGGL(k_pack_fold, blocks((size_t)96 * m.dims[1]), dim3(256), 0, st, wdev, m.dims[0], m.dims[1],
-                           pm.w1_fold);
-        VF_HIP(c, hipGetLastError());
       }
     }
     return VF_OK;
@@ -1383,13 +1392,15 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     fd.wave_stride = c->pm.wave_stride; fd.aux = c->pm.aux; fd.wl_off = c->pm.aux_off[7];
     fd.naux = (int)(c->pm.aux_off[7] + m.dims[L - 1]);
     fd.k0 = m.dims[0] / 16;
-    fd.w1_fold = nullptr;
+    fd.w_full = nullptr;
+    fd.wave_stride_full = 0;
     size_t smem_fast = smem + (size_t)fd.naux * 4;
     if (gen_stage >= 0 && c->pm.w_stream_fold) {
       fd.w_stream = reinterpret_cast<const uint4 *>(c->pm.w_stream_fold);
       fd.wave_stride = c->pm.wave_stride_fold;
       fd.k0 = 4;
-      fd.w1_fold = c->pm.w1_fold;
+      fd.w_full = reinterpret_cast<const uint4 *>(c->pm.w_stream);
+      fd.wave_stride_full = c->pm.wave_stride;
       smem_fast = smem + (size_t)((fd.naux + 3) & ~3) * 4 + (size_t)m.dims[1] * 4;
     }
     // persistent: at most one workgroup per CU, each walking its share of the tiles
