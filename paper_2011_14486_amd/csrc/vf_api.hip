@@ -208,7 +208,7 @@ void vf_destroy(vf_ctx *c) {
   (void)hipStreamSynchronize(c->stream);
   free_pipeline(c);
   vfk_free_model(c);
-  void *ps[] = {c->d_space, c->d_err,  c->d_stat, c->d_wlist, c->d_feat,   c->d_act[0], c->d_act[1],
+  void *ps[] = {c->d_space, c->d_err,  c->d_stat, c->d_wlist, c->d_team, c->d_feat,   c->d_act[0], c->d_act[1],
                 c->d_pval,  c->d_pidx, c->d_scores, c->d_tk_val, c->d_tk_idx};
   for (void *p : ps)
     if (p) (void)hipFree(p);
@@ -400,7 +400,7 @@ int vf_greedy_schedule(vf_ctx *c, int first, int last, vf_state *out_states, int
   if (first < 0 || last >= c->S || first > last + 1) return VF_EINVAL;
   if (first != c->n_sched) return VF_ESTATE;
   DeviceGuard g(c->device);
-  if (first <= last && vfk_can_run_whole(c)) {
+  if (first <= last && vfk_whole_team(c) >= 1) {
     int rc = vfk_greedy_whole(c, first, last);
     if (rc != VF_OK) return rc;
     c->n_sched = last + 1;

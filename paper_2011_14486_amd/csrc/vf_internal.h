@@ -99,6 +99,7 @@ struct vf_ctx {
   int32_t *d_feat = nullptr; size_t feat_elems = 0;
   float *d_act[2] = {nullptr, nullptr}; size_t act_elems = 0;
   float *d_pval = nullptr; int32_t *d_pidx = nullptr; size_t part_elems = 0;
+  unsigned int *d_team = nullptr; size_t team_elems = 0;  // team meetings: counters, error flag, per-member minima
   int32_t *d_wlist = nullptr; size_t wlist_elems = 0;  // [B][Mpad] id lists of the whole-schedule launch
 
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
@@ -172,7 +173,7 @@ int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, i
 // Enumerate + featurize + score + partial argmin of one stage in a single kernel (bf16
 // MLPs of uniform hidden width whose input width is the space's F).
 bool vfk_can_fuse_step(const vf_ctx *c);
-bool vfk_can_run_whole(const vf_ctx *c);
+int vfk_whole_team(const vf_ctx *c);
 bool vfk_seq_model(const vf_ctx *c);
 void vfk_seq_free(vf_ctx *c);
 int vfk_seq_sync(vf_ctx *c, int stage);

@@ -413,12 +413,24 @@ struct GenArgs {
 // The valid candidates of a decision are first compacted into an id list (ascending), so
 // that every tile is full of candidates: ids that break a validity rule never reach the
 // network, and no tile has to be tested for being closed.
+// With fewer problems than compute units a team of `team` workgroups shares one problem:
+// every member builds the decision's context and id list for itself, member m scores
+// tiles m, m + team, ... of the list, publishes its minimum, the team meets at a counter
+// in global memory (one arrival per member and layer, bounded wait), and every member then
+// reduces all minima and commits by itself - the members write identical values to the
+// tables and the list, so one meeting per layer is enough.
 struct WholeArgs {
   Tables t;
   int first, last;
   int32_t *list;   // [nprob][Mpad] scratch for the id lists
   int64_t Mpad;
+  int team;                  // workgroups per problem; grid = nprob * team <= compute units when > 1
+  float *team_val;           // [2][nprob][team] per-member minima, by layer parity
+  int32_t *team_idx;
+  unsigned int *team_count;  // [nprob], zero at launch
+  int32_t *team_err;         // set if a wait ran out
 };
+constexpr unsigned int VF_TEAM_SPINS = 1u << 22;
 
 template <int NC, int RT, int PD, bool GEN, bool WHOLE>
 __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
@@ -471,7 +483,11 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   int t_end = (int)((int64_t)(blockIdx.x + 1) * T / gridDim.x);
   int cur_p = -1;
   int ntile_cand = 0;  // WHOLE: entries of the current decision's id list
-  for (int unit = WHOLE ? (int)blockIdx.x : 0; unit < (WHOLE ? nprob : 1); unit += WHOLE ? (int)gridDim.x : 1)
+  const int team = WHOLE ? wa.team : 1, member = WHOLE ? (int)blockIdx.x % team : 0;
+  __shared__ int team_failed;
+  if (WHOLE && tid == 0) team_failed = 0;
+  for (int unit = WHOLE ? (int)blockIdx.x / team : 0; unit < (WHOLE ? nprob : 1);
+       unit += WHOLE ? (int)gridDim.x / team : 1)
   for (int stage = WHOLE ? wa.first : 0; stage <= (WHOLE ? wa.last : 0); ++stage) {
   float run_v = __builtin_inff();  // thread 0: the scan's incumbent over the tiles of this stage
   int32_t run_c = -1;
@@ -536,11 +552,11 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       idlist[k] = cid;
     }
     __syncthreads();
-    t_begin = 0;
+    t_begin = member;
     t_end = (ncand + NC - 1) / NC;  // tiles of the list
     ntile_cand = ncand;
   }
-  for (int t = t_begin; t < t_end; ++t) {
+  for (int t = t_begin; t < t_end; t += team) {
   const int p = WHOLE ? unit : t / nparts;
   const int64_t n0 = WHOLE ? (int64_t)t * NC : (int64_t)(t - p * nparts) * NC;
   const int32_t *xp = x + (size_t)p * prob_stride;
@@ -857,6 +873,37 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   __syncthreads();  // the tile's LDS is free for the next one
   }
   if (WHOLE) {
+    if (team > 1) {
+      // publish this member's minimum, meet the team, reduce everybody's minima
+      const size_t slot0 = ((size_t)(stage & 1) * nprob + unit) * team;
+      if (tid == 0) {
+        wa.team_val[slot0 + member] = run_v;
+        wa.team_idx[slot0 + member] = run_c;
+        __threadfence();
+        atomicAdd(&wa.team_count[unit], 1u);
+        const unsigned int target = (unsigned int)team * (unsigned int)(stage - wa.first + 1);
+        unsigned int spins = 0;
+        while (__hip_atomic_load(&wa.team_count[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+          if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
+          __builtin_amdgcn_s_sleep(2);
+        }
+        __threadfence();
+      }
+      __syncthreads();
+      if (team_failed) return;  // a member never arrived: give up instead of waiting for ever
+      if (tid < 64) {
+        float v = __builtin_inff();
+        int32_t c = -1;
+        for (int m = tid; m < team; m += 64) {
+          const float mv = __hip_atomic_load(&wa.team_val[slot0 + m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const int32_t mc = __hip_atomic_load(&wa.team_idx[slot0 + m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          take_min(v, c, mv, mc);
+        }
+        wave_min(v, c);
+        run_v = v;
+        run_c = c;
+      }
+    }
     // s_i := the winner; the tables it updates are read back by this same workgroup
     // when it builds the next stage's context
     if (tid == 0) commit_winner_call(wa.t, pk.d, pk.sp, unit, stage, run_c, run_v, (uint32_t)M);
@@ -1253,14 +1300,36 @@ int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out) {
 
 // Whole schedules in one launch pay when the problems fill the compute units evenly:
 // each workgroup then owns ceil(B / units) problems from the first layer to the last.
-bool vfk_can_run_whole(const vf_ctx *c) {
-  if (!vfk_can_fuse_step(c)) return false;
+// Workgroups per problem for a whole-schedule launch, 0 = use the per-layer launches.
+// 1 when the problems fill the compute units by themselves (each workgroup then owns
+// ceil(B / units) problems from the first layer to the last; measured break-even against
+// the per-layer launches: about 72 % of the slots filled); with fewer problems a team per
+// problem, as large as the compute units and the tiles of a decision allow, at most 16
+// (measured: 128 problems x 2: 3.6 instead of 4.9 ms per step, 64 x 4: 2.3 instead of 3.4,
+// 32 x 8: 1.9 instead of 2.2; below 16 problems the meetings cost what the launches did).
+int vfk_whole_team(const vf_ctx *c) {
+  if (!vfk_can_fuse_step(c)) return 0;
   int ncu = 256;
   (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
   const int rounds = (c->B + ncu - 1) / ncu;
-  // measured break-even against the per-layer launches: about 72 % of the slots filled
-  return (double)c->B >= 0.72 * (double)rounds * (double)ncu;
+  if ((double)c->B >= 0.72 * (double)rounds * (double)ncu) return 1;
+  if (c->B > ncu / 2 || c->B < 16) return 0;  // a handful of problems: the per-layer launches are as fast
+  int maxw = 0;
+  for (int l = 0; l < c->model.n_layers; ++l) if (c->model.dims[l] > maxw) maxw = c->model.dims[l];
+  const int NC = maxw > 512 ? 64 : 128;
+  const int nparts = (int)((c->M + NC - 1) / NC);
+  int team = ncu / c->B;
+  if (team > nparts) team = nparts;
+  if (team > 16) team = 16;
+  return team >= 2 ? team : 0;
 }
+
+namespace {
+__global__ __launch_bounds__(256) void k_zero_u32(unsigned int *p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+}  // namespace
 
 // Algorithm 1 over stages first..last for every problem of the batch, one launch.
 int vfk_greedy_whole(vf_ctx *c, int first, int last) {
@@ -1271,6 +1340,20 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
     c->wlist_elems = 0;
     if (hipMalloc((void **)&c->d_wlist, want * 4) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
     c->wlist_elems = want;
+  }
+  const int team = vfk_whole_team(c);
+  if (team > 1) {
+    // [count B][err 1][values 2*B*team][ids 2*B*team]
+    const size_t twant = (size_t)c->B + 1 + (size_t)4 * c->B * team;
+    if (twant > c->team_elems) {
+      if (c->d_team) { VF_HIP(c, hipStreamSynchronize(c->stream)); (void)hipFree(c->d_team); c->d_team = nullptr; }
+      c->team_elems = 0;
+      if (hipMalloc((void **)&c->d_team, twant * 4) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
+      c->team_elems = twant;
+    }
+    hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)((c->B + 1 + 255) / 256)), dim3(256), 0, c->stream, c->d_team,
+                       (size_t)c->B + 1);
+    VF_HIP(c, hipGetLastError());
   }
   int rc = score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, &nparts, first, first, first, last);
   c->dec_stage = -1;
@@ -1418,6 +1501,11 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     wa.t = tables_of(c);
     wa.first = whole_first; wa.last = whole_last;
     wa.list = c->d_wlist; wa.Mpad = c->Mpad;
+    wa.team = whole_first >= 0 ? vfk_whole_team(c) : 1;
+    wa.team_count = c->d_team;
+    wa.team_err = reinterpret_cast<int32_t *>(c->d_team) + c->B;
+    wa.team_val = reinterpret_cast<float *>(c->d_team) + c->B + 1;
+    wa.team_idx = reinterpret_cast<int32_t *>(c->d_team) + c->B + 1 + (size_t)2 * c->B * wa.team;
     const bool whole = whole_first >= 0;
     if (gen_stage >= 0 && !whole) {
       int rc2 = vfk_prepare(c, gen_stage);
@@ -1425,7 +1513,7 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     }
     if (whole) {
       kern = wide ? k_mlp_fast<64, 4, 2, true, true> : k_mlp_fast<128, 2, 4, true, true>;
-      grid = dim3((unsigned)(nprob < ncu ? nprob : ncu));
+      grid = wa.team > 1 ? dim3((unsigned)(nprob * wa.team)) : dim3((unsigned)(nprob < ncu ? nprob : ncu));
     } else if (gen_stage >= 0) {
       kern = wide ? k_mlp_fast<64, 4, 2, true, false> : k_mlp_fast<128, 2, 4, true, false>;
     } else {

@@ -360,3 +360,39 @@ def test_whole_schedule_candidate_lists_against_the_checker(vf, ovf, seed):
             pre.append(int(cids[b, i]))
     assert scored == valid == want
     vf.vf_destroy(ctx)
+
+
+@pytest.mark.parametrize("B", [16, 48, 100])
+def test_team_of_workgroups_per_problem(vf, ovf, B):
+    """Between 16 problems and half the compute units vf_greedy_schedule gives every problem a
+    team of workgroups that meet once per layer: same tables as the per-layer launches, with
+    noise, from a prefix, with a problem that ends early; some problems against the checker."""
+    pipes = I.resnet18_batch(B, seed=9)
+    pipes[3, 2, 3] = 2
+    sp = I.make_space([1, 2, 4], [1, 4], [4, 8], [(0, 1, 2), (2, 1, 0)], 2, 2,
+                      [I.ROOT, I.L1, I.L2, I.INLINE], 2, 256)
+    dims = [256, 512, 512, 1]
+    w = I.mlp_weights(dims, 4)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    S = pipes.shape[1]
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipes); vf.vf_set_model(ctx, model, w)
+    for eps in (0.0, 0.1):
+        vf.vf_set_noise(ctx, eps, seed=5)
+        vf.vf_reset_state(ctx)
+        whole = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
+        vf.vf_reset_state(ctx)
+        for i in range(S):
+            vf.vf_argmin_step(ctx, i, True)
+        steps = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=S)]
+        for a, b in zip(whole, steps):
+            assert np.array_equal(a, b)
+        assert (whole[1][3, 2:] == -1).all() and (whole[1][4] >= 0).all()
+        vf.vf_set_state(ctx, whole[1][:, :2])
+        vf.vf_greedy_schedule(ctx, first=2, last=11)
+        pieces = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=12)]
+        assert np.array_equal(whole[0], pieces[0]) and np.array_equal(whole[1], pieces[1])
+        if eps == 0.0:
+            for b in (0, B - 1):
+                compare_schedule(ovf, pipes[b], sp, model, w, whole[1][b], whole[2][b], whole[0][b], TOL[1])
+    vf.vf_destroy(ctx)
