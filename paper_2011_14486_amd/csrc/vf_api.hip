@@ -212,6 +212,7 @@ void vf_destroy(vf_ctx *c) {
                 c->d_pval,  c->d_pidx, c->d_scores, c->d_tk_val, c->d_tk_idx};
   for (void *p : ps)
     if (p) (void)hipFree(p);
+  if (c->h_team_err) (void)hipHostFree(c->h_team_err);
   if (c->ev0) (void)hipEventDestroy(c->ev0);
   if (c->ev1) (void)hipEventDestroy(c->ev1);
   for (auto &v : c->prof_pairs)
@@ -400,6 +401,11 @@ int vf_greedy_schedule(vf_ctx *c, int first, int last, vf_state *out_states, int
   if (first < 0 || last >= c->S || first > last + 1) return VF_EINVAL;
   if (first != c->n_sched) return VF_ESTATE;
   DeviceGuard g(c->device);
+  if (c->h_team_err && *c->h_team_err) {
+    // an earlier launch gave up waiting for a member of a team: its schedules are incomplete
+    *c->h_team_err = 0;
+    return VF_ESTATE;
+  }
   if (first <= last && vfk_whole_team(c) >= 1) {
     int rc = vfk_greedy_whole(c, first, last);
     if (rc != VF_OK) return rc;

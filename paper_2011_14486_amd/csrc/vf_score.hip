@@ -1354,9 +1354,16 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
     hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)((c->B + 1 + 255) / 256)), dim3(256), 0, c->stream, c->d_team,
                        (size_t)c->B + 1);
     VF_HIP(c, hipGetLastError());
+    if (!c->h_team_err) {
+      VF_HIP(c, hipHostMalloc((void **)&c->h_team_err, sizeof(int32_t), hipHostMallocDefault));
+      *c->h_team_err = 0;
+    }
   }
   int rc = score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, &nparts, first, first, first, last);
   c->dec_stage = -1;
+  if (rc == VF_OK && team > 1)  // the flag of a meeting that ran out, for the next call to look at
+    VF_HIP(c, hipMemcpyAsync(c->h_team_err, reinterpret_cast<int32_t *>(c->d_team) + c->B, sizeof(int32_t),
+                             hipMemcpyDeviceToHost, c->stream));
   return rc;
 }
 
