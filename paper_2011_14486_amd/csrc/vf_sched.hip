@@ -128,12 +128,19 @@ __global__ __launch_bounds__(64) void k_prepare(Tables t, int stage, uint32_t *d
 __global__ __launch_bounds__(64) void k_commit(Tables t, int stage, int nparts, const float *pval,
                                                const int32_t *pidx, const int32_t *forced, int commit,
                                                uint32_t M, int32_t *best_cid, float *best_val,
-                                               uint32_t *decpack_next) {
+                                               const uint32_t *decpack_cur, uint32_t *decpack_next) {
   __shared__ DecPack pk;
   Dec &d = pk.d;
   vf_space &sp = pk.sp;
   const int b = blockIdx.x, S = t.S, lane = threadIdx.x;
-  build_dec(d, sp, t, b, stage);
+  if (decpack_cur) {
+    // the decision's context was built for the scorer already: fetch it
+    for (int i = lane; i < VF_DECPACK_DWORDS; i += 64)
+      reinterpret_cast<uint32_t *>(&pk)[i] = decpack_cur[(size_t)b * VF_DECPACK_DWORDS + i];
+    __syncthreads();
+  } else {
+    build_dec(d, sp, t, b, stage);
+  }
   float v = __builtin_inff();
   int32_t c = -1;
   if (forced) {
@@ -440,7 +447,8 @@ int vfk_featurize(vf_ctx *c, int stage, int32_t *feat) {
 int vfk_commit_from_partials(vf_ctx *c, int stage, int nparts, int commit, int32_t *best_cid, float *best_val) {
   vf_prof_scope prof(c, VF_PROF_COMMIT);
   hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), stage, nparts, c->d_pval,
-                     c->d_pidx, (const int32_t *)nullptr, commit, (uint32_t)c->M, best_cid, best_val, c->d_decpack);
+                     c->d_pidx, (const int32_t *)nullptr, commit, (uint32_t)c->M, best_cid, best_val,
+                     c->dec_stage == stage ? (const uint32_t *)c->d_decpack : (const uint32_t *)nullptr, c->d_decpack);
   VF_HIP(c, hipGetLastError());
   if (commit) c->dec_stage = stage + 1 < c->S ? stage + 1 : -1;
   return VF_OK;
@@ -449,7 +457,8 @@ int vfk_commit_from_partials(vf_ctx *c, int stage, int nparts, int commit, int32
 int vfk_commit_forced(vf_ctx *c, int stage) {
   hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), stage, 0,
                      (const float *)nullptr, (const int32_t *)nullptr, (const int32_t *)c->d_forced, 1,
-                     (uint32_t)c->M, (int32_t *)nullptr, (float *)nullptr, (uint32_t *)nullptr);
+                     (uint32_t)c->M, (int32_t *)nullptr, (float *)nullptr, (const uint32_t *)nullptr,
+                     (uint32_t *)nullptr);
   VF_HIP(c, hipGetLastError());
   c->dec_stage = -1;
   return VF_OK;
