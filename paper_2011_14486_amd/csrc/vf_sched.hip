@@ -117,7 +117,7 @@ __global__ __launch_bounds__(256) void k_featurize(Tables t, int stage, uint32_t
   }
 }
 
-// One workgroup (one wave) per problem: pick the winner of the decision (first
+// One workgroup per problem: pick the winner of the decision (first
 // minimum over the partial minima, or a forced id), report it and, if asked, make
 // it s_i: state record, committed feature vector, running sums.
 __global__ __launch_bounds__(64) void k_prepare(Tables t, int stage, uint32_t *decpack) {
@@ -125,7 +125,7 @@ __global__ __launch_bounds__(64) void k_prepare(Tables t, int stage, uint32_t *d
   write_decpack(pk, t, blockIdx.x, stage, decpack);
 }
 
-__global__ __launch_bounds__(64) void k_commit(Tables t, int stage, int nparts, const float *pval,
+__global__ __launch_bounds__(256) void k_commit(Tables t, int stage, int nparts, const float *pval,
                                                const int32_t *pidx, const int32_t *forced, int commit,
                                                uint32_t M, int32_t *best_cid, float *best_val,
                                                const uint32_t *decpack_cur, uint32_t *decpack_next) {
@@ -135,7 +135,7 @@ __global__ __launch_bounds__(64) void k_commit(Tables t, int stage, int nparts, 
   const int b = blockIdx.x, S = t.S, lane = threadIdx.x;
   if (decpack_cur) {
     // the decision's context was built for the scorer already: fetch it
-    for (int i = lane; i < VF_DECPACK_DWORDS; i += 64)
+    for (int i = lane; i < VF_DECPACK_DWORDS; i += (int)blockDim.x)
       reinterpret_cast<uint32_t *>(&pk)[i] = decpack_cur[(size_t)b * VF_DECPACK_DWORDS + i];
     __syncthreads();
   } else {
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(64) void k_commit(Tables t, int stage, int nparts, 
   if (forced) {
     c = forced[(size_t)b * S + stage];
     v = 0.0f;
-  } else {
+  } else if (lane < 64) {  // the first wave reduces the partial minima
     for (int p = lane; p < nparts; p += 64) {
       float pv = pval[(size_t)b * nparts + p];
       int32_t pi = pidx[(size_t)b * nparts + p];
@@ -446,7 +446,7 @@ int vfk_featurize(vf_ctx *c, int stage, int32_t *feat) {
 
 int vfk_commit_from_partials(vf_ctx *c, int stage, int nparts, int commit, int32_t *best_cid, float *best_val) {
   vf_prof_scope prof(c, VF_PROF_COMMIT);
-  hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), stage, nparts, c->d_pval,
+  hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(256), 0, c->stream, tables_of(c), stage, nparts, c->d_pval,
                      c->d_pidx, (const int32_t *)nullptr, commit, (uint32_t)c->M, best_cid, best_val,
                      c->dec_stage == stage ? (const uint32_t *)c->d_decpack : (const uint32_t *)nullptr, c->d_decpack);
   VF_HIP(c, hipGetLastError());
@@ -455,7 +455,7 @@ int vfk_commit_from_partials(vf_ctx *c, int stage, int nparts, int commit, int32
 }
 
 int vfk_commit_forced(vf_ctx *c, int stage) {
-  hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), stage, 0,
+  hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(256), 0, c->stream, tables_of(c), stage, 0,
                      (const float *)nullptr, (const int32_t *)nullptr, (const int32_t *)c->d_forced, 1,
                      (uint32_t)c->M, (int32_t *)nullptr, (float *)nullptr, (const uint32_t *)nullptr,
                      (uint32_t *)nullptr);
