@@ -661,7 +661,8 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       if (part == 0) {
         // evaluated for padding ids too: core must be defined before put reads it
         const bool valid = eval_candidate<true>(dctx, sp, cid, dec, core);
-        okf[n] = inb && valid;
+        // WHOLE: the flag of a valid column carries its candidate id (+1) for the scan
+        okf[n] = (inb && valid) ? (WHOLE ? (int32_t)cid + 1 : 1) : 0;
         put(core, 0);
         put8(core + 40, 40);
       } else if (part == 1) {
@@ -834,7 +835,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       if (scores && (GEN ? (n0 + tid) < ld_scores : (n0 + tid) < M))
         scores[(size_t)p * ld_scores + n0 + tid] = (GEN && okf[tid] == 0) ? __builtin_inff() : s;
       // the candidate id of this column (WHOLE: from the decision's id list)
-      const int32_t colid = (WHOLE && okf[tid] != 0) ? idlist[n0 + tid] : (int32_t)(n0 + tid);
+      const int32_t colid = WHOLE ? okf[tid] - 1 : (int32_t)(n0 + tid);
       if (na.eps != 0.0f) s = add_noise(na, s, p, colid);
       if (okf[tid] != 0 && s < v) { v = s; c = colid; }
       wave_min(v, c);

@@ -20,12 +20,29 @@ __device__ __forceinline__ float relu_keep_nan(float v) { return v < 0.0f ? 0.0f
 __device__ __forceinline__ void take_min(float &v, int32_t &c, float ov, int32_t oc) {
   if (oc >= 0 && (ov < v || (ov == v && (c < 0 || oc < c)))) { v = ov; c = oc; }
 }
+// Minimum pair of a full wave, left in every lane.  Rows of 16 lanes reduce by data-parallel
+// lane shifts (lane i takes lane i - n; a lane without a source keeps its own pair), the four
+// row results are then read from lanes 15, 31, 47 and 63.  All 64 lanes must be active.
 __device__ __forceinline__ void wave_min(float &v, int32_t &c) {
-  for (int off = 32; off > 0; off >>= 1) {
-    float ov = __shfl_down(v, off);
-    int32_t oc = __shfl_down(c, off);
-    take_min(v, c, ov, oc);
+#define VF_ROW_SHR_MIN(ctrl)                                                                              \
+  {                                                                                                       \
+    const float ov = __int_as_float(                                                                      \
+        __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), ctrl, 0xf, 0xf, false));        \
+    const int32_t oc = __builtin_amdgcn_update_dpp(c, c, ctrl, 0xf, 0xf, false);                          \
+    take_min(v, c, ov, oc);                                                                               \
   }
+  VF_ROW_SHR_MIN(0x111)
+  VF_ROW_SHR_MIN(0x112)
+  VF_ROW_SHR_MIN(0x114)
+  VF_ROW_SHR_MIN(0x118)
+#undef VF_ROW_SHR_MIN
+  float rv = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 15));
+  int32_t rc = __builtin_amdgcn_readlane(c, 15);
+  take_min(rv, rc, __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 31)), __builtin_amdgcn_readlane(c, 31));
+  take_min(rv, rc, __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 47)), __builtin_amdgcn_readlane(c, 47));
+  take_min(rv, rc, __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 63)), __builtin_amdgcn_readlane(c, 63));
+  v = rv;
+  c = rc;
 }
 
 // gate non-linearities of the recurrent network, fp32
