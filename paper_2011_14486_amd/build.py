@@ -9,7 +9,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libvf.so")
-SOURCES = ["vf_api.hip", "vf_sched.hip", "vf_score.hip", "vf_lstm.hip"]
+SOURCES = ["vf_api.hip", "vf_sched.hip", "vf_score.hip", "vf_whole.hip", "vf_lstm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-Wall", "-Wno-unused-command-line-argument"]

@@ -150,6 +150,22 @@ struct vf_prof_scope {
   } while (0)
 
 // ---- vf_sched.hip: enumeration, featurization, commit ----
+// A packed bf16 MLP with uniform hidden width, as the fused scoring kernels take it.
+struct vf_fast_dev {
+  int L;
+  int dims[8];
+  const uint4 *w_stream;   // per wave: [layer][k step][row tile r][lane] fragments
+  size_t wave_stride;      // in uint4
+  const float *aux;
+  int naux;                // floats in aux (biases of all layers, output vector)
+  size_t bias_off[8];
+  size_t wl_off;
+  int k0;                  // k-steps of the first layer present in w_stream
+  const uint4 *w_full;     // nullable (fold): the stream with the whole first layer; its k-steps 4..15 of
+  size_t wave_stride_full; // layer 0 are the weights of input rows 64..255
+};
+void vfk_fast_dev(const vf_ctx *c, bool generating, vf_fast_dev *fd, int *ks, int *NC);
+
 int vfk_setup_tables(vf_ctx *c);
 int vfk_reset_state(vf_ctx *c);
 int vfk_enumerate(vf_ctx *c, int stage, uint32_t *dec, uint8_t *valid, int32_t *n_valid);

@@ -133,13 +133,6 @@ __global__ __launch_bounds__(256) void k_copy_f32(const float *src, float *dst, 
   if (i < n) dst[i] = round_bf16 ? bf16_val(src[i]) : src[i];
 }
 
-// ReLU on the bit pattern: negative values (sign bit set, including -0) become +0,
-// everything else, NaN included, is kept
-__device__ __forceinline__ float relu_bits(float v) {
-  int32_t i = __float_as_int(v);
-  return __int_as_float(i < 0 ? 0 : i);
-}
-
 // The whole MLP for a tile of NC candidates.  8 waves; wave w owns the output row
 // tiles w, w+8, ... (at most RT of them) of every hidden layer and all NC/32 candidate
 // column tiles.  The weight fragments of a wave form one stream over all layers; a
@@ -346,24 +339,11 @@ __global__ __launch_bounds__(512) void k_mlp_bf16(const int32_t *x, int64_t prob
 
 // ------------------------------------------------- bf16 MLP, uniform hidden width
 
-struct FastDev {
-  int L;
-  int dims[8];
-  const uint4 *w_stream;   // per wave: [layer][k step][row tile r][lane] fragments
-  size_t wave_stride;      // in uint4
-  const float *aux;
-  int naux;                // floats in aux (biases of all layers, output vector)
-  size_t bias_off[8];
-  size_t wl_off;
-  int k0;                  // k-steps of the first layer present in w_stream
-  const uint4 *w_full;     // nullable (fold): the stream with the whole first layer; its k-steps 4..15 of
-  size_t wave_stride_full; // layer 0 are the weights of input rows 64..255
-};
 
 // Stream order for k_mlp_fast: wave w's fragments of all hidden layers back to back,
 // out[w][step][r][lane][e] with step running over (layer, k step) and row tile
 // w + 8 r; `pad` zero steps follow so that the prefetch never leaves the buffer.
-__global__ __launch_bounds__(256) void k_pack_stream(const float *blob, FastDev md, int RT, int steps_total,
+__global__ __launch_bounds__(256) void k_pack_stream(const float *blob, vf_fast_dev md, int RT, int steps_total,
                                                      int pad, uint16_t *out) {
   // md.k0: only the first md.k0 k-steps of the first layer are packed
   const size_t per_wave = (size_t)(steps_total + pad) * RT * 512;
@@ -406,38 +386,11 @@ struct GenArgs {
   unsigned long long *stat; // nullable: [0] += ids pushed through the network, [1] += valid ones
 };
 
-// WHOLE (with GEN): the workgroup owns whole problems and runs Algorithm 1 on each of
-// them from stage wa.first to wa.last by itself - decision context, all tiles of the
-// stage, the scan's running minimum, the commit - so that a schedule costs one launch
-// instead of two per layer.  Pays when there are about as many problems as compute units.
-// The valid candidates of a decision are first compacted into an id list (ascending), so
-// that every tile is full of candidates: ids that break a validity rule never reach the
-// network, and no tile has to be tested for being closed.
-// With fewer problems than compute units a team of `team` workgroups shares one problem:
-// every member builds the decision's context and id list for itself, member m scores
-// tiles m, m + team, ... of the list, publishes its minimum, the team meets at a counter
-// in global memory (one arrival per member and layer, bounded wait), and every member then
-// reduces all minima and commits by itself - the members write identical values to the
-// tables and the list, so one meeting per layer is enough.
-struct WholeArgs {
-  Tables t;
-  int first, last;
-  int32_t *list;   // [nprob][Mpad] scratch for the id lists
-  int64_t Mpad;
-  int team;                  // workgroups per problem; grid = nprob * team <= compute units when > 1
-  float *team_val;           // [2][nprob][team] per-member minima, by layer parity
-  int32_t *team_idx;
-  unsigned int *team_count;  // [nprob], zero at launch
-  int32_t *team_err;         // set if a wait ran out
-};
-constexpr unsigned int VF_TEAM_SPINS = 1u << 22;
-
-template <int NC, int RT, int PD, bool GEN, bool WHOLE>
+template <int NC, int RT, int PD, bool GEN>
 __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
-                                                  int use_valid_row, FastDev md, int ks, float *scores,
+                                                  int use_valid_row, vf_fast_dev md, int ks, float *scores,
                                                   int64_t ld_scores, float *pval, int32_t *pidx, int nparts,
-                                                  int nprob, GenArgs ga, NoiseArgs na, WholeArgs wa) {
-  static_assert(GEN || !WHOLE, "whole schedules need the generating form");
+                                                  int nprob, GenArgs ga, NoiseArgs na) {
   constexpr int CT = NC / 32;
   constexpr int SEGS = 512 / NC;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -479,86 +432,12 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   // ---- persistent loop: this workgroup's share of the (problem, tile) pairs, in
   // problem-major order so that consecutive tiles mostly share the decision context
   const int T = nparts * nprob;
-  int t_begin = (int)((int64_t)blockIdx.x * T / gridDim.x);
-  int t_end = (int)((int64_t)(blockIdx.x + 1) * T / gridDim.x);
+  const int t_begin = (int)((int64_t)blockIdx.x * T / gridDim.x);
+  const int t_end = (int)((int64_t)(blockIdx.x + 1) * T / gridDim.x);
   int cur_p = -1;
-  int ntile_cand = 0;  // WHOLE: entries of the current decision's id list
-  const int team = WHOLE ? wa.team : 1, member = WHOLE ? (int)blockIdx.x % team : 0;
-  __shared__ int team_failed;
-  if (WHOLE && tid == 0) team_failed = 0;
-  for (int unit = WHOLE ? (int)blockIdx.x / team : 0; unit < (WHOLE ? nprob : 1);
-       unit += WHOLE ? (int)gridDim.x / team : 1)
-  for (int stage = WHOLE ? wa.first : 0; stage <= (WHOLE ? wa.last : 0); ++stage) {
-  float run_v = __builtin_inff();  // thread 0: the scan's incumbent over the tiles of this stage
-  int32_t run_c = -1;
-  int32_t *const idlist = WHOLE ? wa.list + (size_t)unit * wa.Mpad : nullptr;
-  if (WHOLE) {
-    fill_decpack(pk, wa.t, unit, stage);
-    cur_p = unit;
-    b1_p = -1;
-    na.stage = stage;
-    // Ordered list of the decision's valid ids, written down directly from the validity
-    // rules: per (compute_at, store_at) digit pair that is open - the level is offered and
-    // the hoist does not exceed it - the valid ids are the products of the split factors
-    // that fit the level's region with every loop order / vectorize / parallel choice;
-    // an inlining pair has the single id with every other digit zero.
-    __shared__ int ncand, g_npairs;
-    __shared__ int g_pos[13], g_base[12], g_cat[12];
-    __shared__ int g_nok[3][3], g_ok[3][3][8];
-    if (tid < 9) {
-      const int lvl = tid / 3, dd = tid % 3;
-      int cnt = 0;
-      for (int k = 0; k < pk.sp.nf[dd]; ++k)
-        if ((uint32_t)pk.sp.fac[dd][k] <= pk.d.E[lvl][dd]) g_ok[lvl][dd][cnt++] = k;
-      g_nok[lvl][dd] = cnt;
-    }
-    __syncthreads();
-    const int rest_n = pk.sp.nperm * pk.sp.nvec * pk.sp.npar;
-    const int run_n = pk.sp.nf[0] * pk.sp.nf[1] * pk.sp.nf[2] * rest_n;
-    if (tid == 0) {
-      int np = 0, pos = 0;
-      for (int isat = 0; isat < pk.sp.nsat; ++isat)
-        for (int icat = 0; icat < pk.sp.ncat; ++icat) {
-          const int cat = pk.sp.cat[icat];
-          if (pk.d.lvl_ok[cat] == 0) continue;
-          int cnt = 0;
-          if (cat == VF_INLINE) cnt = isat == 0 ? 1 : 0;
-          else if (isat <= cat) cnt = g_nok[cat][0] * g_nok[cat][1] * g_nok[cat][2] * rest_n;
-          if (cnt == 0) continue;
-          g_pos[np] = pos;
-          g_base[np] = (icat + pk.sp.ncat * isat) * run_n;
-          g_cat[np] = cat;
-          pos += cnt;
-          ++np;
-        }
-      g_pos[np] = pos;
-      g_npairs = np;
-      ncand = pos;
-    }
-    __syncthreads();
-    for (int k = tid; k < ncand; k += 512) {
-      int q = 0;
-      while (q + 1 < g_npairs && k >= g_pos[q + 1]) ++q;
-      const int cat = g_cat[q];
-      int cid = g_base[q];
-      if (cat != VF_INLINE) {
-        int r = k - g_pos[q];
-        const int nx = g_nok[cat][0], ny = g_nok[cat][1], nc = g_nok[cat][2];
-        const int jx = r % nx; r /= nx;
-        const int jy = r % ny; r /= ny;
-        const int jc = r % nc; r /= nc;
-        cid += g_ok[cat][0][jx] + pk.sp.nf[0] * (g_ok[cat][1][jy] + pk.sp.nf[1] * (g_ok[cat][2][jc] + pk.sp.nf[2] * r));
-      }
-      idlist[k] = cid;
-    }
-    __syncthreads();
-    t_begin = member;
-    t_end = (ncand + NC - 1) / NC;  // tiles of the list
-    ntile_cand = ncand;
-  }
-  for (int t = t_begin; t < t_end; t += team) {
-  const int p = WHOLE ? unit : t / nparts;
-  const int64_t n0 = WHOLE ? (int64_t)t * NC : (int64_t)(t - p * nparts) * NC;
+  for (int t = t_begin; t < t_end; ++t) {
+  const int p = t / nparts;
+  const int64_t n0 = (int64_t)(t - p * nparts) * NC;
   const int32_t *xp = x + (size_t)p * prob_stride;
   if (GEN && p != cur_p) {
     if (tid < VF_DECPACK_DWORDS)
@@ -572,9 +451,9 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     // stages whole compute_at levels are closed, and that digit is the most significant
     // but one, so such ids come in runs much longer than a tile.
     const int64_t nend = (n0 + NC < M) ? n0 + NC : M;
-    if (!WHOLE && range_closed(pk.d, pk.sp, (uint32_t)n0, (uint32_t)(nend > n0 ? nend : n0))) {
+    if (range_closed(pk.d, pk.sp, (uint32_t)n0, (uint32_t)(nend > n0 ? nend : n0))) {
       if (scores && tid < NC && (n0 + tid) < ld_scores) scores[(size_t)p * ld_scores + n0 + tid] = __builtin_inff();
-      if (!WHOLE && tid == 0) {
+      if (tid == 0) {
         pval[(size_t)t] = __builtin_inff();
         pidx[(size_t)t] = -1;
       }
@@ -627,9 +506,8 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     // thread does not store are dead code in its copy of the evaluation
     {
       const int n = tid % NC, part = tid / NC;
-      // WHOLE: column n is entry n0 + n of the id list (padding columns evaluate id 0)
-      const bool inb = WHOLE ? (n0 + n) < ntile_cand : (n0 + n) < M;
-      const uint32_t cid = WHOLE ? (inb ? (uint32_t)idlist[n0 + n] : 0u) : (uint32_t)(n0 + n);
+      const bool inb = (n0 + n) < M;
+      const uint32_t cid = (uint32_t)(n0 + n);
       int32_t core[64];
       uint32_t dec;
       auto put = [&](const int32_t *v, int row0) {
@@ -661,8 +539,7 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       if (part == 0) {
         // evaluated for padding ids too: core must be defined before put reads it
         const bool valid = eval_candidate<true>(dctx, sp, cid, dec, core);
-        // WHOLE: the flag of a valid column carries its candidate id (+1) for the scan
-        okf[n] = (inb && valid) ? (WHOLE ? (int32_t)cid + 1 : 1) : 0;
+        okf[n] = inb && valid;
         put(core, 0);
         put8(core + 40, 40);
       } else if (part == 1) {
@@ -834,14 +711,13 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       // scores of a generated tile are masked: invalid candidates and padding read +inf
       if (scores && (GEN ? (n0 + tid) < ld_scores : (n0 + tid) < M))
         scores[(size_t)p * ld_scores + n0 + tid] = (GEN && okf[tid] == 0) ? __builtin_inff() : s;
-      // the candidate id of this column (WHOLE: from the decision's id list)
-      const int32_t colid = WHOLE ? okf[tid] - 1 : (int32_t)(n0 + tid);
+      const int32_t colid = (int32_t)(n0 + tid);
       if (na.eps != 0.0f) s = add_noise(na, s, p, colid);
       if (okf[tid] != 0 && s < v) { v = s; c = colid; }
       wave_min(v, c);
       if (GEN && ga.stat) {
         const int nvalid = __popcll(__ballot(okf[tid] != 0));
-        const int nin = __popcll(__ballot(WHOLE ? (n0 + tid) < ntile_cand : (n0 + tid) < M));
+        const int nin = __popcll(__ballot((n0 + tid) < M));
         if (lane == 0) {
           atomicAdd(&ga.stat[0], (unsigned long long)nin);
           atomicAdd(&ga.stat[1], (unsigned long long)nvalid);
@@ -855,62 +731,15 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       __syncthreads();
       if (tid == 0) {
         for (int k = 1; k < NC / 64; ++k) take_min(v, c, sv[k], sc[k]);
-        if (WHOLE) {
-          take_min(run_v, run_c, v, c);
-        } else {
-          pval[(size_t)t] = v;
-          pidx[(size_t)t] = c;
-        }
-      }
-    } else if (tid == 0) {
-      if (WHOLE) {
-        take_min(run_v, run_c, v, c);
-      } else {
         pval[(size_t)t] = v;
         pidx[(size_t)t] = c;
       }
+    } else if (tid == 0) {
+      pval[(size_t)t] = v;
+      pidx[(size_t)t] = c;
     }
   }
   __syncthreads();  // the tile's LDS is free for the next one
-  }
-  if (WHOLE) {
-    if (team > 1) {
-      // publish this member's minimum, meet the team, reduce everybody's minima
-      const size_t slot0 = ((size_t)(stage & 1) * nprob + unit) * team;
-      if (tid == 0) {
-        wa.team_val[slot0 + member] = run_v;
-        wa.team_idx[slot0 + member] = run_c;
-        __threadfence();
-        atomicAdd(&wa.team_count[unit], 1u);
-        const unsigned int target = (unsigned int)team * (unsigned int)(stage - wa.first + 1);
-        unsigned int spins = 0;
-        while (__hip_atomic_load(&wa.team_count[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-          if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
-          __builtin_amdgcn_s_sleep(2);
-        }
-        __threadfence();
-      }
-      __syncthreads();
-      if (team_failed) return;  // a member never arrived: give up instead of waiting for ever
-      if (tid < 64) {
-        float v = __builtin_inff();
-        int32_t c = -1;
-        for (int m = tid; m < team; m += 64) {
-          const float mv = __hip_atomic_load(&wa.team_val[slot0 + m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          const int32_t mc = __hip_atomic_load(&wa.team_idx[slot0 + m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          take_min(v, c, mv, mc);
-        }
-        wave_min(v, c);
-        run_v = v;
-        run_c = c;
-      }
-    }
-    // s_i := the winner; the tables it updates are read back by this same workgroup
-    // when it builds the next stage's context
-    if (tid == 0) commit_winner_call(wa.t, pk.d, pk.sp, unit, stage, run_c, run_v, (uint32_t)M);
-    __threadfence();
-    __syncthreads();
-  }
   }
 }
 
@@ -1236,7 +1065,7 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
       const int pad = 8;
       const size_t per_wave = (size_t)(steps + pad) * rt * 512;
       VF_HIP(c, hipMalloc((void **)&pm.w_stream, per_wave * 8 * sizeof(uint16_t)));
-      FastDev fd;
+      vf_fast_dev fd;
       fd.L = L;
       for (int l = 0; l < 8; ++l) fd.dims[l] = m.dims[l];
       fd.k0 = m.dims[0] / 16;
@@ -1283,11 +1112,11 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
 
 static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
                      int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage,
-                     int noise_stage, int whole_first, int whole_last);
+                     int noise_stage);
 
 int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
                   int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int noise_stage) {
-  return score_mlp(c, x, prob_stride, nprob, M, ld, use_valid_row, scores, ld_scores, nparts_out, -1, noise_stage, -1, -1);
+  return score_mlp(c, x, prob_stride, nprob, M, ld, use_valid_row, scores, ld_scores, nparts_out, -1, noise_stage);
 }
 
 bool vfk_can_fuse_step(const vf_ctx *c) {
@@ -1296,76 +1125,7 @@ bool vfk_can_fuse_step(const vf_ctx *c) {
 }
 
 int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out) {
-  return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, nparts_out, stage, stage, -1, -1);
-}
-
-// Whole schedules in one launch pay when the problems fill the compute units evenly:
-// each workgroup then owns ceil(B / units) problems from the first layer to the last.
-// Workgroups per problem for a whole-schedule launch, 0 = use the per-layer launches.
-// 1 when the problems fill the compute units by themselves (each workgroup then owns
-// ceil(B / units) problems from the first layer to the last; measured break-even against
-// the per-layer launches: about 72 % of the slots filled); with fewer problems a team per
-// problem, as large as the compute units and the tiles of a decision allow, at most 16
-// (measured: 128 problems x 2: 3.6 instead of 4.9 ms per step, 64 x 4: 2.3 instead of 3.4,
-// 32 x 8: 1.9 instead of 2.2; below 16 problems the meetings cost what the launches did).
-int vfk_whole_team(const vf_ctx *c) {
-  if (!vfk_can_fuse_step(c)) return 0;
-  int ncu = 256;
-  (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
-  const int rounds = (c->B + ncu - 1) / ncu;
-  if ((double)c->B >= 0.72 * (double)rounds * (double)ncu) return 1;
-  if (c->B > ncu / 2 || c->B < 16) return 0;  // a handful of problems: the per-layer launches are as fast
-  int maxw = 0;
-  for (int l = 0; l < c->model.n_layers; ++l) if (c->model.dims[l] > maxw) maxw = c->model.dims[l];
-  const int NC = maxw > 512 ? 64 : 128;
-  const int nparts = (int)((c->M + NC - 1) / NC);
-  int team = ncu / c->B;
-  if (team > nparts) team = nparts;
-  if (team > 16) team = 16;
-  return team >= 2 ? team : 0;
-}
-
-namespace {
-__global__ __launch_bounds__(256) void k_zero_u32(unsigned int *p, size_t n) {
-  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-  if (i < n) p[i] = 0u;
-}
-}  // namespace
-
-// Algorithm 1 over stages first..last for every problem of the batch, one launch.
-int vfk_greedy_whole(vf_ctx *c, int first, int last) {
-  int nparts = 0;
-  const size_t want = (size_t)c->B * c->Mpad;
-  if (want > c->wlist_elems) {
-    if (c->d_wlist) { VF_HIP(c, hipStreamSynchronize(c->stream)); (void)hipFree(c->d_wlist); c->d_wlist = nullptr; }
-    c->wlist_elems = 0;
-    if (hipMalloc((void **)&c->d_wlist, want * 4) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
-    c->wlist_elems = want;
-  }
-  const int team = vfk_whole_team(c);
-  if (team > 1) {
-    // [count B][err 1][values 2*B*team][ids 2*B*team]
-    const size_t twant = (size_t)c->B + 1 + (size_t)4 * c->B * team;
-    if (twant > c->team_elems) {
-      if (c->d_team) { VF_HIP(c, hipStreamSynchronize(c->stream)); (void)hipFree(c->d_team); c->d_team = nullptr; }
-      c->team_elems = 0;
-      if (hipMalloc((void **)&c->d_team, twant * 4) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
-      c->team_elems = twant;
-    }
-    hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)((c->B + 1 + 255) / 256)), dim3(256), 0, c->stream, c->d_team,
-                       (size_t)c->B + 1);
-    VF_HIP(c, hipGetLastError());
-    if (!c->h_team_err) {
-      VF_HIP(c, hipHostMalloc((void **)&c->h_team_err, sizeof(int32_t), hipHostMallocDefault));
-      *c->h_team_err = 0;
-    }
-  }
-  int rc = score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, &nparts, first, first, first, last);
-  c->dec_stage = -1;
-  if (rc == VF_OK && team > 1)  // the flag of a meeting that ran out, for the next call to look at
-    VF_HIP(c, hipMemcpyAsync(c->h_team_err, reinterpret_cast<int32_t *>(c->d_team) + c->B, sizeof(int32_t),
-                             hipMemcpyDeviceToHost, c->stream));
-  return rc;
+  return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, nparts_out, stage, stage);
 }
 
 namespace {
@@ -1387,7 +1147,7 @@ int vfk_step_scores(vf_ctx *c, int stage) {
   if (rc != VF_OK) return rc;
   int nparts = 0;
   if (vfk_seq_model(c)) return vfk_seq_step(c, stage, c->d_scores, c->Mpad, -1, &nparts);
-  if (vfk_can_fuse_step(c)) return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, stage, -1, -1, -1);
+  if (vfk_can_fuse_step(c)) return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, stage, -1);
   // general models: materialise the features, score, mask
   const size_t fwant = (size_t)c->B * c->space.F * c->Mpad;
   rc = grow(c, c->d_feat, c->feat_elems, fwant);
@@ -1395,7 +1155,7 @@ int vfk_step_scores(vf_ctx *c, int stage) {
   rc = vfk_featurize(c, stage, c->d_feat);
   if (rc != VF_OK) return rc;
   const int64_t fstride = (int64_t)c->space.F * c->Mpad;
-  rc = score_mlp(c, c->d_feat, fstride, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, -1, -1, -1, -1);
+  rc = score_mlp(c, c->d_feat, fstride, c->B, c->M, c->Mpad, 1, c->d_scores, c->Mpad, &nparts, -1, -1);
   if (rc != VF_OK) return rc;
   hipLaunchKernelGGL(k_mask_scores, dim3((unsigned)((c->Mpad + 255) / 256), (unsigned)c->B), dim3(256), 0, c->stream,
                      c->d_scores, c->d_feat, fstride, c->M, c->Mpad);
@@ -1403,9 +1163,37 @@ int vfk_step_scores(vf_ctx *c, int stage) {
   return VF_OK;
 }
 
+// The packed bf16 MLP as the fused kernels take it.  generating: the candidates' 64 core
+// rows are produced in the kernel, so with 256 input rows the first layer is cut down to
+// them (k0 = 4) and the other rows' weights are handed over separately (w_full).
+// ks / NC (nullable): row stride of the activation tile in LDS, candidates per tile.
+void vfk_fast_dev(const vf_ctx *c, bool generating, vf_fast_dev *fd, int *ks, int *NC) {
+  const vf_model &m = c->model;
+  const int L = m.n_layers;
+  fd->L = L;
+  for (int l = 0; l < 8; ++l) { fd->dims[l] = m.dims[l]; fd->bias_off[l] = c->pm.aux_off[l]; }
+  fd->w_stream = reinterpret_cast<const uint4 *>(c->pm.w_stream);
+  fd->wave_stride = c->pm.wave_stride; fd->aux = c->pm.aux; fd->wl_off = c->pm.aux_off[7];
+  fd->naux = (int)(c->pm.aux_off[7] + m.dims[L - 1]);
+  fd->k0 = m.dims[0] / 16;
+  fd->w_full = nullptr;
+  fd->wave_stride_full = 0;
+  if (generating && c->pm.w_stream_fold) {
+    fd->w_stream = reinterpret_cast<const uint4 *>(c->pm.w_stream_fold);
+    fd->wave_stride = c->pm.wave_stride_fold;
+    fd->k0 = 4;
+    fd->w_full = reinterpret_cast<const uint4 *>(c->pm.w_stream);
+    fd->wave_stride_full = c->pm.wave_stride;
+  }
+  int maxw = 0;
+  for (int l = 0; l < L; ++l) if (m.dims[l] > maxw) maxw = m.dims[l];
+  if (ks) *ks = maxw + 8;
+  if (NC) *NC = maxw > 512 ? 64 : 128;
+}
+
 static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
                      int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage,
-                     int noise_stage, int whole_first, int whole_last) {
+                     int noise_stage) {
   NoiseArgs na;
   na.eps = noise_stage >= 0 ? c->noise_eps : 0.0f;
   na.k0 = (uint32_t)c->noise_seed; na.k1 = (uint32_t)(c->noise_seed >> 32);
@@ -1477,59 +1265,30 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
   const size_t smem = (size_t)NC * ks * 2 + (size_t)8 * NC * 4 + (size_t)NC * 4;
   if (nparts > 0 && c->pm.fast_rt) {
     vf_prof_scope prof(c, VF_PROF_SCORE);
-    FastDev fd;
-    fd.L = L;
-    for (int l = 0; l < 8; ++l) { fd.dims[l] = m.dims[l]; fd.bias_off[l] = c->pm.aux_off[l]; }
-    fd.w_stream = reinterpret_cast<const uint4 *>(c->pm.w_stream);
-    fd.wave_stride = c->pm.wave_stride; fd.aux = c->pm.aux; fd.wl_off = c->pm.aux_off[7];
-    fd.naux = (int)(c->pm.aux_off[7] + m.dims[L - 1]);
-    fd.k0 = m.dims[0] / 16;
-    fd.w_full = nullptr;
-    fd.wave_stride_full = 0;
+    vf_fast_dev fd;
+    vfk_fast_dev(c, gen_stage >= 0, &fd, nullptr, nullptr);
     size_t smem_fast = smem + (size_t)fd.naux * 4;
-    if (gen_stage >= 0 && c->pm.w_stream_fold) {
-      fd.w_stream = reinterpret_cast<const uint4 *>(c->pm.w_stream_fold);
-      fd.wave_stride = c->pm.wave_stride_fold;
-      fd.k0 = 4;
-      fd.w_full = reinterpret_cast<const uint4 *>(c->pm.w_stream);
-      fd.wave_stride_full = c->pm.wave_stride;
-      smem_fast = smem + (size_t)((fd.naux + 3) & ~3) * 4 + (size_t)m.dims[1] * 4;
-    }
+    if (fd.w_full) smem_fast = smem + (size_t)((fd.naux + 3) & ~3) * 4 + (size_t)m.dims[1] * 4;
     // persistent: at most one workgroup per CU, each walking its share of the tiles
     int ncu = 256;
     (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
     const int64_t tiles = (int64_t)nparts * nprob;
     dim3 grid((unsigned)(tiles < ncu ? tiles : ncu));
-    void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, FastDev, int, float *, int64_t, float *, int32_t *, int,
-                 int, GenArgs, NoiseArgs, WholeArgs);
+    void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, vf_fast_dev, int, float *, int64_t, float *, int32_t *, int,
+                 int, GenArgs, NoiseArgs);
     GenArgs ga;
     ga.decpack = c->d_decpack;
     ga.stat = c->profiling ? c->d_stat : nullptr;
-    WholeArgs wa;
-    wa.t = tables_of(c);
-    wa.first = whole_first; wa.last = whole_last;
-    wa.list = c->d_wlist; wa.Mpad = c->Mpad;
-    wa.team = whole_first >= 0 ? vfk_whole_team(c) : 1;
-    wa.team_count = c->d_team;
-    wa.team_err = reinterpret_cast<int32_t *>(c->d_team) + c->B;
-    wa.team_val = reinterpret_cast<float *>(c->d_team) + c->B + 1;
-    wa.team_idx = reinterpret_cast<int32_t *>(c->d_team) + c->B + 1 + (size_t)2 * c->B * wa.team;
-    const bool whole = whole_first >= 0;
-    if (gen_stage >= 0 && !whole) {
+    if (gen_stage >= 0) {
       int rc2 = vfk_prepare(c, gen_stage);
       if (rc2 != VF_OK) return rc2;
-    }
-    if (whole) {
-      kern = wide ? k_mlp_fast<64, 4, 2, true, true> : k_mlp_fast<128, 2, 4, true, true>;
-      grid = wa.team > 1 ? dim3((unsigned)(nprob * wa.team)) : dim3((unsigned)(nprob < ncu ? nprob : ncu));
-    } else if (gen_stage >= 0) {
-      kern = wide ? k_mlp_fast<64, 4, 2, true, false> : k_mlp_fast<128, 2, 4, true, false>;
+      kern = wide ? k_mlp_fast<64, 4, 2, true> : k_mlp_fast<128, 2, 4, true>;
     } else {
-      kern = wide ? k_mlp_fast<64, 4, 2, false, false> : k_mlp_fast<128, 2, 4, false, false>;
+      kern = wide ? k_mlp_fast<64, 4, 2, false> : k_mlp_fast<128, 2, 4, false>;
     }
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_fast));
     hipLaunchKernelGGL(kern, grid, dim3(512), smem_fast, st, x, prob_stride, M, ld, use_valid_row, fd, ks, scores,
-                       ld_scores, c->d_pval, c->d_pidx, nparts, nprob, ga, na, wa);
+                       ld_scores, c->d_pval, c->d_pidx, nparts, nprob, ga, na);
     VF_HIP(c, hipGetLastError());
   } else if (nparts > 0) {
     vf_prof_scope prof(c, VF_PROF_SCORE);

@@ -16,6 +16,13 @@ __device__ __forceinline__ uint32_t bf16_bits(float v) {
 __device__ __forceinline__ float bf16_val(float v) { return __uint_as_float(bf16_bits(v) << 16); }
 __device__ __forceinline__ float relu_keep_nan(float v) { return v < 0.0f ? 0.0f : v; }
 
+// ReLU on the bit pattern: negative values (sign bit set, including -0) become +0,
+// everything else, NaN included, is kept
+__device__ __forceinline__ float relu_bits(float v) {
+  int32_t i = __float_as_int(v);
+  return __int_as_float(i < 0 ? 0 : i);
+}
+
 // (value, id) ordering of the scan: smaller value first, then smaller id; id < 0 = none
 __device__ __forceinline__ void take_min(float &v, int32_t &c, float ov, int32_t oc) {
   if (oc >= 0 && (ov < v || (ov == v && (c < 0 || oc < c)))) { v = ov; c = oc; }

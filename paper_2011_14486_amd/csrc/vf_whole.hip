@@ -1,0 +1,551 @@
+// Algorithm 1 for whole problems in one launch (gfx950): a workgroup (or a team of
+// workgroups) owns a problem from its first undecided stage to the last and does every
+// step of the greedy scan by itself - decision context, the list of valid candidates,
+// their features, V(s) with the bf16 MLP, the running minimum, the commit "s_i := s" -
+// so that a schedule costs one launch and nothing but the tables and the id list touches
+// memory.  Pays when there are about as many problems as compute units.
+//
+// The MLP is the same contraction as in the per-layer scorer: weights are the MFMA A
+// operand and stream from L2 through a ring of registers, activations are the B operand
+// in LDS, a wave owns RT row tiles of every hidden layer and all NC / 32 column tiles.
+// What differs is the tile pipeline.  The features of a tile (the 64 core rows; the other
+// 192 rows are the same for all candidates of a decision and enter as a bias, see below)
+// go to an input buffer of their own, so the first layer does not have to share the
+// activation buffer with the layers behind it, and they are produced one tile ahead:
+// waves 4..7 evaluate the next tile's candidates before their share of the last hidden
+// layer and waves 0..3 after it, so that on every SIMD one wave's integer work runs under
+// the other wave's matrix work.  The scan over a tile's scores is left to the waves that
+// hold them while the others start the next tile.  Two workgroup barriers per tile remain:
+// one behind the first layer's activations, one behind the partial output dots.
+#include <stdlib.h>
+
+#include "vf_internal.h"
+
+namespace {
+
+#include "vf_sched_dev.h"
+
+#include "vf_score_dev.h"
+
+// With fewer problems than compute units a team of `team` workgroups shares one problem:
+// every member builds the decision's context and id list for itself, member m scores
+// tiles m, m + team, ... of the list, publishes its minimum, the team meets at a counter
+// in global memory (one arrival per member and layer, bounded wait), and every member then
+// reduces all minima and commits by itself - the members write identical values to the
+// tables and the list, so one meeting per layer is enough.
+struct WholeArgs {
+  Tables t;
+  int first, last;
+  int32_t *list;   // [nprob][Mpad] scratch for the id lists
+  int64_t Mpad;
+  int team;                  // workgroups per problem; grid = nprob * team <= compute units when > 1
+  float *team_val;           // [2][nprob][team] per-member minima, by layer parity
+  int32_t *team_idx;
+  unsigned int *team_count;  // [nprob], zero at launch
+  int32_t *team_err;         // set if a wait ran out
+};
+constexpr unsigned int VF_TEAM_SPINS = 1u << 22;
+
+// NC candidates per tile, RT row tiles per wave (hidden width 256 * RT), PD k-steps of
+// weight fragments in flight per wave.  stat: nullable, [0] += candidates pushed through
+// the network, [1] += valid ones (the same here: only valid ids are listed).
+template <int NC, int RT, int PD>
+__global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M, int nprob,
+                                               unsigned long long *stat, NoiseArgs na, WholeArgs wa) {
+  constexpr int CT = NC / 32;
+  constexpr int NWS = NC / 64;  // waves that scan the tile's scores: wave w owns columns 64 w ...
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t *act = reinterpret_cast<uint16_t *>(smem);          // [NC][ks] hidden activations
+  uint16_t *xin = act + (size_t)NC * ks;                       // [NC][64] the tile's core rows, 16-byte
+                                                               // chunk q of column n at chunk q ^ ((n >> 1) & 7)
+  float *red = reinterpret_cast<float *>(xin + (size_t)NC * 64);  // [8][NC] partial output dots
+  int32_t *okf = reinterpret_cast<int32_t *>(red + 8 * NC);    // [2][NC] candidate id + 1 of a valid column, else 0
+  float *auxs = reinterpret_cast<float *>(okf + 2 * NC);       // [naux] biases, output vector
+  __shared__ DecPack pk;
+  __shared__ int team_failed;
+  __shared__ float sv[NWS];      // per scanning wave: the incumbent of the scan over its columns ...
+  __shared__ int32_t sc[NWS];
+  __shared__ unsigned int sn[NWS][2];  // ... and what it counted (candidates, valid ones)
+  // with 256 input rows, rows 64..255 are the same for all candidates of a decision
+  // (neighbour stages): their part of the first layer is a per-decision bias, which
+  // replaces the layer's bias in LDS, and the contraction runs over the 64 core rows only
+  const bool fold = md.w_full != nullptr;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int NH = md.L - 1;
+
+  // ---- once per workgroup: the small fp32 vectors into LDS, the weight ring primed
+  for (int i = tid; i < md.naux; i += 512) auxs[i] = md.aux[i];
+  const uint4 *const wbase = md.w_stream + (size_t)w * md.wave_stride + lane;
+  const uint4 *wp = wbase;
+  uint4 ring[PD][RT];
+#pragma unroll
+  for (int j = 0; j < PD; ++j)
+#pragma unroll
+    for (int r = 0; r < RT; ++r) ring[j][r] = wp[(j * RT + r) * 64];
+  wp += PD * RT * 64;
+
+  const int team = wa.team, member = (int)blockIdx.x % team;
+  if (tid == 0) team_failed = 0;
+
+  for (int unit = (int)blockIdx.x / team; unit < nprob; unit += (int)gridDim.x / team)
+  for (int stage = wa.first; stage <= wa.last; ++stage) {
+    int32_t *const idlist = wa.list + (size_t)unit * wa.Mpad;
+    fill_decpack(pk, wa.t, unit, stage);
+    na.stage = stage;
+    // Ordered list of the decision's valid ids, written down directly from the validity
+    // rules: per (compute_at, store_at) digit pair that is open - the level is offered and
+    // the hoist does not exceed it - the valid ids are the products of the split factors
+    // that fit the level's region with every loop order / vectorize / parallel choice;
+    // an inlining pair has the single id with every other digit zero.
+    __shared__ int ncand, g_npairs;
+    __shared__ int g_pos[13], g_base[12], g_cat[12];
+    __shared__ int g_nok[3][3], g_ok[3][3][8];
+    if (tid < 9) {
+      const int lvl = tid / 3, dd = tid % 3;
+      int cnt = 0;
+      for (int k = 0; k < pk.sp.nf[dd]; ++k)
+        if ((uint32_t)pk.sp.fac[dd][k] <= pk.d.E[lvl][dd]) g_ok[lvl][dd][cnt++] = k;
+      g_nok[lvl][dd] = cnt;
+    }
+    __syncthreads();
+    const int rest_n = pk.sp.nperm * pk.sp.nvec * pk.sp.npar;
+    const int run_n = pk.sp.nf[0] * pk.sp.nf[1] * pk.sp.nf[2] * rest_n;
+    if (tid == 0) {
+      int np = 0, pos = 0;
+      for (int isat = 0; isat < pk.sp.nsat; ++isat)
+        for (int icat = 0; icat < pk.sp.ncat; ++icat) {
+          const int cat = pk.sp.cat[icat];
+          if (pk.d.lvl_ok[cat] == 0) continue;
+          int cnt = 0;
+          if (cat == VF_INLINE) cnt = isat == 0 ? 1 : 0;
+          else if (isat <= cat) cnt = g_nok[cat][0] * g_nok[cat][1] * g_nok[cat][2] * rest_n;
+          if (cnt == 0) continue;
+          g_pos[np] = pos;
+          g_base[np] = (icat + pk.sp.ncat * isat) * run_n;
+          g_cat[np] = cat;
+          pos += cnt;
+          ++np;
+        }
+      g_pos[np] = pos;
+      g_npairs = np;
+      ncand = pos;
+    }
+    __syncthreads();
+    for (int k = tid; k < ncand; k += 512) {
+      int q = 0;
+      while (q + 1 < g_npairs && k >= g_pos[q + 1]) ++q;
+      const int cat = g_cat[q];
+      int cid = g_base[q];
+      if (cat != VF_INLINE) {
+        int r = k - g_pos[q];
+        const int nx = g_nok[cat][0], ny = g_nok[cat][1], nc = g_nok[cat][2];
+        const int jx = r % nx; r /= nx;
+        const int jy = r % ny; r /= ny;
+        const int jc = r % nc; r /= nc;
+        cid += g_ok[cat][0][jx] + pk.sp.nf[0] * (g_ok[cat][1][jy] + pk.sp.nf[1] * (g_ok[cat][2][jc] + pk.sp.nf[2] * r));
+      }
+      idlist[k] = cid;
+    }
+    if (fold) {
+      // the first layer's product with the 192 rows that all candidates of the decision
+      // share, once per decision: the same contraction with the shared vector in every
+      // column (twelve k-steps, one column tile); column 0 of the result plus the layer's
+      // bias is what the candidates' accumulators start from
+      floatx16 fa[RT];
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int q = 0; q < 16; ++q) fa[r][q] = 0.0f;
+      const uint4 *wf = md.w_full + (size_t)w * md.wave_stride_full + lane + (size_t)4 * RT * 64;
+#pragma unroll 4
+      for (int sk = 0; sk < 12; ++sk) {
+        uint4 a[RT];
+#pragma unroll
+        for (int r = 0; r < RT; ++r) a[r] = wf[((size_t)sk * RT + r) * 64];
+        const uint32_t *xb = pk.nbh + 8 * sk + 4 * (lane >> 5);
+        uint4 bv;
+        bv.x = xb[0]; bv.y = xb[1]; bv.z = xb[2]; bv.w = xb[3];
+#pragma unroll
+        for (int r = 0; r < RT; ++r)
+          fa[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[r]),
+                                                         __builtin_bit_cast(bf16x8, bv), fa[r], 0, 0, 0);
+      }
+      if ((lane & 31) == 0) {
+#pragma unroll
+        for (int r = 0; r < RT; ++r) {
+          const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+          for (int g = 0; g < 4; ++g)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              auxs[md.bias_off[0] + mbase + 8 * g + e] = md.aux[md.bias_off[0] + mbase + 8 * g + e] + fa[r][4 * g + e];
+        }
+      }
+    }
+    __syncthreads();  // the id list (written by this workgroup) and the bias are complete
+    const int ncands = ncand;
+    const int ntiles = (ncands + NC - 1) / NC;
+
+    // Thread tid evaluates the candidate of column tid % NC of the tile that starts at list
+    // entry nb and stores its share of the 64 core rows, normalised, as bf16: part 0 rows
+    // 0..15 and 40..47, part 1 rows 16..31, part 2 rows 32..39 and 56..63, part 3 rows
+    // 48..55 - dealt out so that the four copies cost about the same (rows 0..15 and 56..63
+    // are copies of the context, 48..55 the dearest); the rows a part does not store are
+    // dead code in its copy of the evaluation.  Padding columns evaluate id 0 and store zeros.
+    auto featurize = [&](int nb, int par) __attribute__((always_inline)) {
+      const int n = tid % NC, part = tid / NC;
+      const bool inb = (nb + n) < ncands;
+      const uint32_t cid = inb ? (uint32_t)idlist[nb + n] : 0u;
+      int32_t core[64];
+      uint32_t dec;
+      uint16_t *const col = xin + (size_t)n * 64;
+      const int sw = (n >> 1) & 7;
+      auto put8 = [&](const int32_t *v, int chunk) {
+        uint4 q;
+        q.x = pack_bf16(plog2_dev(v[0]), plog2_dev(v[1]));
+        q.y = pack_bf16(plog2_dev(v[2]), plog2_dev(v[3]));
+        q.z = pack_bf16(plog2_dev(v[4]), plog2_dev(v[5]));
+        q.w = pack_bf16(plog2_dev(v[6]), plog2_dev(v[7]));
+        if (!inb) q = make_uint4(0u, 0u, 0u, 0u);
+        *reinterpret_cast<uint4 *>(col + ((chunk ^ sw) << 3)) = q;
+      };
+      if (part == 0) {
+        // evaluated for padding ids too: core must be defined before it is packed
+        const bool valid = eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
+        okf[par * NC + n] = (inb && valid) ? (int32_t)cid + 1 : 0;
+        put8(core, 0);
+        put8(core + 8, 1);
+        put8(core + 40, 5);
+      } else if (part == 1) {
+        eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
+        put8(core + 16, 2);
+        put8(core + 24, 3);
+      } else if (part == 2) {
+        eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
+        put8(core + 32, 4);
+        put8(core + 56, 7);
+      } else if (part == 3) {
+        eval_candidate<true>(pk.d, pk.sp, cid, dec, core);
+        put8(core + 48, 6);
+      }
+    };
+
+    if (w < NWS && lane == 0) {
+      sv[w] = __builtin_inff();
+      sc[w] = -1;
+      sn[w][0] = sn[w][1] = 0u;
+    }
+    // the loop starts one tile early: that round only produces the first tile's features
+    int par = 1;
+    for (int t = member - team; t < ntiles; t += team, par ^= 1) {
+      const bool real = t >= member;
+      const bool has_next = t + team < ntiles;
+      float dot[CT];
+#pragma unroll
+      for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
+      for (int l = 0; l < NH; ++l) {
+        const bool lastl = l == NH - 1;
+        // with a single hidden layer the next tile's features would land in the buffer this
+        // very layer reads: then every wave finishes the layer first
+        const bool feat_first = NH > 1 && w >= 4;
+        for (int ph = 0; ph < (lastl ? 2 : 1); ++ph) {
+          if (lastl && (ph == 0) == feat_first) {
+            if (NH == 1) __syncthreads();
+            if (has_next) featurize((t + team) * NC, par ^ 1);
+            continue;
+          }
+          if (!real) continue;
+          const int ksteps = l == 0 ? md.k0 : md.dims[l] / 16;
+          // the accumulators start from the bias of their output row
+          const float *bias = auxs + md.bias_off[l];
+          floatx16 acc[RT][CT];
+#pragma unroll
+          for (int r = 0; r < RT; ++r) {
+            const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
+#pragma unroll
+              for (int c = 0; c < CT; ++c) {
+                acc[r][c][4 * g + 0] = bv.x; acc[r][c][4 * g + 1] = bv.y;
+                acc[r][c][4 * g + 2] = bv.z; acc[r][c][4 * g + 3] = bv.w;
+              }
+            }
+          }
+          // The contraction.  One memory instruction behind each product, so that a wave
+          // that has its SIMD's matrix core to itself never leaves it waiting for the issue
+          // of a burst of loads: behind the first CT products the activation fragments of
+          // the next k-step (one step past the end stays inside LDS), behind the last
+          // product that reads a weight fragment its refill, in place, PD k-steps ahead of
+          // its next use - so only the oldest slot is ever waited for.  The last PD steps of
+          // a tile prefetch the first PD steps of the next one.
+          {
+            // B operand of this lane: column (lane & 31) of a column tile, k half lane >> 5; the
+            // first layer reads the input buffer (chunks swapped around by column), the others
+            // the activations
+            const bool first = l == 0;
+            const uint16_t *const bb = first ? xin + (size_t)(lane & 31) * 64 : act + (size_t)(lane & 31) * ks;
+            const int cstride = first ? 32 * 64 : 32 * ks;
+            const int h8 = 8 * (lane >> 5), xorv = first ? (((lane & 31) >> 1) & 7) << 3 : 0;
+            auto bfrag = [&](int c, int s) -> const uint4 * {
+              return reinterpret_cast<const uint4 *>(bb + (size_t)c * cstride + ((s * 16 + h8) ^ xorv));
+            };
+            uint4 bcur[CT];
+#pragma unroll
+            for (int c = 0; c < CT; ++c) bcur[c] = *bfrag(c, 0);
+            // the matrix loop goes first on its SIMD: the other wave's vector work fills the gaps
+            __builtin_amdgcn_s_setprio(2);
+            for (int s0 = 0; s0 < ksteps; s0 += PD) {
+              if (lastl && s0 + PD >= ksteps) wp = wbase;
+#pragma unroll
+              for (int j = 0; j < PD; ++j) {
+                uint4 bnext[CT];
+#pragma unroll
+                for (int i = 0; i < RT * CT; ++i) {
+                  const int r = i / CT, c = i % CT;
+                  acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                      __builtin_bit_cast(bf16x8, ring[j][r]), __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
+                  if (i < CT) bnext[i] = *bfrag(i, s0 + j + 1);
+                  if (i >= CT && c == 0) ring[j][r - 1] = wp[(r - 1) * 64];
+                  if (i == RT * CT - 1) ring[j][RT - 1] = wp[(RT - 1) * 64];
+                  __builtin_amdgcn_sched_barrier(0);
+                }
+                wp += RT * 64;
+#pragma unroll
+                for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
+              }
+            }
+            __builtin_amdgcn_s_setprio(0);
+          }
+
+          if (!lastl) {
+            // every wave has read the layer's input before it is overwritten: the first
+            // layer reads the input buffer, and nobody reads the activations of the tile
+            // before any more (barrier behind its output dots)
+            if (l > 0) __syncthreads();
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+              const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+#pragma unroll
+                for (int c = 0; c < CT; ++c) {
+                  uint2 q;
+                  q.x = pack_bf16(relu_bits(acc[r][c][4 * g + 0]), relu_bits(acc[r][c][4 * g + 1]));
+                  q.y = pack_bf16(relu_bits(acc[r][c][4 * g + 2]), relu_bits(acc[r][c][4 * g + 3]));
+                  *reinterpret_cast<uint2 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + mbase + 8 * g) = q;
+                }
+              }
+            }
+            __syncthreads();
+          } else {
+            // last hidden layer: round to bf16 and multiply with the output vector at once
+            const float *wl = auxs + md.wl_off;
+#pragma unroll
+            for (int r = 0; r < RT; ++r) {
+              const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+                const float4 wv = *reinterpret_cast<const float4 *>(wl + mbase + 8 * g);
+#pragma unroll
+                for (int c = 0; c < CT; ++c) {
+                  uint32_t q0 = pack_bf16(relu_bits(acc[r][c][4 * g + 0]), relu_bits(acc[r][c][4 * g + 1]));
+                  uint32_t q1 = pack_bf16(relu_bits(acc[r][c][4 * g + 2]), relu_bits(acc[r][c][4 * g + 3]));
+                  float d = dot[c];
+                  d = fmaf(__uint_as_float(q0 << 16), wv.x, d);
+                  d = fmaf(__uint_as_float(q0 & 0xffff0000u), wv.y, d);
+                  d = fmaf(__uint_as_float(q1 << 16), wv.z, d);
+                  d = fmaf(__uint_as_float(q1 & 0xffff0000u), wv.w, d);
+                  dot[c] = d;
+                }
+              }
+            }
+          }
+        }
+      }
+
+      // ---- value: the partial dots of the two lane halves, then of the waves in order
+      if (real) {
+#pragma unroll
+        for (int c = 0; c < CT; ++c) {
+          float v = dot[c] + __shfl_xor(dot[c], 32);
+          if (lane < 32) red[w * NC + c * 32 + lane] = v;
+        }
+      }
+      __syncthreads();
+      if (real && w < NWS) {
+        float s = auxs[md.bias_off[md.L - 1]];
+#pragma unroll
+        for (int g = 0; g < 8; ++g) s += red[g * NC + tid];
+        const int32_t flag = okf[par * NC + tid];
+        const int32_t colid = flag - 1;
+        if (na.eps != 0.0f) s = add_noise(na, s, unit, colid);
+        float v = __builtin_inff();
+        int32_t c = -1;
+        if (flag != 0 && s < v) { v = s; c = colid; }
+        wave_min(v, c);
+        const unsigned int n_ok = (unsigned int)__popcll(__ballot(flag != 0));
+        const unsigned int n_in = (unsigned int)__popcll(__ballot(t * NC + tid < ncands));
+        if (lane == 0) {
+          float rv = sv[w];
+          int32_t rc = sc[w];
+          take_min(rv, rc, v, c);
+          sv[w] = rv;
+          sc[w] = rc;
+          sn[w][0] += n_in;
+          sn[w][1] += n_ok;
+        }
+      }
+      // no barrier here: the next tile's first layer reads the input buffer and the bias
+      // only; its activations are written behind this barrier, the partial dots and the
+      // flags of the other parity behind the next tile's first one
+    }
+
+    if (stat && w < NWS && lane == 0 && sn[w][0]) {
+      atomicAdd(&stat[0], (unsigned long long)sn[w][0]);
+      atomicAdd(&stat[1], (unsigned long long)sn[w][1]);
+    }
+    __syncthreads();
+    float run_v = sv[0];
+    int32_t run_c = sc[0];
+    if (tid == 0)
+      for (int k = 1; k < NWS; ++k) take_min(run_v, run_c, sv[k], sc[k]);
+    if (team > 1) {
+      // publish this member's minimum, meet the team, reduce everybody's minima
+      const size_t slot0 = ((size_t)(stage & 1) * nprob + unit) * team;
+      if (tid == 0) {
+        wa.team_val[slot0 + member] = run_v;
+        wa.team_idx[slot0 + member] = run_c;
+        __threadfence();
+        atomicAdd(&wa.team_count[unit], 1u);
+        const unsigned int target = (unsigned int)team * (unsigned int)(stage - wa.first + 1);
+        unsigned int spins = 0;
+        while (__hip_atomic_load(&wa.team_count[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+          if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
+          __builtin_amdgcn_s_sleep(2);
+        }
+        __threadfence();
+      }
+      __syncthreads();
+      if (team_failed) return;  // a member never arrived: give up instead of waiting for ever
+      if (tid < 64) {
+        float v = __builtin_inff();
+        int32_t c = -1;
+        for (int m = tid; m < team; m += 64) {
+          const float mv = __hip_atomic_load(&wa.team_val[slot0 + m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const int32_t mc = __hip_atomic_load(&wa.team_idx[slot0 + m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          take_min(v, c, mv, mc);
+        }
+        wave_min(v, c);
+        run_v = v;
+        run_c = c;
+      }
+    }
+    // s_i := the winner; the tables it updates are read back by this same workgroup
+    // when it builds the next stage's context
+    if (tid == 0) commit_winner_call(wa.t, pk.d, pk.sp, unit, stage, run_c, run_v, (uint32_t)M);
+    __threadfence();
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void k_zero_u32(unsigned int *p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+
+}  // namespace
+
+// Workgroups per problem for a whole-schedule launch, 0 = use the per-layer launches.
+// 1 when the problems fill the compute units by themselves (each workgroup then owns
+// ceil(B / units) problems from the first layer to the last; measured break-even against
+// the per-layer launches: about 72 % of the slots filled); with fewer problems a team per
+// problem, as large as the compute units and the tiles of a decision allow, at most 16
+// (measured: 128 problems x 2: 3.6 instead of 4.9 ms per step, 64 x 4: 2.3 instead of 3.4,
+// 32 x 8: 1.9 instead of 2.2; below 16 problems the meetings cost what the launches did).
+int vfk_whole_team(const vf_ctx *c) {
+  if (!vfk_can_fuse_step(c)) return 0;
+  int ncu = 256;
+  (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
+  const int rounds = (c->B + ncu - 1) / ncu;
+  if ((double)c->B >= 0.72 * (double)rounds * (double)ncu) return 1;
+  if (c->B > ncu / 2 || c->B < 16) return 0;  // a handful of problems: the per-layer launches are as fast
+  int maxw = 0;
+  for (int l = 0; l < c->model.n_layers; ++l) if (c->model.dims[l] > maxw) maxw = c->model.dims[l];
+  const int NC = maxw > 512 ? 64 : 128;
+  const int nparts = (int)((c->M + NC - 1) / NC);
+  int team = ncu / c->B;
+  if (team > nparts) team = nparts;
+  if (team > 16) team = 16;
+  return team >= 2 ? team : 0;
+}
+
+// Algorithm 1 over stages first..last for every problem of the batch, one launch.
+int vfk_greedy_whole(vf_ctx *c, int first, int last) {
+  const int team = vfk_whole_team(c);
+  if (team < 1) return VF_ESTATE;
+  const size_t want = (size_t)c->B * c->Mpad;
+  if (want > c->wlist_elems) {
+    if (c->d_wlist) { VF_HIP(c, hipStreamSynchronize(c->stream)); (void)hipFree(c->d_wlist); c->d_wlist = nullptr; }
+    c->wlist_elems = 0;
+    if (hipMalloc((void **)&c->d_wlist, want * 4) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
+    c->wlist_elems = want;
+  }
+  if (team > 1) {
+    // [count B][err 1][values 2*B*team][ids 2*B*team]
+    const size_t twant = (size_t)c->B + 1 + (size_t)4 * c->B * team;
+    if (twant > c->team_elems) {
+      if (c->d_team) { VF_HIP(c, hipStreamSynchronize(c->stream)); (void)hipFree(c->d_team); c->d_team = nullptr; }
+      c->team_elems = 0;
+      if (hipMalloc((void **)&c->d_team, twant * 4) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
+      c->team_elems = twant;
+    }
+    hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)((c->B + 1 + 255) / 256)), dim3(256), 0, c->stream, c->d_team,
+                       (size_t)c->B + 1);
+    VF_HIP(c, hipGetLastError());
+    if (!c->h_team_err) {
+      VF_HIP(c, hipHostMalloc((void **)&c->h_team_err, sizeof(int32_t), hipHostMallocDefault));
+      *c->h_team_err = 0;
+    }
+  }
+
+  vf_fast_dev fd;
+  int ks = 0, NC = 0;
+  vfk_fast_dev(c, true, &fd, &ks, &NC);
+  if (fd.k0 != 4) return VF_ESTATE;  // the generated input is the 64 core rows
+  NoiseArgs na;
+  na.eps = c->noise_eps;
+  na.k0 = (uint32_t)c->noise_seed; na.k1 = (uint32_t)(c->noise_seed >> 32);
+  na.stage = first; na.first_rollout = c->noise_first;
+  WholeArgs wa;
+  wa.t = tables_of(c);
+  wa.first = first; wa.last = last;
+  wa.list = c->d_wlist; wa.Mpad = c->Mpad;
+  wa.team = team;
+  wa.team_count = c->d_team;
+  wa.team_err = reinterpret_cast<int32_t *>(c->d_team) + c->B;
+  wa.team_val = reinterpret_cast<float *>(c->d_team) + c->B + 1;
+  wa.team_idx = reinterpret_cast<int32_t *>(c->d_team) + c->B + 1 + (size_t)2 * c->B * team;
+  int ncu = 256;
+  (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
+  // persistent: at most one workgroup per compute unit
+  const dim3 grid = team > 1 ? dim3((unsigned)(c->B * team)) : dim3((unsigned)(c->B < ncu ? c->B : ncu));
+  const size_t smem = (size_t)NC * ks * 2 + (size_t)NC * 64 * 2 + (size_t)8 * NC * 4 + (size_t)2 * NC * 4 +
+                      (size_t)fd.naux * 4;
+  void (*kern)(vf_fast_dev, int, int64_t, int, unsigned long long *, NoiseArgs, WholeArgs) =
+      NC == 64 ? k_whole<64, 4, 2> : k_whole<128, 2, 4>;
+  {
+    vf_prof_scope prof(c, VF_PROF_SCORE);
+    VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
+    hipLaunchKernelGGL(kern, grid, dim3(512), smem, c->stream, fd, ks, c->M, c->B,
+                       c->profiling ? c->d_stat : (unsigned long long *)nullptr, na, wa);
+    VF_HIP(c, hipGetLastError());
+  }
+  c->dec_stage = -1;
+  if (team > 1)  // the flag of a meeting that ran out, for the next call to look at
+    VF_HIP(c, hipMemcpyAsync(c->h_team_err, reinterpret_cast<int32_t *>(c->d_team) + c->B, sizeof(int32_t),
+                             hipMemcpyDeviceToHost, c->stream));
+  return VF_OK;
+}
