@@ -656,22 +656,28 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     }
     if (l < NH - 1) {
       __syncthreads();  // every wave has read the layer's input: it can be overwritten
+      // rounded to bfloat16, ReLU on the pairs; the two lane halves then trade their row
+      // groups so that every lane writes 8 consecutive rows of its column at once
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
-        const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+        const int m0 = (w + r * 8) * 32 + 8 * (lane >> 5);
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
+        for (int g = 0; g < 4; g += 2) {
 #pragma unroll
           for (int c = 0; c < CT; ++c) {
-            uint2 q;
-            q.x = pack_bf16(relu_bits(acc[r][c][4 * g + 0]), relu_bits(acc[r][c][4 * g + 1]));
-            q.y = pack_bf16(relu_bits(acc[r][c][4 * g + 2]), relu_bits(acc[r][c][4 * g + 3]));
-            *reinterpret_cast<uint2 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + mbase + 8 * g) = q;
+            uint32_t x0 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 0], acc[r][c][4 * g + 1]));
+            uint32_t x1 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 2], acc[r][c][4 * g + 3]));
+            uint32_t y0 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 4], acc[r][c][4 * g + 5]));
+            uint32_t y1 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 6], acc[r][c][4 * g + 7]));
+            swap_halves(x0, y0);
+            swap_halves(x1, y1);
+            *reinterpret_cast<uint4 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + m0 + 8 * g) = make_uint4(x0, x1, y0, y1);
           }
         }
       }
       __syncthreads();
     } else {
+      // last hidden layer: round to bf16 and multiply with the output vector at once
       const float *wl = auxs + md.wl_off;
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
@@ -697,7 +703,9 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
 
 #pragma unroll
   for (int c = 0; c < CT; ++c) {
-    float v = dot[c] + __shfl_xor(dot[c], 32);
+    uint32_t own = __float_as_uint(dot[c]), other = own;
+    swap_halves(own, other);  // lanes below 32: the dot of lane + 32
+    float v = dot[c] + __uint_as_float(other);
     if (lane < 32) red[w * NC + c * 32 + lane] = v;
   }
   __syncthreads();

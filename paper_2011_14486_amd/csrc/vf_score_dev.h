@@ -23,6 +23,23 @@ __device__ __forceinline__ float relu_bits(float v) {
   return __int_as_float(i < 0 ? 0 : i);
 }
 
+typedef short vf_shortx2 __attribute__((ext_vector_type(2)));
+
+// ReLU of a packed bfloat16 pair, on the bit patterns like relu_bits: a half with the sign
+// bit set becomes +0 (rounding to bfloat16 keeps the sign, so the order of the two is free)
+__device__ __forceinline__ uint32_t relu_bf16x2(uint32_t q) {
+  const vf_shortx2 zero = {0, 0};
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(vf_shortx2, q), zero));
+}
+
+// Lanes 0..31 hand their b to lanes 32..63 and take those lanes' a: afterwards a lane below
+// 32 holds (its a, the a of lane + 32) and a lane from 32 up (the b of lane - 32, its b).
+__device__ __forceinline__ void swap_halves(uint32_t &a, uint32_t &b) {
+  const auto r = __builtin_amdgcn_permlane32_swap(a, b, false, false);
+  a = r[0];
+  b = r[1];
+}
+
 // (value, id) ordering of the scan: smaller value first, then smaller id; id < 0 = none
 __device__ __forceinline__ void take_min(float &v, int32_t &c, float ov, int32_t oc) {
   if (oc >= 0 && (ov < v || (ov == v && (c < 0 || oc < c)))) { v = ov; c = oc; }

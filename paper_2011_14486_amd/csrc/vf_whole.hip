@@ -243,8 +243,6 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       const bool real = t >= member;
       const bool has_next = t + team < ntiles;
       float dot[CT];
-#pragma unroll
-      for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
       for (int l = 0; l < NH; ++l) {
         const bool lastl = l == NH - 1;
         // with a single hidden layer the next tile's features would land in the buffer this
@@ -325,17 +323,22 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
             // layer reads the input buffer, and nobody reads the activations of the tile
             // before any more (barrier behind its output dots)
             if (l > 0) __syncthreads();
+            // rounded to bfloat16, ReLU on the pairs; the two lane halves then trade their row
+            // groups so that every lane writes 8 consecutive rows of its column at once
 #pragma unroll
             for (int r = 0; r < RT; ++r) {
-              const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+              const int m0 = (w + r * 8) * 32 + 8 * (lane >> 5);
 #pragma unroll
-              for (int g = 0; g < 4; ++g) {
+              for (int g = 0; g < 4; g += 2) {
 #pragma unroll
                 for (int c = 0; c < CT; ++c) {
-                  uint2 q;
-                  q.x = pack_bf16(relu_bits(acc[r][c][4 * g + 0]), relu_bits(acc[r][c][4 * g + 1]));
-                  q.y = pack_bf16(relu_bits(acc[r][c][4 * g + 2]), relu_bits(acc[r][c][4 * g + 3]));
-                  *reinterpret_cast<uint2 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + mbase + 8 * g) = q;
+                  uint32_t x0 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 0], acc[r][c][4 * g + 1]));
+                  uint32_t x1 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 2], acc[r][c][4 * g + 3]));
+                  uint32_t y0 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 4], acc[r][c][4 * g + 5]));
+                  uint32_t y1 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 6], acc[r][c][4 * g + 7]));
+                  swap_halves(x0, y0);
+                  swap_halves(x1, y1);
+                  *reinterpret_cast<uint4 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + m0 + 8 * g) = make_uint4(x0, x1, y0, y1);
                 }
               }
             }
@@ -343,6 +346,8 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
           } else {
             // last hidden layer: round to bf16 and multiply with the output vector at once
             const float *wl = auxs + md.wl_off;
+#pragma unroll
+            for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
 #pragma unroll
             for (int r = 0; r < RT; ++r) {
               const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
@@ -370,7 +375,9 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       if (real) {
 #pragma unroll
         for (int c = 0; c < CT; ++c) {
-          float v = dot[c] + __shfl_xor(dot[c], 32);
+          uint32_t own = __float_as_uint(dot[c]), other = own;
+          swap_halves(own, other);  // lanes below 32: the dot of lane + 32
+          float v = dot[c] + __uint_as_float(other);
           if (lane < 32) red[w * NC + c * 32 + lane] = v;
         }
       }
