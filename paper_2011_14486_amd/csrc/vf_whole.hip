@@ -465,7 +465,18 @@ __global__ __launch_bounds__(256) void k_zero_u32(unsigned int *p, size_t n) {
 
 }  // namespace
 
-// Workgroups per problem for a whole-schedule launch, 0 = use the per-layer launches.
+// Kernel and dynamic LDS bytes of a whole-schedule launch for the context's model.
+typedef void (*whole_kernel)(vf_fast_dev, int, int64_t, int, unsigned long long *, NoiseArgs, WholeArgs);
+static whole_kernel whole_launch_shape(const vf_ctx *c, vf_fast_dev *fd, int *ks, size_t *smem) {
+  int NC = 0;
+  vfk_fast_dev(c, true, fd, ks, &NC);
+  *smem = (size_t)NC * *ks * 2 + (size_t)NC * 64 * 2 + (size_t)8 * NC * 4 + (size_t)2 * NC * 4 + (size_t)fd->naux * 4;
+  return NC == 64 ? k_whole<64, 4, 2> : k_whole<128, 2, 4>;
+}
+
+// Workgroups per problem for a whole-schedule launch, 0 = use the per-layer launches
+// (also when the model's tile does not fit the LDS of a compute unit next to its input
+// buffer, e.g. three hidden layers of 512 with all their biases).
 // 1 when the problems fill the compute units by themselves (each workgroup then owns
 // ceil(B / units) problems from the first layer to the last; measured break-even against
 // the per-layer launches: about 72 % of the slots filled); with fewer problems a team per
@@ -474,6 +485,16 @@ __global__ __launch_bounds__(256) void k_zero_u32(unsigned int *p, size_t n) {
 // 32 x 8: 1.9 instead of 2.2; below 16 problems the meetings cost what the launches did).
 int vfk_whole_team(const vf_ctx *c) {
   if (!vfk_can_fuse_step(c)) return 0;
+  {
+    vf_fast_dev fd;
+    int ks = 0, lds_max = 0;
+    size_t smem = 0;
+    const whole_kernel kern = whole_launch_shape(c, &fd, &ks, &smem);
+    hipFuncAttributes attr;
+    if (hipFuncGetAttributes(&attr, (const void *)kern) != hipSuccess) { (void)hipGetLastError(); return 0; }
+    (void)hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, c->device);
+    if (fd.k0 != 4 || smem + attr.sharedSizeBytes > (size_t)lds_max) return 0;
+  }
   int ncu = 256;
   (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
   const int rounds = (c->B + ncu - 1) / ncu;
@@ -519,9 +540,9 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
   }
 
   vf_fast_dev fd;
-  int ks = 0, NC = 0;
-  vfk_fast_dev(c, true, &fd, &ks, &NC);
-  if (fd.k0 != 4) return VF_ESTATE;  // the generated input is the 64 core rows
+  int ks = 0;
+  size_t smem = 0;
+  const whole_kernel kern = whole_launch_shape(c, &fd, &ks, &smem);
   NoiseArgs na;
   na.eps = c->noise_eps;
   na.k0 = (uint32_t)c->noise_seed; na.k1 = (uint32_t)(c->noise_seed >> 32);
@@ -539,10 +560,6 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
   (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
   // persistent: at most one workgroup per compute unit
   const dim3 grid = team > 1 ? dim3((unsigned)(c->B * team)) : dim3((unsigned)(c->B < ncu ? c->B : ncu));
-  const size_t smem = (size_t)NC * ks * 2 + (size_t)NC * 64 * 2 + (size_t)8 * NC * 4 + (size_t)2 * NC * 4 +
-                      (size_t)fd.naux * 4;
-  void (*kern)(vf_fast_dev, int, int64_t, int, unsigned long long *, NoiseArgs, WholeArgs) =
-      NC == 64 ? k_whole<64, 4, 2> : k_whole<128, 2, 4>;
   {
     vf_prof_scope prof(c, VF_PROF_SCORE);
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));

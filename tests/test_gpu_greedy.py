@@ -396,3 +396,31 @@ def test_team_of_workgroups_per_problem(vf, ovf, B):
             for b in (0, B - 1):
                 compare_schedule(ovf, pipes[b], sp, model, w, whole[1][b], whole[2][b], whole[0][b], TOL[1])
     vf.vf_destroy(ctx)
+
+
+@pytest.mark.parametrize("dims", [[256, 512, 1], [256, 512, 512, 512, 1], [64, 512, 512, 1], [256, 1024, 1]])
+def test_whole_schedule_launch_other_depths(vf, ovf, dims):
+    """vf_greedy_schedule with a team per problem for other network shapes: one hidden layer
+    (the next tile's features cannot be produced next to the layer that reads the input buffer),
+    three hidden layers (their tile no longer fits the LDS next to the input buffer: the call
+    falls back to the launches per layer), 64 input rows (no shared rows to fold), the wide
+    tile.  Same tables as stepping layer by layer; two problems against the checker."""
+    B = 16
+    pipes = I.resnet18_batch(B, seed=21)
+    sp = I.make_space([1, 2, 4], [1, 4], [4, 8], [(0, 1, 2), (2, 1, 0)], 2, 2,
+                      [I.ROOT, I.L1, I.L2, I.INLINE], 2, dims[0])
+    w = I.mlp_weights(dims, 6, bias_std=0.1)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    S = pipes.shape[1]
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipes); vf.vf_set_model(ctx, model, w)
+    whole = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
+    vf.vf_reset_state(ctx)
+    for i in range(S):
+        vf.vf_argmin_step(ctx, i, True)
+    steps = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=S)]
+    for a, b in zip(whole, steps):
+        assert np.array_equal(a, b)
+    for b in (0, B - 1):
+        compare_schedule(ovf, pipes[b], sp, model, w, whole[1][b], whole[2][b], whole[0][b], TOL[1])
+    vf.vf_destroy(ctx)
