@@ -143,25 +143,65 @@ __device__ void build_dec(Dec &d, vf_space &sp, const Tables &t, int b, int stag
   __syncthreads();
 }
 
-// One candidate state: digits, validity and (FEATS) the 64 core features.
-// Rows 0..15 are always the stage's intrinsic block; rows 16..63 are zero when the
-// candidate is not valid.
-template <bool FEATS>
-__device__ __forceinline__ bool eval_candidate(const Dec &d, const vf_space &sp, uint32_t cid,
-                                               uint32_t &dec, int32_t *core) {
-  // Table 1 digits, least significant first
+// Table 1 digits of a candidate id, least significant first.
+struct Digits {
+  uint32_t ix, iy, ic, ip, vec, par, icat, isat;
+};
+__device__ __forceinline__ Digits digits_of(const vf_space &sp, uint32_t cid) {
+  Digits g;
   uint32_t r = cid;
-  uint32_t ix = r % (uint32_t)sp.nf[0]; r /= (uint32_t)sp.nf[0];
-  uint32_t iy = r % (uint32_t)sp.nf[1]; r /= (uint32_t)sp.nf[1];
-  uint32_t ic = r % (uint32_t)sp.nf[2]; r /= (uint32_t)sp.nf[2];
-  uint32_t ip = r % (uint32_t)sp.nperm; r /= (uint32_t)sp.nperm;
-  uint32_t vec = r % (uint32_t)sp.nvec; r /= (uint32_t)sp.nvec;
-  uint32_t par = r % (uint32_t)sp.npar; r /= (uint32_t)sp.npar;
-  uint32_t icat = r % (uint32_t)sp.ncat; r /= (uint32_t)sp.ncat;
-  uint32_t isat = r;
-  dec = ix | iy << 4 | ic << 8 | ip << 12 | vec << 16 | par << 20 | icat << 24 | isat << 28;
+  g.ix = r % (uint32_t)sp.nf[0]; r /= (uint32_t)sp.nf[0];
+  g.iy = r % (uint32_t)sp.nf[1]; r /= (uint32_t)sp.nf[1];
+  g.ic = r % (uint32_t)sp.nf[2]; r /= (uint32_t)sp.nf[2];
+  g.ip = r % (uint32_t)sp.nperm; r /= (uint32_t)sp.nperm;
+  g.vec = r % (uint32_t)sp.nvec; r /= (uint32_t)sp.nvec;
+  g.par = r % (uint32_t)sp.npar; r /= (uint32_t)sp.npar;
+  g.icat = r % (uint32_t)sp.ncat; r /= (uint32_t)sp.ncat;
+  g.isat = r;
+  return g;
+}
+__device__ __forceinline__ uint32_t pack_digits(const Digits &g) {
+  return g.ix | g.iy << 4 | g.ic << 8 | g.ip << 12 | g.vec << 16 | g.par << 20 | g.icat << 24 | g.isat << 28;
+}
+__device__ __forceinline__ Digits unpack_digits(uint32_t dec) {
+  Digits g;
+  g.ix = dec & 15u; g.iy = (dec >> 4) & 15u; g.ic = (dec >> 8) & 15u; g.ip = (dec >> 12) & 15u;
+  g.vec = (dec >> 16) & 15u; g.par = (dec >> 20) & 15u; g.icat = (dec >> 24) & 15u; g.isat = dec >> 28;
+  return g;
+}
 
-  const int cat = sp.cat[icat];
+// The quotients of the evaluation that depend on a digit and the decision only, so that
+// a kernel that evaluates many candidates of one decision can look them up: per level
+// and dimension the tile count of every split factor and the parallel efficiency of that
+// many tasks; per dimension the vector lanes and vector efficiency of every factor.
+struct EvalTabs {
+  uint32_t O[3][3][8];        // cdiv(E[level][dim], fac[dim][k])
+  uint32_t par_eff[3][3][8];  // ratio16(O, cdiv(O, ncores) * ncores)
+  uint32_t lanes[3][8];       // min(fac[dim][k], vlen)
+  uint32_t vec_eff[3][8];     // ratio16(fac, cdiv(fac, vlen) * vlen)
+};
+[[maybe_unused]] __device__ void fill_evaltabs(EvalTabs &tb, const Dec &d, const vf_space &sp) {
+  for (int i = threadIdx.x; i < 72; i += blockDim.x) {
+    const int lvl = i / 24, dd = (i / 8) % 3, k = i % 8;
+    const uint32_t f = k < sp.nf[dd] ? (uint32_t)sp.fac[dd][k] : 1u;
+    const uint32_t o = cdiv(d.E[lvl][dd], f);
+    tb.O[lvl][dd][k] = o;
+    tb.par_eff[lvl][dd][k] = ratio16(o, smul(cdiv(o, (uint32_t)sp.ncores), (uint32_t)sp.ncores));
+    if (lvl == 0) {
+      tb.lanes[dd][k] = umin(f, (uint32_t)sp.vlen);
+      tb.vec_eff[dd][k] = ratio16(f, smul(cdiv(f, (uint32_t)sp.vlen), (uint32_t)sp.vlen));
+    }
+  }
+}
+
+// One candidate state from its digits: validity and (FEATS) the 64 core features.
+// Rows 0..15 are always the stage's intrinsic block; rows 16..63 are zero when the
+// candidate is not valid.  tb (nullable): the decision's quotient tables.
+template <bool FEATS>
+__device__ __forceinline__ bool eval_digits(const Dec &d, const vf_space &sp, const Digits &g, const EvalTabs *tb,
+                                            int32_t *core) {
+  const uint32_t ix = g.ix, iy = g.iy, ic = g.ic, ip = g.ip, vec = g.vec, par = g.par, isat = g.isat;
+  const int cat = sp.cat[g.icat];
   const uint32_t hoist = isat;
   uint32_t f[3] = {(uint32_t)sp.fac[0][ix], (uint32_t)sp.fac[1][iy], (uint32_t)sp.fac[2][ic]};
   uint32_t E[3] = {1u, 1u, 1u};
@@ -191,7 +231,14 @@ __device__ __forceinline__ bool eval_candidate(const Dec &d, const vf_space &sp,
   const uint32_t kind = d.srec[0], RC = d.srec[4], KH = d.srec[5], KW = d.srec[6];
   const uint32_t stride = d.srec[7], eb = d.srec[12];
   const uint32_t R = d.intr[4], points = d.intr[7];
-  uint32_t O[3] = {cdiv(E[0], f[0]), cdiv(E[1], f[1]), cdiv(E[2], f[2])};
+  const bool looked_up = tb != nullptr && cat != VF_INLINE;
+  const uint32_t idx[3] = {ix, iy, ic};
+  uint32_t O[3];
+  if (looked_up) {
+    O[0] = tb->O[cat][0][ix]; O[1] = tb->O[cat][1][iy]; O[2] = tb->O[cat][2][ic];
+  } else {
+    O[0] = cdiv(E[0], f[0]); O[1] = cdiv(E[1], f[1]); O[2] = cdiv(E[2], f[2]);
+  }
 
   core[16] = 1;
   core[17] = f[0]; core[18] = f[1]; core[19] = f[2];
@@ -199,13 +246,19 @@ __device__ __forceinline__ bool eval_candidate(const Dec &d, const vf_space &sp,
   core[23] = ip; core[24] = p2; core[25] = p0;
   core[26] = vec;
   const uint32_t fin = p2 == 0 ? f[0] : (p2 == 1 ? f[1] : f[2]);
-  core[27] = vec ? umin(fin, (uint32_t)sp.vlen) : 1u;
-  core[28] = vec ? ratio16(fin, smul(cdiv(fin, (uint32_t)sp.vlen), (uint32_t)sp.vlen)) : 16u;
+  if (looked_up) {
+    core[27] = vec ? tb->lanes[p2][idx[p2]] : 1u;
+    core[28] = vec ? tb->vec_eff[p2][idx[p2]] : 16u;
+  } else {
+    core[27] = vec ? umin(fin, (uint32_t)sp.vlen) : 1u;
+    core[28] = vec ? ratio16(fin, smul(cdiv(fin, (uint32_t)sp.vlen), (uint32_t)sp.vlen)) : 16u;
+  }
   core[29] = par;
   const uint32_t Oout = p0 == 0 ? O[0] : (p0 == 1 ? O[1] : O[2]);
   const uint32_t tasks = par ? Oout : 1u;
   core[30] = tasks;
-  core[31] = ratio16(tasks, smul(cdiv(tasks, (uint32_t)sp.ncores), (uint32_t)sp.ncores));
+  if (looked_up && par) core[31] = tb->par_eff[cat][p0][idx[p0]];
+  else core[31] = ratio16(tasks, smul(cdiv(tasks, (uint32_t)sp.ncores), (uint32_t)sp.ncores));
   core[32] = cat; core[33] = hoist;
   core[34] = E[0]; core[35] = E[1]; core[36] = E[2];
   core[37] = inst;
@@ -248,6 +301,16 @@ __device__ __forceinline__ bool eval_candidate(const Dec &d, const vf_space &sp,
   core[59] = d.anchored ? (int32_t)((int32_t)ip == d.a_perm) : 0;
   core[60] = d.pm; core[61] = d.pb; core[62] = d.sm; core[63] = d.spt;
   return true;
+}
+
+// One candidate state from its id: digits (packed into dec), validity and (FEATS) the
+// 64 core features.
+template <bool FEATS>
+__device__ __forceinline__ bool eval_candidate(const Dec &d, const vf_space &sp, uint32_t cid,
+                                               uint32_t &dec, int32_t *core) {
+  const Digits g = digits_of(sp, cid);
+  dec = pack_digits(g);
+  return eval_digits<FEATS>(d, sp, g, nullptr, core);
 }
 
 
