@@ -60,7 +60,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
                                                                // chunk q of column n at chunk q ^ ((n >> 1) & 7)
   float *red = reinterpret_cast<float *>(xin + (size_t)NC * 64);  // [8][NC] partial output dots
   int32_t *okf = reinterpret_cast<int32_t *>(red + 8 * NC);    // [2][NC] candidate id + 1 of a valid column, else 0
-  float *auxs = reinterpret_cast<float *>(okf + 2 * NC);       // [naux] biases, output vector
+  float *auxs = reinterpret_cast<float *>(okf + 2 * NC);       // biases; output vector as bfloat16 pairs
   __shared__ DecPack pk;
   __shared__ EvalTabs tabs;  // the decision's quotient tables: no division per candidate
   __shared__ int team_failed;
@@ -77,7 +77,10 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
   const int NH = md.L - 1;
 
   // ---- once per workgroup: the small fp32 vectors into LDS, the weight ring primed
-  for (int i = tid; i < md.naux; i += 512) auxs[i] = md.aux[i];
+  // (the output vector's values are bfloat16 numbers: two to a word, to save LDS)
+  for (int i = tid; i < (int)md.wl_off; i += 512) auxs[i] = md.aux[i];
+  for (int i = tid; i < md.dims[NH] / 2; i += 512)
+    reinterpret_cast<uint32_t *>(auxs + md.wl_off)[i] = pack_bf16(md.aux[md.wl_off + 2 * i], md.aux[md.wl_off + 2 * i + 1]);
   const uint4 *const wbase = md.w_stream + (size_t)w * md.wave_stride + lane;
   const uint4 *wp = wbase;
   uint4 ring[PD][RT];
@@ -356,7 +359,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
             __syncthreads();
           } else {
             // last hidden layer: round to bf16 and multiply with the output vector at once
-            const float *wl = auxs + md.wl_off;
+            const uint32_t *wl = reinterpret_cast<const uint32_t *>(auxs + md.wl_off);
 #pragma unroll
             for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
 #pragma unroll
@@ -364,7 +367,10 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
               const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
 #pragma unroll
               for (int g = 0; g < 4; ++g) {
-                const float4 wv = *reinterpret_cast<const float4 *>(wl + mbase + 8 * g);
+                const uint2 wpair = *reinterpret_cast<const uint2 *>(wl + (mbase + 8 * g) / 2);
+                float4 wv;
+                wv.x = __uint_as_float(wpair.x << 16); wv.y = __uint_as_float(wpair.x & 0xffff0000u);
+                wv.z = __uint_as_float(wpair.y << 16); wv.w = __uint_as_float(wpair.y & 0xffff0000u);
 #pragma unroll
                 for (int c = 0; c < CT; ++c) {
                   uint32_t q0 = pack_bf16(relu_bits(acc[r][c][4 * g + 0]), relu_bits(acc[r][c][4 * g + 1]));
@@ -481,7 +487,8 @@ typedef void (*whole_kernel)(vf_fast_dev, int, int64_t, int, unsigned long long 
 static whole_kernel whole_launch_shape(const vf_ctx *c, vf_fast_dev *fd, int *ks, size_t *smem) {
   int NC = 0;
   vfk_fast_dev(c, true, fd, ks, &NC);
-  *smem = (size_t)NC * *ks * 2 + (size_t)NC * 64 * 2 + (size_t)8 * NC * 4 + (size_t)2 * NC * 4 + (size_t)fd->naux * 4;
+  const size_t aux_words = fd->wl_off + (size_t)(fd->naux - (int)fd->wl_off + 1) / 2;  // output vector: two to a word
+  *smem = (size_t)NC * *ks * 2 + (size_t)NC * 64 * 2 + (size_t)8 * NC * 4 + (size_t)2 * NC * 4 + aux_words * 4;
   return NC == 64 ? k_whole<64, 4, 2> : k_whole<128, 2, 4>;
 }
 
