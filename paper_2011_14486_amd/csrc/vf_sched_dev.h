@@ -160,6 +160,16 @@ __device__ __forceinline__ Digits digits_of(const vf_space &sp, uint32_t cid) {
   g.isat = r;
   return g;
 }
+__device__ __forceinline__ uint32_t id_of(const vf_space &sp, const Digits &g) {
+  uint32_t r = g.isat;
+  r = r * (uint32_t)sp.ncat + g.icat;
+  r = r * (uint32_t)sp.npar + g.par;
+  r = r * (uint32_t)sp.nvec + g.vec;
+  r = r * (uint32_t)sp.nperm + g.ip;
+  r = r * (uint32_t)sp.nf[2] + g.ic;
+  r = r * (uint32_t)sp.nf[1] + g.iy;
+  return r * (uint32_t)sp.nf[0] + g.ix;
+}
 __device__ __forceinline__ uint32_t pack_digits(const Digits &g) {
   return g.ix | g.iy << 4 | g.ic << 8 | g.ip << 12 | g.vec << 16 | g.par << 20 | g.icat << 24 | g.isat << 28;
 }

@@ -36,7 +36,7 @@ namespace {
 struct WholeArgs {
   Tables t;
   int first, last;
-  int2 *list;      // [nprob][Mpad] scratch for the lists of valid candidates: (id, packed digits)
+  uint32_t *list;  // [nprob][Mpad] scratch for the lists of valid candidates (their packed digits)
   int64_t Mpad;
   int team;                  // workgroups per problem; grid = nprob * team <= compute units when > 1
   float *team_val;           // [2][nprob][team] per-member minima, by layer parity
@@ -95,7 +95,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
 
   for (int unit = (int)blockIdx.x / team; unit < nprob; unit += (int)gridDim.x / team)
   for (int stage = wa.first; stage <= wa.last; ++stage) {
-    int2 *const idlist = wa.list + (size_t)unit * wa.Mpad;
+    uint32_t *const idlist = wa.list + (size_t)unit * wa.Mpad;
     fill_decpack(pk, wa.t, unit, stage);
     fill_evaltabs(tabs, pk.d, pk.sp);
     na.stage = stage;
@@ -103,10 +103,11 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     // rules: per (compute_at, store_at) digit pair that is open - the level is offered and
     // the hoist does not exceed it - the valid ids are the products of the split factors
     // that fit the level's region with every loop order / vectorize / parallel choice;
-    // an inlining pair has the single id with every other digit zero.  The digits go into
-    // the list with the id, so that the evaluation does not have to take the id apart again.
+    // an inlining pair has the single id with every other digit zero.  The list holds the
+    // digits, packed, rather than the id: the evaluation works on digits, and putting an id
+    // together takes a few multiplications where taking it apart takes as many divisions.
     __shared__ int ncand, g_npairs;
-    __shared__ int g_pos[13], g_base[12], g_cat[12], g_dec[12];
+    __shared__ int g_pos[13], g_cat[12], g_dec[12];
     __shared__ int g_nok[3][3], g_ok[3][3][8];
     if (tid < 9) {
       const int lvl = tid / 3, dd = tid % 3;
@@ -117,7 +118,6 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     }
     __syncthreads();
     const int rest_n = pk.sp.nperm * pk.sp.nvec * pk.sp.npar;
-    const int run_n = pk.sp.nf[0] * pk.sp.nf[1] * pk.sp.nf[2] * rest_n;
     if (tid == 0) {
       int np = 0, pos = 0;
       for (int isat = 0; isat < pk.sp.nsat; ++isat)
@@ -129,7 +129,6 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
           else if (isat <= cat) cnt = g_nok[cat][0] * g_nok[cat][1] * g_nok[cat][2] * rest_n;
           if (cnt == 0) continue;
           g_pos[np] = pos;
-          g_base[np] = (icat + pk.sp.ncat * isat) * run_n;
           g_cat[np] = cat;
           g_dec[np] = (int)((uint32_t)icat << 24 | (uint32_t)isat << 28);
           pos += cnt;
@@ -144,7 +143,6 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       int q = 0;
       while (q + 1 < g_npairs && k >= g_pos[q + 1]) ++q;
       const int cat = g_cat[q];
-      int cid = g_base[q];
       uint32_t dec = (uint32_t)g_dec[q];
       if (cat != VF_INLINE) {
         int r = k - g_pos[q];
@@ -153,13 +151,12 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
         const int jy = r % ny; r /= ny;
         const int jc = r % nc; r /= nc;
         const int ix = g_ok[cat][0][jx], iy = g_ok[cat][1][jy], ic = g_ok[cat][2][jc];
-        cid += ix + pk.sp.nf[0] * (iy + pk.sp.nf[1] * (ic + pk.sp.nf[2] * r));
         const int ip = r % pk.sp.nperm; r /= pk.sp.nperm;
         const int vec = r % pk.sp.nvec, par = r / pk.sp.nvec;
         dec |= (uint32_t)ix | (uint32_t)iy << 4 | (uint32_t)ic << 8 | (uint32_t)ip << 12 | (uint32_t)vec << 16 |
                (uint32_t)par << 20;
       }
-      idlist[k] = make_int2(cid, (int)dec);
+      idlist[k] = dec;
     }
     if (fold) {
       // the first layer's product with the 192 rows that all candidates of the decision
@@ -210,9 +207,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     auto featurize = [&](int nb, int par) __attribute__((always_inline)) {
       const int n = tid % NC, part = tid / NC;
       const bool inb = (nb + n) < ncands;
-      const int2 entry = inb ? idlist[nb + n] : make_int2(0, 0);
-      const uint32_t cid = (uint32_t)entry.x;
-      const Digits dg = unpack_digits((uint32_t)entry.y);
+      const Digits dg = unpack_digits(inb ? idlist[nb + n] : 0u);
       int32_t core[64];
       uint16_t *const col = xin + (size_t)n * 64;
       const int sw = (n >> 1) & 7;
@@ -228,7 +223,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       if (part == 0) {
         // evaluated for padding ids too: core must be defined before it is packed
         const bool valid = eval_digits<true>(pk.d, pk.sp, dg, &tabs, core);
-        okf[par * NC + n] = (inb && valid) ? (int32_t)cid + 1 : 0;
+        okf[par * NC + n] = (inb && valid) ? (int32_t)id_of(pk.sp, dg) + 1 : 0;
         put8(core, 0);
         put8(core + 8, 1);
         put8(core + 40, 5);
@@ -532,7 +527,7 @@ int vfk_whole_team(const vf_ctx *c) {
 int vfk_greedy_whole(vf_ctx *c, int first, int last) {
   const int team = vfk_whole_team(c);
   if (team < 1) return VF_ESTATE;
-  const size_t want = (size_t)2 * c->B * c->Mpad;  // (id, digits) per entry
+  const size_t want = (size_t)c->B * c->Mpad;
   if (want > c->wlist_elems) {
     if (c->d_wlist) { VF_HIP(c, hipStreamSynchronize(c->stream)); (void)hipFree(c->d_wlist); c->d_wlist = nullptr; }
     c->wlist_elems = 0;
@@ -568,7 +563,7 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
   WholeArgs wa;
   wa.t = tables_of(c);
   wa.first = first; wa.last = last;
-  wa.list = reinterpret_cast<int2 *>(c->d_wlist); wa.Mpad = c->Mpad;
+  wa.list = reinterpret_cast<uint32_t *>(c->d_wlist); wa.Mpad = c->Mpad;
   wa.team = team;
   wa.team_count = c->d_team;
   wa.team_err = reinterpret_cast<int32_t *>(c->d_team) + c->B;
