@@ -22,8 +22,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at batch 256, scaled by a
 # plain 1 GiB copy (profiles/*_hbm_counters.txt); only valid for the default batch, and to be
 # set to None whenever the kernel changes without the counters being taken again
-TRAFFIC_SCORE_BYTES = {256: 9241.1 * 1024 * 2.0 + 70251.5 * 1024}
-TRAFFIC_FEATURIZE_BYTES = {256: 2238.4 * 1024 * 2.0 + 1073741824.0}
+TRAFFIC_SCORE_BYTES = {256: 12003.1 * 1024 * 2.0 + 73346.2 * 1024}
+TRAFFIC_FEATURIZE_BYTES = {256: 2208.4 * 1024 * 2.0 + 1073741824.0}
 
 
 def mlp_flops(dims):
@@ -137,7 +137,7 @@ def main():
     flops_per_launch = fused_mlp_flops(dims) * scored / max(n_score, 1)
     score_ms = ms_score / max(n_score, 1)
     achieved = flops_per_launch / (score_ms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "k_mlp_fast<128,2,4,gen,whole> (Algorithm 1 per problem in one workgroup: enumerate+featurize+MLP+argmin+commit)", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
+    roofline = {"bound": "mfma", "kernel": "k_whole<128,2,4> (Algorithm 1 per problem in one workgroup: enumerate+featurize+MLP+argmin+commit)", "achieved": achieved, "peak": PEAK_BF16_TFLOPS,
                 "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": TRAFFIC_SCORE_BYTES.get(B),
                 "flops_per_candidate_executed": fused_mlp_flops(dims), "flops_per_candidate_model": mlp_flops(dims),
                 "launch_ms": score_ms, "launches": n_score}
