@@ -64,9 +64,9 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
   __shared__ DecPack pk;
   __shared__ EvalTabs tabs;  // the decision's quotient tables: no division per candidate
   __shared__ int team_failed;
-  __shared__ float sv[NWS];      // per scanning wave: the incumbent of the scan over its columns ...
+  __shared__ float sv[NWS];      // per scanning wave: the minimum over its columns at the end of a layer
   __shared__ int32_t sc[NWS];
-  __shared__ unsigned int sn[NWS][2];  // ... and what it counted (candidates, valid ones)
+  __shared__ unsigned int sn[2];  // what the layer counted (candidates, valid ones)
   // with 256 input rows, rows 64..255 are the same for all candidates of a decision
   // (neighbour stages): their part of the first layer is a per-decision bias, which
   // replaces the layer's bias in LDS, and the contraction runs over the 64 core rows only
@@ -241,11 +241,13 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       }
     };
 
-    if (w < NWS && lane == 0) {
-      sv[w] = __builtin_inff();
-      sc[w] = -1;
-      sn[w][0] = sn[w][1] = 0u;
-    }
+    // Waves below NWS scan the scores: thread tid keeps the incumbent of column tid over the
+    // tiles of the layer (and counts, candidates in the low half, valid ones in the high half),
+    // the columns are reduced once per layer.
+    float col_v = __builtin_inff();
+    int32_t col_c = -1;
+    unsigned int col_n = 0u;
+    if (tid == 0) sn[0] = sn[1] = 0u;
     // the loop starts one tile early: that round only produces the first tile's features
     int par = 1;
     for (int t = member - team; t < ntiles; t += team, par ^= 1) {
@@ -401,32 +403,28 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
         const int32_t flag = okf[par * NC + tid];
         const int32_t colid = flag - 1;
         if (na.eps != 0.0f) s = add_noise(na, s, unit, colid);
-        float v = __builtin_inff();
-        int32_t c = -1;
-        if (flag != 0 && s < v) { v = s; c = colid; }
-        wave_min(v, c);
-        const unsigned int n_ok = (unsigned int)__popcll(__ballot(flag != 0));
-        const unsigned int n_in = (unsigned int)__popcll(__ballot(t * NC + tid < ncands));
-        if (lane == 0) {
-          float rv = sv[w];
-          int32_t rc = sc[w];
-          take_min(rv, rc, v, c);
-          sv[w] = rv;
-          sc[w] = rc;
-          sn[w][0] += n_in;
-          sn[w][1] += n_ok;
-        }
+        // (+inf and NaN never win: Algorithm 1 compares with a strict "<" from +inf)
+        if (flag != 0 && s < __builtin_inff()) take_min(col_v, col_c, s, colid);
+        col_n += (t * NC + tid < ncands ? 1u : 0u) + (flag != 0 ? 0x10000u : 0u);
       }
       // no barrier here: the next tile's first layer reads the input buffer and the bias
       // only; its activations are written behind this barrier, the partial dots and the
       // flags of the other parity behind the next tile's first one
     }
 
-    if (stat && w < NWS && lane == 0 && sn[w][0]) {
-      atomicAdd(&stat[0], (unsigned long long)sn[w][0]);
-      atomicAdd(&stat[1], (unsigned long long)sn[w][1]);
+    if (w < NWS) {
+      wave_min(col_v, col_c);
+      if (lane == 0) { sv[w] = col_v; sc[w] = col_c; }
+      if (stat && col_n) {
+        atomicAdd(&sn[0], col_n & 0xffffu);
+        atomicAdd(&sn[1], col_n >> 16);
+      }
     }
     __syncthreads();
+    if (stat && tid == 0 && sn[0]) {
+      atomicAdd(&stat[0], (unsigned long long)sn[0]);
+      atomicAdd(&stat[1], (unsigned long long)sn[1]);
+    }
     float run_v = sv[0];
     int32_t run_c = sc[0];
     if (tid == 0)
