@@ -33,18 +33,37 @@ namespace {
 // in global memory (one arrival per member and layer, bounded wait), and every member then
 // reduces all minima and commits by itself - the members write identical values to the
 // tables and the list, so one meeting per layer is enough.
+//
+// With about as many problems as compute units (team = 1) the problems differ in size, and
+// the launch would take as long as the largest one.  Then a workgroup that has finished its
+// own problems (or never had one) becomes a helper: it picks the running problem that is
+// furthest behind, registers with it, and from the next layer that the problem's owner
+// announces it works as one more member of that problem's team (at most VF_MAX_HELPERS per
+// problem) until the problem is done; then it looks for the next one.  The owner decides the
+// team of a layer when it starts the layer - the helpers registered by then - and publishes
+// it with the arrival count the meeting has to reach; a helper builds the layer's context
+// from the tables the owner's commits have left in memory.  The grid is one workgroup per
+// compute unit, so every workgroup that is waited for is resident.
 struct WholeArgs {
   Tables t;
   int first, last;
   uint32_t *list;  // [nprob][Mpad] scratch for the lists of valid candidates (their packed digits)
   int64_t Mpad;
   int team;                  // workgroups per problem; grid = nprob * team <= compute units when > 1
-  float *team_val;           // [2][nprob][team] per-member minima, by layer parity
+  int helpers;               // team == 1: finished workgroups help (grid = compute units)
+  int tstride;               // slots per problem in team_val / team_idx
+  float *team_val;           // [2][nprob][tstride] per-member minima, by layer parity
   int32_t *team_idx;
-  unsigned int *team_count;  // [nprob], zero at launch
+  unsigned int *team_count;  // [nprob] arrivals at the meetings, zero at launch
   int32_t *team_err;         // set if a wait ran out
+  // helpers (all zero at launch), per problem:
+  unsigned int *ann;         // announcement of the running layer: (layers started << 8) | team size
+  unsigned int *tgt;         // arrivals the meeting of that layer waits for
+  unsigned int *nhelp;       // helpers registered
+  unsigned int *done;        // the problem's last layer is committed
 };
 constexpr unsigned int VF_TEAM_SPINS = 1u << 22;
+constexpr int VF_MAX_HELPERS = 3;
 
 // NC candidates per tile, RT row tiles per wave (hidden width 256 * RT), PD k-steps of
 // weight fragments in flight per wave.  stat: nullable, [0] += candidates pushed through
@@ -90,11 +109,104 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     for (int r = 0; r < RT; ++r) ring[j][r] = wp[(j * RT + r) * 64];
   wp += PD * RT * 64;
 
-  const int team = wa.team, member = (int)blockIdx.x % team;
   if (tid == 0) team_failed = 0;
-
-  for (int unit = (int)blockIdx.x / team; unit < nprob; unit += (int)gridDim.x / team)
-  for (int stage = wa.first; stage <= wa.last; ++stage) {
+  // what this workgroup does next: a layer of one of its own problems (owner), or of a problem
+  // it helps with.  Thread 0 decides and hands the result to the others through LDS.
+  __shared__ int job_unit, job_stage, job_team, job_member;
+  __shared__ unsigned int pick_best;
+  bool helping = false;
+  int unit = (int)blockIdx.x / wa.team, stage = wa.first;
+  // thread 0 only - owner: arrivals all meetings of the problem so far waited for; helper: the
+  // problem it is registered with (-1: none), its member index there, the last announcement seen
+  unsigned int owner_target = 0u;
+  int h_unit = -1, h_member = 0;
+  unsigned int h_seen = 0u;
+  for (;;) {
+    int team = wa.team, member = (int)blockIdx.x % wa.team;
+    if (!helping && unit >= nprob) {
+      if (!wa.helpers) break;
+      helping = true;
+    }
+    if (!helping) {
+      if (wa.helpers) {
+        // owner: the helpers registered by now join this layer
+        if (tid == 0) {
+          unsigned int nh = __hip_atomic_load(&wa.nhelp[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (nh > (unsigned int)VF_MAX_HELPERS) nh = VF_MAX_HELPERS;
+          job_team = 1 + (int)nh;
+          if (nh > 0u) owner_target += 1u + nh;
+          wa.tgt[unit] = owner_target;
+          __threadfence();  // the tables of the layers before and the target, then the announcement
+          __hip_atomic_store(&wa.ann[unit], ((unsigned int)(stage - wa.first + 1) << 8) | (1u + nh), __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+        }
+        __syncthreads();
+        team = job_team;
+        member = 0;
+      }
+    } else {
+      // helper: find a problem to help with, then wait for its owner to announce a layer that
+      // counts this workgroup in (every wait is bounded; a problem that is done is left)
+      __syncthreads();
+      bool found = false;
+      for (int attempt = 0; attempt < 64 && !found; ++attempt) {
+        if (tid == 0) pick_best = 0xffffffffu;
+        __syncthreads();
+        if (tid == 0) job_unit = h_unit;  // only thread 0 knows where it is registered
+        __syncthreads();
+        if (job_unit < 0) {
+          // the running problem that is furthest behind and has room for a helper
+          for (int u = tid; u < nprob; u += 512) {
+            if (__hip_atomic_load(&wa.done[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) continue;
+            if (__hip_atomic_load(&wa.nhelp[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= (unsigned int)VF_MAX_HELPERS) continue;
+            const unsigned int a = __hip_atomic_load(&wa.ann[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((a >> 8) == 0u) continue;  // not started: its owner is still busy with another problem
+            atomicMin(&pick_best, ((a >> 8) << 16) | (unsigned int)u);
+          }
+          __syncthreads();
+          if (pick_best == 0xffffffffu) break;  // nothing to help with
+          if (tid == 0) {
+            const int u = (int)(pick_best & 0xffffu);
+            const unsigned int old = atomicAdd(&wa.nhelp[u], 1u);
+            if (old >= (unsigned int)VF_MAX_HELPERS) {
+              atomicSub(&wa.nhelp[u], 1u);  // somebody else was faster: look again
+            } else {
+              // (the layer that is running may already count this workgroup in: the owner
+              // may have read the registration before this thread reads the announcement)
+              h_unit = u;
+              h_member = (int)old + 1;
+              h_seen = 0u;
+            }
+          }
+        }
+        if (tid == 0) {
+          job_stage = -1;
+          if (h_unit >= 0) {
+            unsigned int spins = 0;
+            for (;;) {
+              const unsigned int a = __hip_atomic_load(&wa.ann[h_unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              if ((a >> 8) > h_seen) {
+                h_seen = a >> 8;
+                if ((int)(a & 255u) > h_member) {  // this layer counts this workgroup in
+                  job_unit = h_unit; job_stage = wa.first + (int)h_seen - 1;
+                  job_team = (int)(a & 255u); job_member = h_member;
+                  break;
+                }
+              }
+              if (__hip_atomic_load(&wa.done[h_unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) { h_unit = -1; break; }
+              if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
+              __builtin_amdgcn_s_sleep(8);
+            }
+            __threadfence();  // what the owner wrote before the announcement is read from memory
+          }
+        }
+        __syncthreads();
+        if (team_failed) return;
+        found = job_stage >= 0;
+      }
+      if (!found) break;
+      unit = job_unit; stage = job_stage; team = job_team; member = job_member;
+    }
     uint32_t *const idlist = wa.list + (size_t)unit * wa.Mpad;
     fill_decpack(pk, wa.t, unit, stage);
     fill_evaltabs(tabs, pk.d, pk.sp);
@@ -431,13 +543,14 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       for (int k = 1; k < NWS; ++k) take_min(run_v, run_c, sv[k], sc[k]);
     if (team > 1) {
       // publish this member's minimum, meet the team, reduce everybody's minima
-      const size_t slot0 = ((size_t)(stage & 1) * nprob + unit) * team;
+      const size_t slot0 = ((size_t)(stage & 1) * nprob + unit) * wa.tstride;
       if (tid == 0) {
         wa.team_val[slot0 + member] = run_v;
         wa.team_idx[slot0 + member] = run_c;
         __threadfence();
         atomicAdd(&wa.team_count[unit], 1u);
-        const unsigned int target = (unsigned int)team * (unsigned int)(stage - wa.first + 1);
+        const unsigned int target = wa.helpers ? __hip_atomic_load(&wa.tgt[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                                               : (unsigned int)team * (unsigned int)(stage - wa.first + 1);
         unsigned int spins = 0;
         while (__hip_atomic_load(&wa.team_count[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
           if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
@@ -465,6 +578,15 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     if (tid == 0) commit_winner_call(wa.t, pk.d, pk.sp, unit, stage, run_c, run_v, (uint32_t)M);
     __threadfence();
     __syncthreads();
+    // what comes next: an owner goes on to the next layer, then to its next problem; a helper
+    // goes back to waiting for an announcement
+    if (!helping && ++stage > wa.last) {
+      if (wa.helpers && tid == 0)
+        __hip_atomic_store(&wa.done[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // (behind the fence above)
+      stage = wa.first;
+      unit += (int)gridDim.x / wa.team;
+      owner_target = 0u;
+    }
   }
 }
 
@@ -532,17 +654,19 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
     if (hipMalloc((void **)&c->d_wlist, want * 4) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
     c->wlist_elems = want;
   }
-  if (team > 1) {
-    // [count B][err 1][values 2*B*team][ids 2*B*team]
-    const size_t twant = (size_t)c->B + 1 + (size_t)4 * c->B * team;
+  // meetings: [arrivals B][err 1][announcement B][target B][helpers B][done B][values 2*B*T][ids 2*B*T],
+  // T slots per problem; everything before the values starts at zero
+  const int tstride = team > 1 ? team : 1 + VF_MAX_HELPERS;
+  const size_t nzero = (size_t)5 * c->B + 1;
+  {
+    const size_t twant = nzero + (size_t)4 * c->B * tstride;
     if (twant > c->team_elems) {
       if (c->d_team) { VF_HIP(c, hipStreamSynchronize(c->stream)); (void)hipFree(c->d_team); c->d_team = nullptr; }
       c->team_elems = 0;
       if (hipMalloc((void **)&c->d_team, twant * 4) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
       c->team_elems = twant;
     }
-    hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)((c->B + 1 + 255) / 256)), dim3(256), 0, c->stream, c->d_team,
-                       (size_t)c->B + 1);
+    hipLaunchKernelGGL(k_zero_u32, dim3((unsigned)((nzero + 255) / 256)), dim3(256), 0, c->stream, c->d_team, nzero);
     VF_HIP(c, hipGetLastError());
     if (!c->h_team_err) {
       VF_HIP(c, hipHostMalloc((void **)&c->h_team_err, sizeof(int32_t), hipHostMallocDefault));
@@ -563,14 +687,21 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
   wa.first = first; wa.last = last;
   wa.list = reinterpret_cast<uint32_t *>(c->d_wlist); wa.Mpad = c->Mpad;
   wa.team = team;
+  wa.helpers = team == 1;
+  wa.tstride = tstride;
   wa.team_count = c->d_team;
   wa.team_err = reinterpret_cast<int32_t *>(c->d_team) + c->B;
-  wa.team_val = reinterpret_cast<float *>(c->d_team) + c->B + 1;
-  wa.team_idx = reinterpret_cast<int32_t *>(c->d_team) + c->B + 1 + (size_t)2 * c->B * team;
+  wa.ann = c->d_team + c->B + 1;
+  wa.tgt = wa.ann + c->B;
+  wa.nhelp = wa.tgt + c->B;
+  wa.done = wa.nhelp + c->B;
+  wa.team_val = reinterpret_cast<float *>(c->d_team) + nzero;
+  wa.team_idx = reinterpret_cast<int32_t *>(c->d_team) + nzero + (size_t)2 * c->B * tstride;
   int ncu = 256;
   (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
-  // persistent: at most one workgroup per compute unit
-  const dim3 grid = team > 1 ? dim3((unsigned)(c->B * team)) : dim3((unsigned)(c->B < ncu ? c->B : ncu));
+  // persistent: at most one workgroup per compute unit; with helpers exactly one, so that
+  // compute units without a problem of their own help from the start
+  const dim3 grid = team > 1 ? dim3((unsigned)(c->B * team)) : dim3((unsigned)ncu);
   {
     vf_prof_scope prof(c, VF_PROF_SCORE);
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
@@ -579,8 +710,8 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
     VF_HIP(c, hipGetLastError());
   }
   c->dec_stage = -1;
-  if (team > 1)  // the flag of a meeting that ran out, for the next call to look at
-    VF_HIP(c, hipMemcpyAsync(c->h_team_err, reinterpret_cast<int32_t *>(c->d_team) + c->B, sizeof(int32_t),
+  // the flag of a wait that ran out, for the next call to look at
+  VF_HIP(c, hipMemcpyAsync(c->h_team_err, reinterpret_cast<int32_t *>(c->d_team) + c->B, sizeof(int32_t),
                              hipMemcpyDeviceToHost, c->stream));
   return VF_OK;
 }

@@ -424,3 +424,40 @@ def test_whole_schedule_launch_other_depths(vf, ovf, dims):
     for b in (0, B - 1):
         compare_schedule(ovf, pipes[b], sp, model, w, whole[1][b], whole[2][b], whole[0][b], TOL[1])
     vf.vf_destroy(ctx)
+
+
+def test_whole_schedule_launch_with_helpers_from_the_start(vf, ovf):
+    """200 problems on 256 compute units: the workgroups without a problem of their own help
+    the others from the first layers on (and the ones that finish early later); a problem that
+    ends early and exploration noise included.  Same tables as stepping layer by layer; the
+    counters say that only listed candidates were scored; two problems against the checker."""
+    B = 200
+    pipes = I.resnet18_batch(B, seed=33)
+    pipes[5, 2, 3] = 2
+    sp = I.make_space([1, 2, 4], [1, 4], [4, 8], [(0, 1, 2), (2, 1, 0)], 2, 2,
+                      [I.ROOT, I.L1, I.L2, I.INLINE], 2, 256)
+    dims = [256, 512, 512, 1]
+    w = I.mlp_weights(dims, 8, bias_std=0.1)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    S = pipes.shape[1]
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipes); vf.vf_set_model(ctx, model, w)
+    for eps in (0.0, 0.1):
+        vf.vf_set_noise(ctx, eps, seed=3)
+        vf.vf_reset_state(ctx)
+        vf.vf_profile_enable(ctx, True); vf.vf_profile_counts(ctx)
+        whole = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
+        scored, valid = vf.vf_profile_counts(ctx)
+        vf.vf_profile_enable(ctx, False)
+        assert scored == valid > 0
+        vf.vf_reset_state(ctx)
+        for i in range(S):
+            vf.vf_argmin_step(ctx, i, True)
+        steps = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=S)]
+        for a, b in zip(whole, steps):
+            assert np.array_equal(a, b)
+        assert (whole[1][5, 2:] == -1).all()
+        if eps == 0.0:
+            for b in (0, B - 1):
+                compare_schedule(ovf, pipes[b], sp, model, w, whole[1][b], whole[2][b], whole[0][b], TOL[1])
+    vf.vf_destroy(ctx)
