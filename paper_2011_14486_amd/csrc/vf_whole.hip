@@ -155,18 +155,24 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
         if (tid == 0) job_unit = h_unit;  // only thread 0 knows where it is registered
         __syncthreads();
         if (job_unit < 0) {
-          // the running problem that is furthest behind and has room for a helper
+          // the running problem that is furthest behind and has room for a helper; among equals
+          // the one with the fewest helpers, then a different one for every workgroup
           for (int u = tid; u < nprob; u += 512) {
             if (__hip_atomic_load(&wa.done[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) continue;
-            if (__hip_atomic_load(&wa.nhelp[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= (unsigned int)VF_MAX_HELPERS) continue;
+            const unsigned int nh = __hip_atomic_load(&wa.nhelp[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (nh >= (unsigned int)VF_MAX_HELPERS) continue;
             const unsigned int a = __hip_atomic_load(&wa.ann[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if ((a >> 8) == 0u) continue;  // not started: its owner is still busy with another problem
-            atomicMin(&pick_best, ((a >> 8) << 16) | (unsigned int)u);
+            // not started yet: fine if its owner starts with it (it is about to announce the first
+            // layer), not if the owner is still busy with another problem
+            if ((a >> 8) == 0u && u >= (int)gridDim.x) continue;
+            const unsigned int layers = (a >> 8) < 8191u ? (a >> 8) : 8191u;
+            const unsigned int turned = (unsigned int)(u + nprob - (int)(blockIdx.x % (unsigned int)nprob)) % (unsigned int)nprob;
+            atomicMin(&pick_best, (layers << 19) | (nh << 16) | turned);
           }
           __syncthreads();
           if (pick_best == 0xffffffffu) break;  // nothing to help with
           if (tid == 0) {
-            const int u = (int)(pick_best & 0xffffu);
+            const int u = (int)(((pick_best & 0xffffu) + blockIdx.x) % (unsigned int)nprob);
             const unsigned int old = atomicAdd(&wa.nhelp[u], 1u);
             if (old >= (unsigned int)VF_MAX_HELPERS) {
               atomicSub(&wa.nhelp[u], 1u);  // somebody else was faster: look again
@@ -610,12 +616,14 @@ static whole_kernel whole_launch_shape(const vf_ctx *c, vf_fast_dev *fd, int *ks
 // Workgroups per problem for a whole-schedule launch, 0 = use the per-layer launches
 // (also when the model's tile does not fit the LDS of a compute unit next to its input
 // buffer, e.g. three hidden layers of 512 with all their biases).
-// 1 when the problems fill the compute units by themselves (each workgroup then owns
-// ceil(B / units) problems from the first layer to the last; measured break-even against
-// the per-layer launches: about 72 % of the slots filled); with fewer problems a team per
-// problem, as large as the compute units and the tiles of a decision allow, at most 16
-// (measured: 128 problems x 2: 3.6 instead of 4.9 ms per step, 64 x 4: 2.3 instead of 3.4,
-// 32 x 8: 1.9 instead of 2.2; below 16 problems the meetings cost what the launches did).
+// 1 with more problems than half the compute units: every workgroup owns ceil(B / units)
+// problems from the first layer to the last and helps the others when it is done (measured
+// per step against the per-layer launches: 140 problems 3.6 instead of 5.1 ms, 160: 4.0
+// instead of 5.6, 300: 7.0 instead of 8.5); with fewer problems a fixed team per problem, as
+// large as the compute units and the tiles of a decision allow, at most 16 (128 problems x
+// 2: 3.1 instead of 4.9 ms, 64 x 4: 2.1 instead of 3.4, 32 x 8: 1.7 instead of 2.2; helpers
+// instead of fixed teams are slower there: 64 problems 2.9 ms); below 16 problems the
+// meetings cost what the launches did.
 int vfk_whole_team(const vf_ctx *c) {
   if (!vfk_can_fuse_step(c)) return 0;
   {
@@ -630,9 +638,8 @@ int vfk_whole_team(const vf_ctx *c) {
   }
   int ncu = 256;
   (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
-  const int rounds = (c->B + ncu - 1) / ncu;
-  if ((double)c->B >= 0.72 * (double)rounds * (double)ncu) return 1;
-  if (c->B > ncu / 2 || c->B < 16) return 0;  // a handful of problems: the per-layer launches are as fast
+  if (c->B > ncu / 2) return 1;
+  if (c->B < 16) return 0;  // a handful of problems: the per-layer launches are as fast
   int maxw = 0;
   for (int l = 0; l < c->model.n_layers; ++l) if (c->model.dims[l] > maxw) maxw = c->model.dims[l];
   const int NC = maxw > 512 ? 64 : 128;
