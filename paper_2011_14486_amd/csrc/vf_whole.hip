@@ -34,36 +34,44 @@ namespace {
 // reduces all minima and commits by itself - the members write identical values to the
 // tables and the list, so one meeting per layer is enough.
 //
-// With about as many problems as compute units (team = 1) the problems differ in size, and
-// the launch would take as long as the largest one.  Then a workgroup that has finished its
-// own problems (or never had one) becomes a helper: it picks the running problem that is
-// furthest behind, registers with it, and from the next layer that the problem's owner
-// announces it works as one more member of that problem's team (at most VF_MAX_HELPERS per
-// problem) until the problem is done; then it looks for the next one.  The owner decides the
-// team of a layer when it starts the layer - the helpers registered by then - and publishes
-// it with the arrival count the meeting has to reach; a helper builds the layer's context
-// from the tables the owner's commits have left in memory.  The grid is one workgroup per
-// compute unit, so every workgroup that is waited for is resident.
+// With more problems than half the compute units (team = 1) the problems differ in size,
+// and the launch would take as long as the largest one.  Then a workgroup that has
+// finished its own problems (or never had one) becomes a helper: it queues up in a pool.
+// An owner that starts a layer with enough tiles takes up to VF_MAX_HELPERS workgroups out
+// of the pool and sends each of them the layer (problem, layer, team size, member index)
+// through its mailbox; the helper builds the layer's context from the tables the owner's
+// commits have left in memory, scores tiles member, member + team, ..., publishes its
+// minimum, reports its arrival and queues up again - it neither waits for anybody nor
+// commits.  The owner waits (bounded) for the arrivals of the helpers it sent for and commits
+// alone.  The grid is one workgroup per compute unit, so every workgroup that is waited
+// for is resident; helpers leave when every problem is done.
 struct WholeArgs {
   Tables t;
   int first, last;
   uint32_t *list;  // [nprob][Mpad] scratch for the lists of valid candidates (their packed digits)
   int64_t Mpad;
   int team;                  // workgroups per problem; grid = nprob * team <= compute units when > 1
-  int helpers;               // team == 1: finished workgroups help (grid = compute units)
+  int helpers;               // team == 1: idle workgroups help (grid = compute units)
   int tstride;               // slots per problem in team_val / team_idx
   float *team_val;           // [2][nprob][tstride] per-member minima, by layer parity
   int32_t *team_idx;
   unsigned int *team_count;  // [nprob] arrivals at the meetings, zero at launch
   int32_t *team_err;         // set if a wait ran out
-  // helpers (all zero at launch), per problem:
-  unsigned int *ann;         // announcement of the running layer: (layers started << 8) | team size
-  unsigned int *tgt;         // arrivals the meeting of that layer waits for
-  unsigned int *nhelp;       // helpers registered
-  unsigned int *done;        // the problem's last layer is committed
+  // the pool (all zero at launch)
+  unsigned int *pool;                // [0] entries taken, [1] entries put, [2] problems done
+  unsigned int *pool_q;              // [VF_POOL_SLOTS] workgroup id + 1 of a queued helper, 0 = empty
+  unsigned long long *mailbox;       // [grid] the layer a helper is sent: see mail_pack
 };
 constexpr unsigned int VF_TEAM_SPINS = 1u << 22;
 constexpr int VF_MAX_HELPERS = 3;
+constexpr int VF_POOL_SLOTS = 1024;       // more than the workgroups of a launch
+constexpr int VF_TILES_PER_MEMBER = 4;    // a helper is sent for when every member gets at least this many tiles
+
+__device__ __forceinline__ unsigned long long mail_pack(int unit, int stage, int team, int member) {
+  return 1ull << 63 | (unsigned long long)unit << 40 | (unsigned long long)stage << 16 |
+         (unsigned long long)team << 8 | (unsigned long long)member;
+}
+
 
 // NC candidates per tile, RT row tiles per wave (hidden width 256 * RT), PD k-steps of
 // weight fragments in flight per wave.  stat: nullable, [0] += candidates pushed through
@@ -110,107 +118,44 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
   wp += PD * RT * 64;
 
   if (tid == 0) team_failed = 0;
-  // what this workgroup does next: a layer of one of its own problems (owner), or of a problem
-  // it helps with.  Thread 0 decides and hands the result to the others through LDS.
+  // what this workgroup does next: a layer of one of its own problems (owner), or a layer it
+  // is sent as a helper.  Thread 0 finds out and hands the result to the others through LDS.
   __shared__ int job_unit, job_stage, job_team, job_member;
-  __shared__ unsigned int pick_best;
   bool helping = false;
   int unit = (int)blockIdx.x / wa.team, stage = wa.first;
-  // thread 0 only - owner: arrivals all meetings of the problem so far waited for; helper: the
-  // problem it is registered with (-1: none), its member index there, the last announcement seen
-  unsigned int owner_target = 0u;
-  int h_unit = -1, h_member = 0;
-  unsigned int h_seen = 0u;
+  unsigned int owner_target = 0u;  // thread 0, owner: helper arrivals the problem's layers so far sent for
   for (;;) {
     int team = wa.team, member = (int)blockIdx.x % wa.team;
     if (!helping && unit >= nprob) {
       if (!wa.helpers) break;
       helping = true;
     }
-    if (!helping) {
-      if (wa.helpers) {
-        // owner: the helpers registered by now join this layer
-        if (tid == 0) {
-          unsigned int nh = __hip_atomic_load(&wa.nhelp[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          if (nh > (unsigned int)VF_MAX_HELPERS) nh = VF_MAX_HELPERS;
-          job_team = 1 + (int)nh;
-          if (nh > 0u) owner_target += 1u + nh;
-          wa.tgt[unit] = owner_target;
-          __threadfence();  // the tables of the layers before and the target, then the announcement
-          __hip_atomic_store(&wa.ann[unit], ((unsigned int)(stage - wa.first + 1) << 8) | (1u + nh), __ATOMIC_RELAXED,
-                             __HIP_MEMORY_SCOPE_AGENT);
+    if (helping) {
+      // queue up in the pool, then wait for mail (bounded) or for every problem to be done
+      if (tid == 0) {
+        job_stage = -1;
+        const unsigned int slot = atomicAdd(&wa.pool[1], 1u);
+        __hip_atomic_store(&wa.pool_q[slot % VF_POOL_SLOTS], (unsigned int)blockIdx.x + 1u, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+        unsigned int spins = 0;
+        for (;;) {
+          const unsigned long long m = __hip_atomic_load(&wa.mailbox[blockIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (m != 0ull) {
+            job_unit = (int)((m >> 40) & 0x7fffffull); job_stage = (int)((m >> 16) & 0xffffffull);
+            job_team = (int)((m >> 8) & 255ull); job_member = (int)(m & 255ull);
+            // emptied before this workgroup queues up again
+            __hip_atomic_store(&wa.mailbox[blockIdx.x], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+          }
+          if (__hip_atomic_load(&wa.pool[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= (unsigned int)nprob) break;
+          if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
+          __builtin_amdgcn_s_sleep(8);
         }
-        __syncthreads();
-        team = job_team;
-        member = 0;
+        __threadfence();  // what the owner wrote before it sent the mail is read from memory
       }
-    } else {
-      // helper: find a problem to help with, then wait for its owner to announce a layer that
-      // counts this workgroup in (every wait is bounded; a problem that is done is left)
       __syncthreads();
-      bool found = false;
-      for (int attempt = 0; attempt < 64 && !found; ++attempt) {
-        if (tid == 0) pick_best = 0xffffffffu;
-        __syncthreads();
-        if (tid == 0) job_unit = h_unit;  // only thread 0 knows where it is registered
-        __syncthreads();
-        if (job_unit < 0) {
-          // the running problem that is furthest behind and has room for a helper; among equals
-          // the one with the fewest helpers, then a different one for every workgroup
-          for (int u = tid; u < nprob; u += 512) {
-            if (__hip_atomic_load(&wa.done[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) continue;
-            const unsigned int nh = __hip_atomic_load(&wa.nhelp[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (nh >= (unsigned int)VF_MAX_HELPERS) continue;
-            const unsigned int a = __hip_atomic_load(&wa.ann[u], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            // not started yet: fine if its owner starts with it (it is about to announce the first
-            // layer), not if the owner is still busy with another problem
-            if ((a >> 8) == 0u && u >= (int)gridDim.x) continue;
-            const unsigned int layers = (a >> 8) < 8191u ? (a >> 8) : 8191u;
-            const unsigned int turned = (unsigned int)(u + nprob - (int)(blockIdx.x % (unsigned int)nprob)) % (unsigned int)nprob;
-            atomicMin(&pick_best, (layers << 19) | (nh << 16) | turned);
-          }
-          __syncthreads();
-          if (pick_best == 0xffffffffu) break;  // nothing to help with
-          if (tid == 0) {
-            const int u = (int)(((pick_best & 0xffffu) + blockIdx.x) % (unsigned int)nprob);
-            const unsigned int old = atomicAdd(&wa.nhelp[u], 1u);
-            if (old >= (unsigned int)VF_MAX_HELPERS) {
-              atomicSub(&wa.nhelp[u], 1u);  // somebody else was faster: look again
-            } else {
-              // (the layer that is running may already count this workgroup in: the owner
-              // may have read the registration before this thread reads the announcement)
-              h_unit = u;
-              h_member = (int)old + 1;
-              h_seen = 0u;
-            }
-          }
-        }
-        if (tid == 0) {
-          job_stage = -1;
-          if (h_unit >= 0) {
-            unsigned int spins = 0;
-            for (;;) {
-              const unsigned int a = __hip_atomic_load(&wa.ann[h_unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-              if ((a >> 8) > h_seen) {
-                h_seen = a >> 8;
-                if ((int)(a & 255u) > h_member) {  // this layer counts this workgroup in
-                  job_unit = h_unit; job_stage = wa.first + (int)h_seen - 1;
-                  job_team = (int)(a & 255u); job_member = h_member;
-                  break;
-                }
-              }
-              if (__hip_atomic_load(&wa.done[h_unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) { h_unit = -1; break; }
-              if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
-              __builtin_amdgcn_s_sleep(8);
-            }
-            __threadfence();  // what the owner wrote before the announcement is read from memory
-          }
-        }
-        __syncthreads();
-        if (team_failed) return;
-        found = job_stage >= 0;
-      }
-      if (!found) break;
+      if (team_failed) return;
+      if (job_stage < 0) break;  // every problem is done
       unit = job_unit; stage = job_stage; team = job_team; member = job_member;
     }
     uint32_t *const idlist = wa.list + (size_t)unit * wa.Mpad;
@@ -275,6 +220,40 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
                (uint32_t)par << 20;
       }
       idlist[k] = dec;
+    }
+    if (wa.helpers && !helping) {
+      // owner: with enough tiles, take helpers out of the pool and send them this layer
+      if (tid == 0) {
+        int n = 0;
+        int want = (ncand + NC - 1) / NC / VF_TILES_PER_MEMBER - 1;
+        if (want > VF_MAX_HELPERS) want = VF_MAX_HELPERS;
+        for (int attempt = 0; attempt < 4 && want > 0 && n == 0; ++attempt) {
+          const unsigned int taken = __hip_atomic_load(&wa.pool[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const int avail = (int)(__hip_atomic_load(&wa.pool[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - taken);
+          if (avail <= 0) break;
+          const int take = avail < want ? avail : want;
+          if (atomicCAS(&wa.pool[0], taken, taken + (unsigned int)take) != taken) continue;  // somebody else took some
+          for (int i = 0; i < take; ++i) {
+            unsigned int *const q = &wa.pool_q[(taken + (unsigned int)i) % VF_POOL_SLOTS];
+            unsigned int id = 0u, spins = 0u;
+            // (the helper bumps the count before it writes its id)
+            while ((id = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == 0u) {
+              if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
+              __builtin_amdgcn_s_sleep(1);
+            }
+            if (id == 0u) break;
+            __hip_atomic_store(q, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&wa.mailbox[id - 1u], mail_pack(unit, stage, take + 1, i + 1), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+          }
+          n = take;
+        }
+        job_team = 1 + n;
+        owner_target += (unsigned int)n;
+      }
+      __syncthreads();
+      if (team_failed) return;
+      team = job_team;
     }
     if (fold) {
       // the first layer's product with the 192 rows that all candidates of the decision
@@ -548,28 +527,39 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     if (tid == 0)
       for (int k = 1; k < NWS; ++k) take_min(run_v, run_c, sv[k], sc[k]);
     if (team > 1) {
-      // publish this member's minimum, meet the team, reduce everybody's minima
+      // fixed team: every member publishes its minimum, meets the others and reduces all minima.
+      // pool: a helper publishes, reports its arrival and is done with the layer; the owner
+      // waits for the helpers it sent for and reduces their minima and its own
       const size_t slot0 = ((size_t)(stage & 1) * nprob + unit) * wa.tstride;
+      const bool pool = wa.helpers != 0;
       if (tid == 0) {
-        wa.team_val[slot0 + member] = run_v;
-        wa.team_idx[slot0 + member] = run_c;
-        __threadfence();
-        atomicAdd(&wa.team_count[unit], 1u);
-        const unsigned int target = wa.helpers ? __hip_atomic_load(&wa.tgt[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
-                                               : (unsigned int)team * (unsigned int)(stage - wa.first + 1);
-        unsigned int spins = 0;
-        while (__hip_atomic_load(&wa.team_count[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-          if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
-          __builtin_amdgcn_s_sleep(2);
+        if (!pool || helping) {
+          wa.team_val[slot0 + member] = run_v;
+          wa.team_idx[slot0 + member] = run_c;
+          __threadfence();
+          atomicAdd(&wa.team_count[unit], 1u);
         }
-        __threadfence();
+        if (!pool || !helping) {
+          const unsigned int target = pool ? owner_target : (unsigned int)team * (unsigned int)(stage - wa.first + 1);
+          unsigned int spins = 0;
+          while (__hip_atomic_load(&wa.team_count[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
+            if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
+            __builtin_amdgcn_s_sleep(2);
+          }
+          __threadfence();
+        }
       }
       __syncthreads();
       if (team_failed) return;  // a member never arrived: give up instead of waiting for ever
+      if (pool && helping) continue;
       if (tid < 64) {
         float v = __builtin_inff();
         int32_t c = -1;
         for (int m = tid; m < team; m += 64) {
+          if (pool && m == 0) {  // (thread 0: the owner's own minimum is not published)
+            take_min(v, c, run_v, run_c);
+            continue;
+          }
           const float mv = __hip_atomic_load(&wa.team_val[slot0 + m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           const int32_t mc = __hip_atomic_load(&wa.team_idx[slot0 + m], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           take_min(v, c, mv, mc);
@@ -578,6 +568,8 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
         run_v = v;
         run_c = c;
       }
+    } else if (helping) {
+      continue;  // (a helper is never sent a layer alone)
     }
     // s_i := the winner; the tables it updates are read back by this same workgroup
     // when it builds the next stage's context
@@ -587,8 +579,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     // what comes next: an owner goes on to the next layer, then to its next problem; a helper
     // goes back to waiting for an announcement
     if (!helping && ++stage > wa.last) {
-      if (wa.helpers && tid == 0)
-        __hip_atomic_store(&wa.done[unit], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // (behind the fence above)
+      if (wa.helpers && tid == 0) atomicAdd(&wa.pool[2], 1u);
       stage = wa.first;
       unit += (int)gridDim.x / wa.team;
       owner_target = 0u;
@@ -661,10 +652,15 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
     if (hipMalloc((void **)&c->d_wlist, want * 4) != hipSuccess) { (void)hipGetLastError(); return VF_ENOMEM; }
     c->wlist_elems = want;
   }
-  // meetings: [arrivals B][err 1][announcement B][target B][helpers B][done B][values 2*B*T][ids 2*B*T],
-  // T slots per problem; everything before the values starts at zero
+  // meetings: [arrivals B][err 1][pool counters 3][pool queue][mailboxes, 8 bytes per compute unit]
+  // [values 2*B*T][ids 2*B*T], T slots per problem; everything before the values starts at zero
+  int ncu = 256;
+  (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
+  if (ncu >= VF_POOL_SLOTS) return VF_ESTATE;
   const int tstride = team > 1 ? team : 1 + VF_MAX_HELPERS;
-  const size_t nzero = (size_t)5 * c->B + 1;
+  const size_t off_pool = (size_t)c->B + 1, off_q = off_pool + 3;
+  const size_t off_mail = (off_q + VF_POOL_SLOTS + 1) & ~(size_t)1;  // 8-byte aligned
+  const size_t nzero = off_mail + (size_t)2 * ncu;
   {
     const size_t twant = nzero + (size_t)4 * c->B * tstride;
     if (twant > c->team_elems) {
@@ -698,14 +694,11 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
   wa.tstride = tstride;
   wa.team_count = c->d_team;
   wa.team_err = reinterpret_cast<int32_t *>(c->d_team) + c->B;
-  wa.ann = c->d_team + c->B + 1;
-  wa.tgt = wa.ann + c->B;
-  wa.nhelp = wa.tgt + c->B;
-  wa.done = wa.nhelp + c->B;
+  wa.pool = c->d_team + off_pool;
+  wa.pool_q = c->d_team + off_q;
+  wa.mailbox = reinterpret_cast<unsigned long long *>(c->d_team + off_mail);
   wa.team_val = reinterpret_cast<float *>(c->d_team) + nzero;
   wa.team_idx = reinterpret_cast<int32_t *>(c->d_team) + nzero + (size_t)2 * c->B * tstride;
-  int ncu = 256;
-  (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
   // persistent: at most one workgroup per compute unit; with helpers exactly one, so that
   // compute units without a problem of their own help from the start
   const dim3 grid = team > 1 ? dim3((unsigned)(c->B * team)) : dim3((unsigned)ncu);
