@@ -245,6 +245,12 @@ int vf_profile_read(vf_ctx *ctx, int which, double *total_ms_host, int64_t *laun
  * decided without the network and are not counted).  vf_profile_counts synchronises,
  * returns both counts since the last call and clears them.  Either pointer may be NULL. */
 int vf_profile_counts(vf_ctx *ctx, int64_t *scored_host, int64_t *valid_host);
+/* Bound of the waits between the workgroups that share a problem inside a whole-schedule
+ * launch of vf_greedy_schedule, in polling rounds (default 2^22, seconds).  A wait that
+ * reaches the bound gives up: the launch still ends, its schedules are incomplete and the
+ * next vf_greedy_schedule returns VF_ESTATE.  A bound of 0 makes every wait that cannot be
+ * satisfied at once give up; meant for tests of that path. */
+int vf_set_wait_limit(vf_ctx *ctx, unsigned int rounds);
 
 #ifdef __cplusplus
 }

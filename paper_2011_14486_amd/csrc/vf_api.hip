@@ -539,4 +539,10 @@ int vf_profile_counts(vf_ctx *c, int64_t *scored, int64_t *valid) {
   return VF_OK;
 }
 
+int vf_set_wait_limit(vf_ctx *c, unsigned int rounds) {
+  if (!c) return VF_EINVAL;
+  c->wait_rounds = rounds;
+  return VF_OK;
+}
+
 }  // extern "C"

@@ -101,6 +101,7 @@ struct vf_ctx {
   float *d_pval = nullptr; int32_t *d_pidx = nullptr; size_t part_elems = 0;
   unsigned int *d_team = nullptr; size_t team_elems = 0;  // team meetings: counters, error flag, per-member minima
   int32_t *h_team_err = nullptr;  // pinned: the error flag of the last team launch, copied back after it
+  unsigned int wait_rounds = 1u << 22;  // bound of the waits between workgroups that share a problem
   int32_t *d_wlist = nullptr; size_t wlist_elems = 0;  // [B][Mpad] id lists of the whole-schedule launch
 
   hipEvent_t ev0 = nullptr, ev1 = nullptr;

@@ -57,12 +57,12 @@ struct WholeArgs {
   int32_t *team_idx;
   unsigned int *team_count;  // [nprob] arrivals at the meetings, zero at launch
   int32_t *team_err;         // set if a wait ran out
+  unsigned int wait_rounds;  // polling rounds after which a wait gives up
   // the pool (all zero at launch)
   unsigned int *pool;                // [0] entries taken, [1] entries put, [2] problems done
   unsigned int *pool_q;              // [VF_POOL_SLOTS] workgroup id + 1 of a queued helper, 0 = empty
   unsigned long long *mailbox;       // [grid] the layer a helper is sent: see mail_pack
 };
-constexpr unsigned int VF_TEAM_SPINS = 1u << 22;
 constexpr int VF_MAX_HELPERS = 3;
 constexpr int VF_POOL_SLOTS = 1024;       // more than the workgroups of a launch
 constexpr int VF_TILES_PER_MEMBER = 4;    // a helper is sent for when every member gets at least this many tiles
@@ -148,7 +148,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
             break;
           }
           if (__hip_atomic_load(&wa.pool[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= (unsigned int)nprob) break;
-          if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
+          if (++spins > wa.wait_rounds) { team_failed = 1; wa.team_err[0] = 1; break; }
           __builtin_amdgcn_s_sleep(8);
         }
         __threadfence();  // what the owner wrote before it sent the mail is read from memory
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
             unsigned int id = 0u, spins = 0u;
             // (the helper bumps the count before it writes its id)
             while ((id = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == 0u) {
-              if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
+              if (++spins > wa.wait_rounds) { team_failed = 1; wa.team_err[0] = 1; break; }
               __builtin_amdgcn_s_sleep(1);
             }
             if (id == 0u) break;
@@ -543,7 +543,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
           const unsigned int target = pool ? owner_target : (unsigned int)team * (unsigned int)(stage - wa.first + 1);
           unsigned int spins = 0;
           while (__hip_atomic_load(&wa.team_count[unit], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < target) {
-            if (++spins > VF_TEAM_SPINS) { team_failed = 1; wa.team_err[0] = 1; break; }
+            if (++spins > wa.wait_rounds) { team_failed = 1; wa.team_err[0] = 1; break; }
             __builtin_amdgcn_s_sleep(2);
           }
           __threadfence();
@@ -694,6 +694,7 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
   wa.tstride = tstride;
   wa.team_count = c->d_team;
   wa.team_err = reinterpret_cast<int32_t *>(c->d_team) + c->B;
+  wa.wait_rounds = c->wait_rounds;
   wa.pool = c->d_team + off_pool;
   wa.pool_q = c->d_team + off_q;
   wa.mailbox = reinterpret_cast<unsigned long long *>(c->d_team + off_mail);

@@ -461,3 +461,39 @@ def test_whole_schedule_launch_with_helpers_from_the_start(vf, ovf):
             for b in (0, B - 1):
                 compare_schedule(ovf, pipes[b], sp, model, w, whole[1][b], whole[2][b], whole[0][b], TOL[1])
     vf.vf_destroy(ctx)
+
+
+@pytest.mark.parametrize("B", [16, 200])
+def test_wait_between_workgroups_that_runs_out_is_reported(vf, ovf, B):
+    """Workgroups that share a problem wait for each other with a bound (B = 16: a fixed team
+    per problem meets once per layer; B = 200: helpers wait for mail, owners for the helpers
+    they sent for).  With the bound set to zero from the host every wait that is not satisfied
+    at once gives up: the launch must still end, the next call must report VF_ESTATE, and with
+    the default bound the same context must give the schedules of the per-layer launches."""
+    import torch
+    pipes = I.resnet18_batch(B, seed=40)
+    sp = I.make_space([1, 2, 4], [1, 4], [4, 8], [(0, 1, 2), (2, 1, 0)], 2, 2,
+                      [I.ROOT, I.L1, I.L2, I.INLINE], 2, 256)
+    dims = [256, 512, 512, 1]
+    w = I.mlp_weights(dims, 2, bias_std=0.1)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    S = pipes.shape[1]
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipes); vf.vf_set_model(ctx, model, w)
+    vf.vf_set_wait_limit(ctx, 0)
+    vf.vf_greedy_schedule(ctx)
+    torch.cuda.synchronize()
+    with pytest.raises(vf.VfError) as e:
+        vf.vf_greedy_schedule(ctx, first=S)
+    assert e.value.code == vf.VF_ESTATE
+    vf.vf_set_wait_limit(ctx, 1 << 22)
+    vf.vf_reset_state(ctx)
+    whole = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
+    vf.vf_reset_state(ctx)
+    for i in range(S):
+        vf.vf_argmin_step(ctx, i, True)
+    steps = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=S)]
+    for a, b in zip(whole, steps):
+        assert np.array_equal(a, b)
+    assert (whole[1] >= 0).all()
+    vf.vf_destroy(ctx)
