@@ -3,7 +3,7 @@
 // step of the greedy scan by itself - decision context, the list of valid candidates,
 // their features, V(s) with the bf16 MLP, the running minimum, the commit "s_i := s" -
 // so that a schedule costs one launch and nothing but the tables and the id list touches
-// memory.  Pays when there are about as many problems as compute units.
+// memory.  Used from 16 problems on (fewer do not fill the chip even with teams).
 //
 // The MLP is the same contraction as in the per-layer scorer: weights are the MFMA A
 // operand and stream from L2 through a ring of registers, activations are the B operand
@@ -67,11 +67,11 @@ constexpr int VF_MAX_HELPERS = 3;
 constexpr int VF_POOL_SLOTS = 1024;       // more than the workgroups of a launch
 constexpr int VF_TILES_PER_MEMBER = 4;    // a helper is sent for when every member gets at least this many tiles
 
+// What a mailbox holds: never zero (zero = empty).
 __device__ __forceinline__ unsigned long long mail_pack(int unit, int stage, int team, int member) {
   return 1ull << 63 | (unsigned long long)unit << 40 | (unsigned long long)stage << 16 |
          (unsigned long long)team << 8 | (unsigned long long)member;
 }
-
 
 // NC candidates per tile, RT row tiles per wave (hidden width 256 * RT), PD k-steps of
 // weight fragments in flight per wave.  stat: nullable, [0] += candidates pushed through
