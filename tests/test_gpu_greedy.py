@@ -426,12 +426,13 @@ def test_whole_schedule_launch_other_depths(vf, ovf, dims):
     vf.vf_destroy(ctx)
 
 
-def test_whole_schedule_launch_with_helpers_from_the_start(vf, ovf):
+@pytest.mark.parametrize("B", [200, 300])
+def test_whole_schedule_launch_with_helpers(vf, ovf, B):
     """200 problems on 256 compute units: the workgroups without a problem of their own help
-    the others from the first layers on (and the ones that finish early later); a problem that
-    ends early and exploration noise included.  Same tables as stepping layer by layer; the
-    counters say that only listed candidates were scored; two problems against the checker."""
-    B = 200
+    the others from the first layers on (and the ones that finish early later); 300 problems:
+    some workgroups own two problems and the others help them when they are done.  A problem
+    that ends early and exploration noise included.  Same tables as stepping layer by layer;
+    the counters say that only listed candidates were scored; two problems against the checker."""
     pipes = I.resnet18_batch(B, seed=33)
     pipes[5, 2, 3] = 2
     sp = I.make_space([1, 2, 4], [1, 4], [4, 8], [(0, 1, 2), (2, 1, 0)], 2, 2,
