@@ -401,6 +401,12 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
             uint4 bcur[CT];
 #pragma unroll
             for (int c = 0; c < CT; ++c) bcur[c] = *bfrag(c, 0);
+            // Nothing but this loop's own loads may be in flight when it starts: with a store to
+            // scratch or a scalar load still counted, the compiler can no longer tell the order
+            // in which the counters come down and waits for every load at the top of each round
+            // instead of for the oldest one.  (vmcnt 0, lgkmcnt 0; the ring's loads were issued
+            // a tile ago.)
+            __builtin_amdgcn_s_waitcnt(0x0070);
             // the matrix loop goes first on its SIMD: the other wave's vector work fills the gaps
             __builtin_amdgcn_s_setprio(2);
             for (int s0 = 0; s0 < ksteps; s0 += PD) {
