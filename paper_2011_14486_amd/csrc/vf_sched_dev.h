@@ -23,6 +23,17 @@ __device__ __forceinline__ uint32_t ratio16(uint32_t num, uint32_t den) {
 }
 __device__ __forceinline__ uint32_t umin(uint32_t a, uint32_t b) { return a < b ? a : b; }
 
+// r / n for a divisor n >= 1 with rcp = 1.0f / n, a handful of instructions instead of an
+// integer division: below 2^24 the dividend is a float, the product is less than one away
+// from the quotient, and one compare either way puts it right.
+__device__ __forceinline__ uint32_t div_small(uint32_t r, uint32_t n, float rcp) {
+  if (r >= (1u << 24)) return r / n;
+  uint32_t q = (uint32_t)((float)r * rcp);
+  if (q * n > r) --q;
+  else if ((q + 1u) * n <= r) ++q;
+  return q;
+}
+
 struct Tables {
   const int32_t *space, *stages, *intr, *suffix;
   int32_t *states, *cf, *prefix, *cids, *alive, *err;
@@ -160,6 +171,22 @@ __device__ __forceinline__ Digits digits_of(const vf_space &sp, uint32_t cid) {
   g.isat = r;
   return g;
 }
+// The same digits through div_small (for a single thread that has a chain of them to do).
+__device__ __forceinline__ Digits digits_small(const vf_space &sp, uint32_t cid) {
+  const uint32_t radix[7] = {(uint32_t)sp.nf[0], (uint32_t)sp.nf[1], (uint32_t)sp.nf[2], (uint32_t)sp.nperm,
+                             (uint32_t)sp.nvec, (uint32_t)sp.npar, (uint32_t)sp.ncat};
+  uint32_t dig[7], r = cid;
+#pragma unroll
+  for (int k = 0; k < 7; ++k) {
+    const uint32_t q = div_small(r, radix[k], 1.0f / (float)radix[k]);
+    dig[k] = r - q * radix[k];
+    r = q;
+  }
+  Digits g;
+  g.ix = dig[0]; g.iy = dig[1]; g.ic = dig[2]; g.ip = dig[3]; g.vec = dig[4]; g.par = dig[5]; g.icat = dig[6];
+  g.isat = r;
+  return g;
+}
 __device__ __forceinline__ uint32_t id_of(const vf_space &sp, const Digits &g) {
   uint32_t r = g.isat;
   r = r * (uint32_t)sp.ncat + g.icat;
@@ -189,6 +216,7 @@ struct EvalTabs {
   uint32_t par_eff[3][3][8];  // ratio16(O, cdiv(O, ncores) * ncores)
   uint32_t lanes[3][8];       // min(fac[dim][k], vlen)
   uint32_t vec_eff[3][8];     // ratio16(fac, cdiv(fac, vlen) * vlen)
+  uint32_t par_eff1;          // the parallel efficiency of a single task
 };
 [[maybe_unused]] __device__ void fill_evaltabs(EvalTabs &tb, const Dec &d, const vf_space &sp) {
   for (int i = threadIdx.x; i < 72; i += blockDim.x) {
@@ -201,6 +229,7 @@ struct EvalTabs {
       tb.lanes[dd][k] = umin(f, (uint32_t)sp.vlen);
       tb.vec_eff[dd][k] = ratio16(f, smul(cdiv(f, (uint32_t)sp.vlen), (uint32_t)sp.vlen));
     }
+    if (i == 0) tb.par_eff1 = ratio16(1u, smul(cdiv(1u, (uint32_t)sp.ncores), (uint32_t)sp.ncores));
   }
 }
 
@@ -267,7 +296,8 @@ __device__ __forceinline__ bool eval_digits(const Dec &d, const vf_space &sp, co
   const uint32_t Oout = p0 == 0 ? O[0] : (p0 == 1 ? O[1] : O[2]);
   const uint32_t tasks = par ? Oout : 1u;
   core[30] = tasks;
-  if (looked_up && par) core[31] = tb->par_eff[cat][p0][idx[p0]];
+  if (tb != nullptr && !par) core[31] = tb->par_eff1;
+  else if (looked_up) core[31] = tb->par_eff[cat][p0][idx[p0]];
   else core[31] = ratio16(tasks, smul(cdiv(tasks, (uint32_t)sp.ncores), (uint32_t)sp.ncores));
   core[32] = cat; core[33] = hoist;
   core[34] = E[0]; core[35] = E[1]; core[36] = E[2];
@@ -423,23 +453,30 @@ static_assert(sizeof(DecPack) == VF_DECPACK_DWORDS * 4, "DecPack size");
 // the decision for `stage` - its derived loop structure, its 64 core features, the
 // running sums - or, when there is no valid winner, ends that problem's schedule.
 // d / sp are the decision context of (b, stage).
+// tb (nullable): the decision's quotient tables, for a caller that has them at hand.
 [[maybe_unused]] __device__ __forceinline__ void commit_winner(const Tables &t, const Dec &d, const vf_space &sp, int b, int stage,
-                                               int32_t c, float v, uint32_t M, bool forced) {
+                                               int32_t c, float v, uint32_t M, bool forced, const EvalTabs *tb = nullptr) {
   const int S = t.S;
   const size_t row = (size_t)b * S + stage;
   int32_t *pre = t.prefix + ((size_t)b * (S + 1) + stage) * 2;
+  // (read before anything is stored: a load behind the stores would wait for all of them)
+  const int32_t pre_m = pre[0], pre_b = pre[1];
   int32_t core[64];
   bool ok = false;
   if (c >= 0 && (uint32_t)c < M) {
-    uint32_t dec;
-    ok = eval_candidate<true>(d, sp, (uint32_t)c, dec, core);
+    if (tb != nullptr) {
+      ok = eval_digits<true>(d, sp, digits_small(sp, (uint32_t)c), tb, core);
+    } else {
+      uint32_t dec;
+      ok = eval_candidate<true>(d, sp, (uint32_t)c, dec, core);
+    }
   }
   if (!ok) {
     if (forced) t.err[0] = 1;
     t.alive[b] = 0;
     t.cids[row] = -1;
     t.vals[row] = __builtin_inff();
-    pre[2] = pre[0]; pre[3] = pre[1];
+    pre[2] = pre_m; pre[3] = pre_b;
   } else {
 #pragma unroll
     for (int k = 0; k < 64; ++k) t.cf[row * 64 + k] = core[k];
@@ -452,17 +489,25 @@ static_assert(sizeof(DecPack) == VF_DECPACK_DWORDS * 4, "DecPack size");
     st[15] = 1;
     t.cids[row] = c;
     t.vals[row] = v;
-    pre[2] = sadd((uint32_t)pre[0], (uint32_t)core[40]);
-    pre[3] = sadd((uint32_t)pre[1], (uint32_t)core[50]);
+    pre[2] = sadd((uint32_t)pre_m, (uint32_t)core[40]);
+    pre[3] = sadd((uint32_t)pre_b, (uint32_t)core[50]);
   }
 }
 
 // The same as a real call, for kernels whose main loop should not carry the registers of
-// an inlined copy.
-[[maybe_unused]] __device__ __attribute__((noinline)) void commit_winner_call(const Tables &t, const Dec &d,
-                                                                            const vf_space &sp, int b, int stage,
-                                                                            int32_t c, float v, uint32_t M) {
-  commit_winner(t, d, sp, b, stage, c, v, M, false);
+// an inlined copy.  The table pointers that a commit touches come one by one, so that they
+// travel in registers: a structure would go through the stack (scratch memory, a round trip
+// to memory on either side of the call), a reference to it would be read again behind every
+// store.
+[[maybe_unused]] __device__ __attribute__((noinline)) void commit_winner_call(
+    int32_t *states, int32_t *cf, int32_t *prefix, int32_t *cids, float *vals, int32_t *alive, int S, const Dec &d,
+    const vf_space &sp, const EvalTabs &tb, int b, int stage, int32_t c, float v, uint32_t M) {
+  Tables t;
+  t.space = t.stages = t.intr = t.suffix = nullptr;
+  t.states = states; t.cf = cf; t.prefix = prefix; t.cids = cids; t.alive = alive; t.err = nullptr;
+  t.vals = vals;
+  t.S = S;
+  commit_winner(t, d, sp, b, stage, c, v, M, false, &tb);
 }
 
 // Builds the pack for (problem b, stage) in LDS and copies it to out[b].

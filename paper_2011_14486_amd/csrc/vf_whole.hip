@@ -159,9 +159,16 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       unit = job_unit; stage = job_stage; team = job_team; member = job_member;
     }
     uint32_t *const idlist = wa.list + (size_t)unit * wa.Mpad;
-    fill_decpack(pk, wa.t, unit, stage);
-    fill_evaltabs(tabs, pk.d, pk.sp);
+    build_dec(pk.d, pk.sp, wa.t, unit, stage);
     na.stage = stage;
+    // three small jobs side by side, on different waves: the quotient tables (waves 0, 1), the
+    // neighbour rows as the first layer wants them (waves 2, 3), the split factors that fit
+    // (wave 4)
+    fill_evaltabs(tabs, pk.d, pk.sp);
+    if (tid >= 128 && tid < 224) {
+      const int q = tid - 128;
+      pk.nbh[q] = pack_bf16(plog2_dev(pk.d.nb[2 * q]), plog2_dev(pk.d.nb[2 * q + 1]));
+    }
     // Ordered list of the decision's valid ids, written down directly from the validity
     // rules: per (compute_at, store_at) digit pair that is open - the level is offered and
     // the hoist does not exceed it - the valid ids are the products of the split factors
@@ -172,88 +179,51 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     __shared__ int ncand, g_npairs;
     __shared__ int g_pos[13], g_cat[12], g_dec[12];
     __shared__ int g_nok[3][3], g_ok[3][3][8];
-    if (tid < 9) {
-      const int lvl = tid / 3, dd = tid % 3;
+    __shared__ float g_rcp[3][3];  // 1 / g_nok, for div_small
+    if (tid >= 256 && tid < 265) {
+      const int lvl = (tid - 256) / 3, dd = (tid - 256) % 3;
       int cnt = 0;
       for (int k = 0; k < pk.sp.nf[dd]; ++k)
         if ((uint32_t)pk.sp.fac[dd][k] <= pk.d.E[lvl][dd]) g_ok[lvl][dd][cnt++] = k;
       g_nok[lvl][dd] = cnt;
+      g_rcp[lvl][dd] = 1.0f / (float)(cnt > 0 ? cnt : 1);
     }
     __syncthreads();
     const int rest_n = pk.sp.nperm * pk.sp.nvec * pk.sp.npar;
-    if (tid == 0) {
-      int np = 0, pos = 0;
-      for (int isat = 0; isat < pk.sp.nsat; ++isat)
-        for (int icat = 0; icat < pk.sp.ncat; ++icat) {
-          const int cat = pk.sp.cat[icat];
-          if (pk.d.lvl_ok[cat] == 0) continue;
-          int cnt = 0;
+    const float rcp_perm = 1.0f / (float)pk.sp.nperm, rcp_vec = 1.0f / (float)pk.sp.nvec;
+    if (w == 0) {
+      // lane j looks at pair j = (store_at digit, compute_at digit); the open pairs are then
+      // numbered and given their first list position in order
+      const int npairs_all = pk.sp.nsat * pk.sp.ncat;
+      int cnt = 0, cat = 0, dec = 0;
+      if (lane < npairs_all && lane < 12) {
+        const int isat = lane / pk.sp.ncat, icat = lane % pk.sp.ncat;
+        cat = pk.sp.cat[icat];
+        dec = (int)((uint32_t)icat << 24 | (uint32_t)isat << 28);
+        if (pk.d.lvl_ok[cat] != 0) {
           if (cat == VF_INLINE) cnt = isat == 0 ? 1 : 0;
           else if (isat <= cat) cnt = g_nok[cat][0] * g_nok[cat][1] * g_nok[cat][2] * rest_n;
-          if (cnt == 0) continue;
+        }
+      }
+      int np = 0, pos = 0;
+#pragma unroll
+      for (int j = 0; j < 12; ++j) {
+        const int cj = __builtin_amdgcn_readlane(cnt, j);
+        if (cj == 0) continue;
+        const int catj = __builtin_amdgcn_readlane(cat, j), decj = __builtin_amdgcn_readlane(dec, j);
+        if (lane == 0) {
           g_pos[np] = pos;
-          g_cat[np] = cat;
-          g_dec[np] = (int)((uint32_t)icat << 24 | (uint32_t)isat << 28);
-          pos += cnt;
-          ++np;
+          g_cat[np] = catj;
+          g_dec[np] = decj;
         }
-      g_pos[np] = pos;
-      g_npairs = np;
-      ncand = pos;
-    }
-    __syncthreads();
-    for (int k = tid; k < ncand; k += 512) {
-      int q = 0;
-      while (q + 1 < g_npairs && k >= g_pos[q + 1]) ++q;
-      const int cat = g_cat[q];
-      uint32_t dec = (uint32_t)g_dec[q];
-      if (cat != VF_INLINE) {
-        int r = k - g_pos[q];
-        const int nx = g_nok[cat][0], ny = g_nok[cat][1], nc = g_nok[cat][2];
-        const int jx = r % nx; r /= nx;
-        const int jy = r % ny; r /= ny;
-        const int jc = r % nc; r /= nc;
-        const int ix = g_ok[cat][0][jx], iy = g_ok[cat][1][jy], ic = g_ok[cat][2][jc];
-        const int ip = r % pk.sp.nperm; r /= pk.sp.nperm;
-        const int vec = r % pk.sp.nvec, par = r / pk.sp.nvec;
-        dec |= (uint32_t)ix | (uint32_t)iy << 4 | (uint32_t)ic << 8 | (uint32_t)ip << 12 | (uint32_t)vec << 16 |
-               (uint32_t)par << 20;
+        pos += cj;
+        ++np;
       }
-      idlist[k] = dec;
-    }
-    if (wa.helpers && !helping) {
-      // owner: with enough tiles, take helpers out of the pool and send them this layer
-      if (tid == 0) {
-        int n = 0;
-        int want = (ncand + NC - 1) / NC / VF_TILES_PER_MEMBER - 1;
-        if (want > VF_MAX_HELPERS) want = VF_MAX_HELPERS;
-        for (int attempt = 0; attempt < 4 && want > 0 && n == 0; ++attempt) {
-          const unsigned int taken = __hip_atomic_load(&wa.pool[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          const int avail = (int)(__hip_atomic_load(&wa.pool[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - taken);
-          if (avail <= 0) break;
-          const int take = avail < want ? avail : want;
-          if (atomicCAS(&wa.pool[0], taken, taken + (unsigned int)take) != taken) continue;  // somebody else took some
-          for (int i = 0; i < take; ++i) {
-            unsigned int *const q = &wa.pool_q[(taken + (unsigned int)i) % VF_POOL_SLOTS];
-            unsigned int id = 0u, spins = 0u;
-            // (the helper bumps the count before it writes its id)
-            while ((id = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == 0u) {
-              if (++spins > wa.wait_rounds) { team_failed = 1; wa.team_err[0] = 1; break; }
-              __builtin_amdgcn_s_sleep(1);
-            }
-            if (id == 0u) break;
-            __hip_atomic_store(q, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&wa.mailbox[id - 1u], mail_pack(unit, stage, take + 1, i + 1), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
-          }
-          n = take;
-        }
-        job_team = 1 + n;
-        owner_target += (unsigned int)n;
+      if (lane == 0) {
+        g_pos[np] = pos;
+        g_npairs = np;
+        ncand = pos;
       }
-      __syncthreads();
-      if (team_failed) return;
-      team = job_team;
     }
     if (fold) {
       // the first layer's product with the 192 rows that all candidates of the decision
@@ -291,7 +261,66 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
         }
       }
     }
-    __syncthreads();  // the id list (written by this workgroup) and the bias are complete
+    __syncthreads();  // the pairs are numbered, the bias is complete
+    // (the pairs' first positions into registers: the pair of an entry is then found without
+    // a chain of dependent reads)
+    int pos_r[12];
+#pragma unroll
+    for (int j = 0; j < 12; ++j) pos_r[j] = j < g_npairs ? g_pos[j] : 0x7fffffff;
+    for (int k = tid; k < ncand; k += 512) {
+      int q = 0;
+#pragma unroll
+      for (int j = 1; j < 12; ++j) q += k >= pos_r[j] ? 1 : 0;
+      const int cat = g_cat[q];
+      uint32_t dec = (uint32_t)g_dec[q];
+      if (cat != VF_INLINE) {
+        uint32_t r = (uint32_t)(k - g_pos[q]), nxt;
+        const uint32_t nx = g_nok[cat][0], ny = g_nok[cat][1], nc = g_nok[cat][2];
+        nxt = div_small(r, nx, g_rcp[cat][0]); const uint32_t jx = r - nxt * nx; r = nxt;
+        nxt = div_small(r, ny, g_rcp[cat][1]); const uint32_t jy = r - nxt * ny; r = nxt;
+        nxt = div_small(r, nc, g_rcp[cat][2]); const uint32_t jc = r - nxt * nc; r = nxt;
+        const int ix = g_ok[cat][0][jx], iy = g_ok[cat][1][jy], ic = g_ok[cat][2][jc];
+        nxt = div_small(r, (uint32_t)pk.sp.nperm, rcp_perm); const uint32_t ip = r - nxt * (uint32_t)pk.sp.nperm; r = nxt;
+        const uint32_t par = div_small(r, (uint32_t)pk.sp.nvec, rcp_vec), vec = r - par * (uint32_t)pk.sp.nvec;
+        dec |= (uint32_t)ix | (uint32_t)iy << 4 | (uint32_t)ic << 8 | (uint32_t)ip << 12 | (uint32_t)vec << 16 |
+               (uint32_t)par << 20;
+      }
+      idlist[k] = dec;
+    }
+    if (wa.helpers && !helping) {
+      // owner: with enough tiles, take helpers out of the pool and send them this layer
+      if (tid == 0) {
+        int n = 0;
+        int want = (ncand + NC - 1) / NC / VF_TILES_PER_MEMBER - 1;
+        if (want > VF_MAX_HELPERS) want = VF_MAX_HELPERS;
+        for (int attempt = 0; attempt < 4 && want > 0 && n == 0; ++attempt) {
+          const unsigned int taken = __hip_atomic_load(&wa.pool[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          const int avail = (int)(__hip_atomic_load(&wa.pool[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - taken);
+          if (avail <= 0) break;
+          const int take = avail < want ? avail : want;
+          if (atomicCAS(&wa.pool[0], taken, taken + (unsigned int)take) != taken) continue;  // somebody else took some
+          for (int i = 0; i < take; ++i) {
+            unsigned int *const q = &wa.pool_q[(taken + (unsigned int)i) % VF_POOL_SLOTS];
+            unsigned int id = 0u, spins = 0u;
+            // (the helper bumps the count before it writes its id)
+            while ((id = __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) == 0u) {
+              if (++spins > wa.wait_rounds) { team_failed = 1; wa.team_err[0] = 1; break; }
+              __builtin_amdgcn_s_sleep(1);
+            }
+            if (id == 0u) break;
+            __hip_atomic_store(q, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&wa.mailbox[id - 1u], mail_pack(unit, stage, take + 1, i + 1), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+          }
+          n = take;
+        }
+        job_team = 1 + n;
+        owner_target += (unsigned int)n;
+      }
+    }
+    __syncthreads();  // the id list (written by this workgroup) is complete
+    if (team_failed) return;
+    if (wa.helpers && !helping) team = job_team;
     const int ncands = ncand;
     const int ntiles = (ncands + NC - 1) / NC;
 
@@ -579,7 +608,9 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     }
     // s_i := the winner; the tables it updates are read back by this same workgroup
     // when it builds the next stage's context
-    if (tid == 0) commit_winner_call(wa.t, pk.d, pk.sp, unit, stage, run_c, run_v, (uint32_t)M);
+    if (tid == 0)
+      commit_winner_call(wa.t.states, wa.t.cf, wa.t.prefix, wa.t.cids, wa.t.vals, wa.t.alive, wa.t.S, pk.d, pk.sp, tabs, unit,
+                         stage, run_c, run_v, (uint32_t)M);
     __threadfence();
     __syncthreads();
     // what comes next: an owner goes on to the next layer, then to its next problem; a helper
