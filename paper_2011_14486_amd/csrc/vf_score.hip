@@ -625,31 +625,32 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     uint4 bcur[CT];
 #pragma unroll
     for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ks);
+    // Nothing but this loop's own loads may be in flight when it starts: with a store to
+    // scratch or a scalar load still counted, the compiler can no longer tell the order in
+    // which the counters come down and waits for every load at the top of each round instead
+    // of for the oldest one.  (vmcnt 0, lgkmcnt 0; the ring's loads were issued a tile ago.)
+    __builtin_amdgcn_s_waitcnt(0x0070);
     for (int s0 = 0; s0 < ksteps; s0 += PD) {
       // the last PD steps of a tile prefetch the first PD steps of the next one
       if (l == NH - 1 && s0 + PD >= ksteps) wp = wbase;
 #pragma unroll
       for (int j = 0; j < PD; ++j) {
-        uint4 a[RT], bnext[CT];
+        // One memory instruction behind each product: behind the first CT products the
+        // activation fragments of the next k-step (one step past the end stays inside the
+        // tile's LDS), behind the last product that reads a weight fragment its refill, in
+        // place, PD k-steps ahead of its next use - so only the oldest slot is ever waited for
+        uint4 bnext[CT];
 #pragma unroll
-        for (int r = 0; r < RT; ++r) {
-          a[r] = ring[j][r];
-          ring[j][r] = wp[r * 64];
+        for (int i = 0; i < RT * CT; ++i) {
+          const int r = i / CT, c = i % CT;
+          acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8, ring[j][r]), __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
+          if (i < CT) bnext[i] = *reinterpret_cast<const uint4 *>(brow + (size_t)i * 32 * ks + (s0 + j + 1) * 16);
+          if (i >= CT && c == 0) ring[j][r - 1] = wp[(r - 1) * 64];
+          if (i == RT * CT - 1) ring[j][RT - 1] = wp[(RT - 1) * 64];
+          __builtin_amdgcn_sched_barrier(0);
         }
         wp += RT * 64;
-        // keep the prefetch where it is: the scheduler would otherwise sink these loads
-        // towards their use, PD k-steps later, and lose the latency cover
-        __builtin_amdgcn_sched_barrier(0);
-        // fragments of the next k-step (one step past the end stays inside the tile's LDS)
-#pragma unroll
-        for (int c = 0; c < CT; ++c)
-          bnext[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ks + (s0 + j + 1) * 16);
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-#pragma unroll
-          for (int c = 0; c < CT; ++c)
-            acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                __builtin_bit_cast(bf16x8, a[r]), __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
 #pragma unroll
         for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
       }
