@@ -369,23 +369,21 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
         if (s0 + PD >= nsteps) wp = whp;  // the next step's first fragments (always an h step)
 #pragma unroll
         for (int j = 0; j < PD; ++j) {
-          uint4 a[4], bnext[CT];
+          // one memory instruction behind each product: the activation fragments of the next
+          // k-step (one k-step past the end stays inside the row's padding or the next row),
+          // then the refill, in place, of each weight fragment behind its last use
+          uint4 bnext[CT];
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            a[g] = ring[j][g];
-            ring[j][g] = wp[g * 64];
+          for (int i = 0; i < 4 * CT; ++i) {
+            const int g = i / CT, c = i % CT;
+            acc[g][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                __builtin_bit_cast(bf16x8, ring[j][g]), __builtin_bit_cast(bf16x8, bcur[c]), acc[g][c], 0, 0, 0);
+            if (i < CT) bnext[i] = *reinterpret_cast<const uint4 *>(brow + (size_t)i * 32 * ld + (s0 + j + 1) * 16);
+            if (i >= CT && c == 0) ring[j][g - 1] = wp[(g - 1) * 64];
+            if (i == 4 * CT - 1) ring[j][3] = wp[3 * 64];
+            __builtin_amdgcn_sched_barrier(0);
           }
           wp += 4 * 64;
-          // one k-step past the end stays inside the row's padding or the next row
-#pragma unroll
-          for (int c = 0; c < CT; ++c)
-            bnext[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ld + (s0 + j + 1) * 16);
-#pragma unroll
-          for (int g = 0; g < 4; ++g)
-#pragma unroll
-            for (int c = 0; c < CT; ++c)
-              acc[g][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                  __builtin_bit_cast(bf16x8, a[g]), __builtin_bit_cast(bf16x8, bcur[c]), acc[g][c], 0, 0, 0);
 #pragma unroll
           for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
         }
