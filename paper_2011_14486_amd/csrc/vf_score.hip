@@ -1268,7 +1268,13 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
   md.w_pack = c->pm.w_pack; md.aux = c->pm.aux; md.wl_off = c->pm.aux_off[7];
   const int ks = maxw + 8;
   const bool wide = maxw > 512;
-  const int NC = wide ? 64 : 128;
+  int ncu = 256;
+  (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
+  // A decision of a few pipelines has fewer tiles of 128 candidates than half the compute
+  // units: then tiles of 64 spread the same work over twice as many of them, and the
+  // contraction of a tile - most of the time a layer takes - is half as long.
+  const bool narrow = !wide && gen_stage >= 0 && c->pm.fast_rt && ((M + 127) / 128) * nprob * 2 <= ncu;
+  const int NC = (wide || narrow) ? 64 : 128;
   const int nparts = (int)((M + NC - 1) / NC);
   int rc = vfk_ensure_parts(c, (size_t)(nparts > 0 ? nparts : 1) * nprob);
   if (rc != VF_OK) return rc;
@@ -1280,8 +1286,6 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     size_t smem_fast = smem + (size_t)fd.naux * 4;
     if (fd.w_full) smem_fast = smem + (size_t)((fd.naux + 3) & ~3) * 4 + (size_t)m.dims[1] * 4;
     // persistent: at most one workgroup per CU, each walking its share of the tiles
-    int ncu = 256;
-    (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
     const int64_t tiles = (int64_t)nparts * nprob;
     dim3 grid((unsigned)(tiles < ncu ? tiles : ncu));
     void (*kern)(const int32_t *, int64_t, int64_t, int64_t, int, vf_fast_dev, int, float *, int64_t, float *, int32_t *, int,
@@ -1292,7 +1296,7 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     if (gen_stage >= 0) {
       int rc2 = vfk_prepare(c, gen_stage);
       if (rc2 != VF_OK) return rc2;
-      kern = wide ? k_mlp_fast<64, 4, 2, true> : k_mlp_fast<128, 2, 4, true>;
+      kern = wide ? k_mlp_fast<64, 4, 2, true> : narrow ? k_mlp_fast<64, 2, 4, true> : k_mlp_fast<128, 2, 4, true>;
     } else {
       kern = wide ? k_mlp_fast<64, 4, 2, false> : k_mlp_fast<128, 2, 4, false>;
     }
