@@ -141,6 +141,10 @@ __global__ __launch_bounds__(256) void k_commit(Tables t, int stage, int nparts,
   } else {
     build_dec(d, sp, t, b, stage);
   }
+  // the decision's quotient tables, so that the one thread that evaluates the winner has no
+  // chain of integer divisions to work through (built next to the reduction, by other waves)
+  __shared__ EvalTabs tabs;
+  fill_evaltabs(tabs, d, sp, 64);
   float v = __builtin_inff();
   int32_t c = -1;
   if (forced) {
@@ -158,10 +162,11 @@ __global__ __launch_bounds__(256) void k_commit(Tables t, int stage, int nparts,
       if (oc >= 0 && (ov < v || (ov == v && (c < 0 || oc < c)))) { v = ov; c = oc; }
     }
   }
+  __syncthreads();  // the tables are complete
   if (lane == 0) {
     if (best_cid) best_cid[b] = c;
     if (best_val) best_val[b] = v;
-    if (commit) commit_winner(t, d, sp, b, stage, c, v, M, forced != nullptr);
+    if (commit) commit_winner(t, d, sp, b, stage, c, v, M, forced != nullptr, &tabs);
   }
   // the next stage's decision context, for the fused scorer
   if (commit && decpack_next && stage + 1 < S) {

@@ -218,8 +218,10 @@ struct EvalTabs {
   uint32_t vec_eff[3][8];     // ratio16(fac, cdiv(fac, vlen) * vlen)
   uint32_t par_eff1;          // the parallel efficiency of a single task
 };
-[[maybe_unused]] __device__ void fill_evaltabs(EvalTabs &tb, const Dec &d, const vf_space &sp) {
-  for (int i = threadIdx.x; i < 72; i += blockDim.x) {
+// first: the thread that takes entry 0 (the others follow it), for a caller whose first
+// threads are busy with something else.
+[[maybe_unused]] __device__ void fill_evaltabs(EvalTabs &tb, const Dec &d, const vf_space &sp, int first = 0) {
+  for (int i = (int)threadIdx.x - first; i >= 0 && i < 72; i += blockDim.x) {
     const int lvl = i / 24, dd = (i / 8) % 3, k = i % 8;
     const uint32_t f = k < sp.nf[dd] ? (uint32_t)sp.fac[dd][k] : 1u;
     const uint32_t o = cdiv(d.E[lvl][dd], f);
