@@ -182,7 +182,7 @@ int vf_argmin_step(vf_ctx *ctx, int stage, int commit, int32_t *best_cid_dev, fl
  * out_states_dev[batch][S] the committed states s_1..s_n so far (all stages),
  * out_cids_dev[batch][S] the chosen candidate ids, out_values_dev[batch][S] their
  * values; entries of stages not scheduled yet are zero states, -1 and +inf.
- * With 16 or more problems (and a model whose tile fits the LDS) the layers run inside one
+ * With 24 or more problems (and a model whose tile fits the LDS) the layers run inside one
  * launch: with fewer problems than half the compute units several workgroups share a problem
  * from the start, with more a workgroup that has finished its own problems helps with the
  * ones still running; workgroups that share a problem meet once per layer with a bounded

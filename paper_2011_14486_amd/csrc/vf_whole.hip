@@ -3,7 +3,7 @@
 // step of the greedy scan by itself - decision context, the list of valid candidates,
 // their features, V(s) with the bf16 MLP, the running minimum, the commit "s_i := s" -
 // so that a schedule costs one launch and nothing but the tables and the id list touches
-// memory.  Used from 16 problems on (fewer do not fill the chip even with teams).
+// memory.  Used from 24 problems on (below that the two launches per layer are faster).
 //
 // The MLP is the same contraction as in the per-layer scorer: weights are the MFMA A
 // operand and stream from L2 through a ring of registers, activations are the B operand
@@ -650,7 +650,7 @@ static whole_kernel whole_launch_shape(const vf_ctx *c, vf_fast_dev *fd, int *ks
 // instead of 5.6, 300: 7.0 instead of 8.5); with fewer problems a fixed team per problem, as
 // large as the compute units and the tiles of a decision allow, at most 16 (128 problems x
 // 2: 3.1 instead of 4.9 ms, 64 x 4: 2.1 instead of 3.4, 32 x 8: 1.7 instead of 2.2; helpers
-// instead of fixed teams are slower there: 64 problems 2.9 ms); below 16 problems the
+// instead of fixed teams are slower there: 64 problems 2.9 ms); below 24 problems the
 // meetings cost what the launches did.
 int vfk_whole_team(const vf_ctx *c) {
   if (!vfk_can_fuse_step(c)) return 0;
@@ -667,7 +667,7 @@ int vfk_whole_team(const vf_ctx *c) {
   int ncu = 256;
   (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
   if (c->B > ncu / 2) return 1;
-  if (c->B < 16) return 0;  // a handful of problems: the per-layer launches are as fast
+  if (c->B < 24) return 0;  // a handful of problems: the per-layer launches are faster (16: 1.3 against 1.6 ms)
   int maxw = 0;
   for (int l = 0; l < c->model.n_layers; ++l) if (c->model.dims[l] > maxw) maxw = c->model.dims[l];
   const int NC = maxw > 512 ? 64 : 128;

@@ -362,9 +362,9 @@ def test_whole_schedule_candidate_lists_against_the_checker(vf, ovf, seed):
     vf.vf_destroy(ctx)
 
 
-@pytest.mark.parametrize("B", [16, 48, 100])
+@pytest.mark.parametrize("B", [24, 48, 100])
 def test_team_of_workgroups_per_problem(vf, ovf, B):
-    """Between 16 problems and half the compute units vf_greedy_schedule gives every problem a
+    """Between 24 problems and half the compute units vf_greedy_schedule gives every problem a
     team of workgroups that meet once per layer: same tables as the per-layer launches, with
     noise, from a prefix, with a problem that ends early; some problems against the checker."""
     pipes = I.resnet18_batch(B, seed=9)
@@ -464,9 +464,9 @@ def test_whole_schedule_launch_with_helpers(vf, ovf, B):
     vf.vf_destroy(ctx)
 
 
-@pytest.mark.parametrize("B", [16, 200])
+@pytest.mark.parametrize("B", [24, 200])
 def test_wait_between_workgroups_that_runs_out_is_reported(vf, ovf, B):
-    """Workgroups that share a problem wait for each other with a bound (B = 16: a fixed team
+    """Workgroups that share a problem wait for each other with a bound (B = 24: a fixed team
     per problem meets once per layer; B = 200: helpers wait for mail, owners for the helpers
     they sent for).  With the bound set to zero from the host every wait that is not satisfied
     at once gives up: the launch must still end, the next call must report VF_ESTATE, and with
