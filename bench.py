@@ -22,8 +22,8 @@ PEAK_HBM_GBS = 8000.0       # MI355X HBM3E
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE at batch 256, scaled by a
 # plain 1 GiB copy (profiles/*_hbm_counters.txt); only valid for the default batch, and to be
 # set to None whenever the kernel changes without the counters being taken again
-TRAFFIC_SCORE_BYTES = {256: 8751.1 * 1024 * 2.0 + 50760.0 * 1024}
-TRAFFIC_FEATURIZE_BYTES = {256: 2230.0 * 1024 * 2.0 + 1073741824.0}
+TRAFFIC_SCORE_BYTES = {256: 8827.5 * 1024 * 2.0 + 50885.0 * 1024}
+TRAFFIC_FEATURIZE_BYTES = {256: 945.0 * 1024 * 2.0 + 1073741824.0}
 
 
 def mlp_flops(dims):

@@ -80,39 +80,63 @@ __global__ __launch_bounds__(256) void k_enumerate(Tables t, int stage, uint32_t
   }
 }
 
-// Feature-major output feat[b][F][Mpad]: consecutive lanes hold consecutive
-// candidates, so every store instruction of a wave writes one contiguous run.
+// Feature-major output feat[b][F][Mpad].  A workgroup covers SPAN consecutive blocks of 256
+// candidates.  The 64 rows that differ from candidate to candidate go through LDS, 32 rows
+// of a block at a time, so that every store instruction of a wave writes a kilobyte of one
+// row (16 bytes per lane); the other rows are the same for every candidate and are written
+// over the workgroup's whole span at once.
+constexpr int VF_FEAT_SPAN = 4;
 __global__ __launch_bounds__(256) void k_featurize(Tables t, int stage, uint32_t M, uint32_t Mpad, int F,
                                                    int32_t *feat) {
   __shared__ Dec d;
   __shared__ vf_space sp;
+  __shared__ __attribute__((aligned(16))) int32_t tile[32][256];
   const int b = blockIdx.y;
   build_dec(d, sp, t, b, stage);
-  const uint32_t cid = blockIdx.x * 256u + threadIdx.x;
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   int32_t *out = feat + (size_t)b * F * Mpad;
-  int32_t core[64];
-  if (cid < M) {
-    uint32_t dec;
-    eval_candidate<true>(d, sp, cid, dec, core);
-  } else {
-#pragma unroll
-    for (int k = 0; k < 64; ++k) core[k] = 0;
-  }
-#pragma unroll
-  for (int k = 0; k < 64; ++k) out[(size_t)k * Mpad + cid] = core[k];
+  const uint32_t first = blockIdx.x * (uint32_t)(256 * VF_FEAT_SPAN);
   if (F == 256) {
-    // rows 64..255 are the same for every candidate: each wave writes whole rows
-    // with 16-byte stores (4 candidates per lane)
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const uint32_t col0 = blockIdx.x * 256u + 4u * lane;
+    // rows 64..255: each wave writes its rows over the whole span (first: these stores need
+    // no evaluation and are under way while the candidates are evaluated)
     for (int r = w; r < 192; r += 4) {
       const int32_t v = d.nb[r];
-      int4 q;
-      q.x = col0 + 0 < M ? v : 0;
-      q.y = col0 + 1 < M ? v : 0;
-      q.z = col0 + 2 < M ? v : 0;
-      q.w = col0 + 3 < M ? v : 0;
-      *reinterpret_cast<int4 *>(out + (size_t)(64 + r) * Mpad + col0) = q;
+#pragma unroll
+      for (int sb = 0; sb < VF_FEAT_SPAN; ++sb) {
+        const uint32_t col0 = first + 256u * sb + 4u * lane;
+        if (col0 >= Mpad) break;
+        int4 q;
+        q.x = col0 + 0 < M ? v : 0;
+        q.y = col0 + 1 < M ? v : 0;
+        q.z = col0 + 2 < M ? v : 0;
+        q.w = col0 + 3 < M ? v : 0;
+        *reinterpret_cast<int4 *>(out + (size_t)(64 + r) * Mpad + col0) = q;
+      }
+    }
+  }
+  for (int sb = 0; sb < VF_FEAT_SPAN; ++sb) {
+    const uint32_t base = first + 256u * sb;
+    if (base >= Mpad) break;
+    const uint32_t cid = base + threadIdx.x;
+    int32_t core[64];
+    if (cid < M) {
+      uint32_t dec;
+      eval_candidate<true>(d, sp, cid, dec, core);
+    } else {
+#pragma unroll
+      for (int k = 0; k < 64; ++k) core[k] = 0;
+    }
+    const uint32_t col0 = base + 4u * lane;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      __syncthreads();  // the tile has been read
+#pragma unroll
+      for (int k = 0; k < 32; ++k) tile[k][threadIdx.x] = core[32 * half + k];
+      __syncthreads();
+#pragma unroll
+      for (int r = w; r < 32; r += 4)
+        *reinterpret_cast<int4 *>(out + (size_t)(32 * half + r) * Mpad + col0) =
+            *reinterpret_cast<const int4 *>(&tile[r][4 * lane]);
     }
   }
 }
@@ -442,7 +466,7 @@ int vfk_enumerate(vf_ctx *c, int stage, uint32_t *dec, uint8_t *valid, int32_t *
 
 int vfk_featurize(vf_ctx *c, int stage, int32_t *feat) {
   vf_prof_scope prof(c, VF_PROF_FEATURIZE);
-  dim3 grid((unsigned)(c->Mpad / 256), (unsigned)c->B);
+  dim3 grid((unsigned)((c->Mpad / 256 + VF_FEAT_SPAN - 1) / VF_FEAT_SPAN), (unsigned)c->B);
   hipLaunchKernelGGL(k_featurize, grid, dim3(256), 0, c->stream, tables_of(c), stage, (uint32_t)c->M,
                      (uint32_t)c->Mpad, (int)c->space.F, feat);
   VF_HIP(c, hipGetLastError());
