@@ -1060,14 +1060,14 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
       VF_HIP(c, hipGetLastError());
       off += (size_t)K * N + N;
     }
-    // uniform hidden width 512 or 1024 with k-step counts that are multiples of 8:
-    // pack the per-wave fragment stream for k_mlp_fast as well
+    // uniform hidden width 512 or 1024 with k-step counts that are multiples of 4 (the
+    // deepest weight ring): pack the per-wave fragment stream for k_mlp_fast as well
     int rt = 0;
     if (L >= 2) {
       rt = m.dims[1] / 256;
       if (rt != 2 && rt != 4) rt = 0;
       for (int l = 1; l < L; ++l) if (m.dims[l] != 256 * rt) rt = 0;
-      for (int l = 0; l < L - 1; ++l) if ((m.dims[l] / 16) % 8 != 0) rt = 0;
+      for (int l = 0; l < L - 1; ++l) if ((m.dims[l] / 16) % 4 != 0) rt = 0;
     }
     if (rt) {
       int steps = 0;

@@ -405,7 +405,7 @@ def test_whole_schedule_launch_other_depths(vf, ovf, dims):
     three hidden layers (their tile no longer fits the LDS next to the input buffer: the call
     falls back to the launches per layer), 64 input rows (no shared rows to fold), the wide
     tile.  Same tables as stepping layer by layer; two problems against the checker."""
-    B = 16
+    B = 24
     pipes = I.resnet18_batch(B, seed=21)
     sp = I.make_space([1, 2, 4], [1, 4], [4, 8], [(0, 1, 2), (2, 1, 0)], 2, 2,
                       [I.ROOT, I.L1, I.L2, I.INLINE], 2, dims[0])
