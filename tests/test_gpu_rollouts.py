@@ -40,14 +40,16 @@ def test_noise_alone_is_bit_exact(vf, ovf, dtype, dims):
     vf.vf_destroy(ctx)
 
 
-def test_noisy_rollouts_fused_bf16(vf, ovf):
+@pytest.mark.parametrize("B", [3, 6])
+def test_noisy_rollouts_fused_bf16(vf, ovf, B):
     """A batch of copies of one network is a batch of different rollouts; each follows the
-    checker's rollout with the same id (decisions inside the score tolerance are forced)."""
+    checker's rollout with the same id (decisions inside the score tolerance are forced).
+    (3 rollouts: few enough for the scorer's tiles of 64 candidates; 6: tiles of 128.)"""
     pipe, sp = I.resnet18_shaped(), I.resnet18_space()
     dims = [256, 512, 512, 1]
     w = I.mlp_weights(dims, 0)
     model = I.model_record(I.MLP, dims, I.BF16)
-    B, eps, seed = 6, 0.5, 2024
+    eps, seed = 0.5, 2024
     ctx, cids, vals, st = gpu_rollouts(vf, pipe, sp, model, w, B, eps, seed)
     assert len({tuple(r) for r in cids}) == B                     # all different
     forced = np.full((B, 20), -1, np.int32)
