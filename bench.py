@@ -195,6 +195,34 @@ def main():
         mb_ms = (time.perf_counter() - t1) / 5 * 1e3
         vf.vf_destroy(ctx5)
 
+    # Algorithm 2's use of the scan: 100 noisy rollouts of one network (Sec. 3.1), here the
+    # 100-stage pipeline: a batch of 100 copies with different noise
+    rollouts = None
+    if not args.no_latency:
+        ctxr = vf.vf_create(0)
+        vf.vf_set_space(ctxr, I.mobilenetv2_space())
+        vf.vf_set_pipeline(ctxr, np.repeat(I.mobilenetv2_shaped()[None], 100, axis=0))
+        vf.vf_set_model(ctxr, model, w)
+        vf.vf_set_noise(ctxr, 0.3, 7)
+        vf.vf_profile_enable(ctxr, True)
+        for _ in range(2):
+            vf.vf_reset_state(ctxr); vf.vf_greedy_schedule(ctxr)
+        torch.cuda.synchronize()
+        vf.vf_profile_counts(ctxr)
+        t1 = time.perf_counter()
+        for _ in range(3):
+            vf.vf_reset_state(ctxr); vf.vf_greedy_schedule(ctxr)
+        torch.cuda.synchronize()
+        dtr = (time.perf_counter() - t1) / 3
+        _, valid_r = vf.vf_profile_counts(ctxr)
+        vf.vf_profile_enable(ctxr, False)
+        for k in (0, 1, 2):
+            vf.vf_profile_read(ctxr, k)
+        rollouts = {"workload": "100 noisy rollouts (eps 0.3) of the MobileNet-V2-shaped pipeline, 100 stages, "
+                                "16384 candidate ids per decision", "ms_per_batch": dtr * 1e3,
+                    "valid_candidates_per_s": valid_r / 3 / dtr}
+        vf.vf_destroy(ctxr)
+
     # the paper's own kind of V (Sec. 3.2): LSTM 64 -> 256 over one timestep per stage, head
     # summed, guiding the same greedy scan on a smaller batch of the same pipelines
     lstm = None
@@ -239,6 +267,7 @@ def main():
         "candidate_ids_per_s": ids_per_step * args.steps / dt,
         "greedy_ms_single_pipeline": single_ms,
         "greedy_ms_mobilenetv2_100_stages_16384_candidates": mb_ms,
+        "noisy_rollouts_100": rollouts,
         "greedy_with_recurrent_network": lstm,
         "kernel_ms_per_step": {"featurize": ms_feat / args.steps, "score": ms_score / args.steps,
                                "commit": ms_commit / args.steps},
