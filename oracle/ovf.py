@@ -62,6 +62,7 @@ def lib():
         L.ovf_noise.restype = C.c_float
         L.ovf_noise.argtypes = [C.c_uint64, i32, i32, i32]
         L.ovf_rollouts.argtypes = [vp, i32, vp, vp, vp, C.c_float, C.c_uint64, i32, i32, vp, vp, vp, vp]
+        L.ovf_decision_scores.argtypes = [vp, i32, vp, vp, vp, vp, i32, C.c_float, C.c_uint64, i32, vp, vp]
         L.ovf_beam.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.ovf_num_threads.restype = i32
         _lib = L
@@ -229,6 +230,19 @@ def rollouts(stages, space, model, weights, eps, seed, n_rollouts, first_rollout
     _check(lib().ovf_rollouts(_p(stages), S, _p(space), _p(model), _p(weights), C.c_float(eps), seed,
                               first_rollout, n_rollouts, _p(forced), _p(cids), _p(values), _p(top2)))
     return dict(cids=cids, values=values, top2=top2)
+
+
+def decision_scores(stages, space, model, weights, prefix_cids, stage, eps=0.0, seed=0, rollout=0):
+    """(scores [M] float32, valid [M] bool) as the scan of decision `stage` sees them after the
+    committed prefix, exploration noise of `rollout` included when eps != 0."""
+    stages = _i32(stages, (-1, 16)); space = _i32(space); model = _i32(model)
+    weights = np.ascontiguousarray(weights, np.float32); pre = _i32(prefix_cids, (-1,))
+    assert len(pre) >= stage
+    M = dense_count(space)
+    sc = np.empty(M, np.float32); ok = np.zeros(M, np.uint8)
+    _check(lib().ovf_decision_scores(_p(stages), len(stages), _p(space), _p(model), _p(weights), _p(pre), stage,
+                                     C.c_float(eps), seed, rollout, _p(sc), _p(ok)))
+    return sc, ok != 0
 
 
 def beam(stages, space, width, model=None, weights=None, vfun=None):

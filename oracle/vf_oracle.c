@@ -805,6 +805,66 @@ float ovf_noise(uint64_t seed, int32_t rollout, int32_t stage, int32_t cid) {
 
 /* ----------------------------------------------------------------- greedy */
 
+/* V(s) of every candidate state of one decision (the inner loop of Algorithm 1 before the
+ * scan): sc[cid] for cid < M, ok[cid] = validity; the score of an invalid id is left
+ * unspecified (the callback path sets +inf).  xcol is scratch of F * M values.  With
+ * eps != 0 the exploration noise of Section 3.1 for (rollout, layer, candidate) is added
+ * to the valid ones: one float multiply, one float add. */
+static int decision_scores(const decision *dp, const ovf_model *m, const float *weights, ovf_vfun vfun,
+                           void *user, int recurrent, float eps, uint64_t seed, int32_t rollout,
+                           int32_t *xcol, float *sc, uint8_t *ok) {
+  const decision d = *dp;
+  const ovf_stage *stages = d.stages;
+  const ovf_space *sp = d.sp;
+  const int S = d.S, i = d.i, F = sp->F;
+  const int32_t *cf = d.cf;
+  const int64_t M = ovf_dense_count(sp);
+  int rc = OVF_OK;
+  {
+    int32_t nb[192];
+    memset(nb, 0, sizeof nb);
+    for (int k = 1; k <= 3; ++k) {
+      if (i - k >= 0)
+        for (int t = 0; t < 48; ++t) nb[48 * (k - 1) + t] = cf[64 * (size_t)(i - k) + t];
+      if (i + k < S) intrinsic(stages, S, i + k, nb + 144 + 16 * (k - 1));
+    }
+    /* features of every candidate state, column-per-candidate for the scorer */
+    if (!recurrent) {
+#pragma omp parallel for schedule(static)
+      for (int64_t cid = 0; cid < M; ++cid) {
+        int32_t core[64];
+        ok[cid] = (uint8_t)candidate(&d, cid, NULL, core, NULL);
+        for (int k = 0; k < 64; ++k) xcol[(size_t)k * M + cid] = core[k];
+        if (F == 256)
+          for (int k = 0; k < 192; ++k) xcol[(size_t)(64 + k) * M + cid] = nb[k];
+      }
+    }
+    if (recurrent) {
+      rc = score_decision_lstm(&d, m, weights, sc, ok);
+      if (rc != OVF_OK) return rc;
+    } else if (vfun) {
+      for (int64_t cid = 0; cid < M; ++cid) {
+        if (!ok[cid]) { sc[cid] = INFINITY; continue; }
+        int32_t core[64];
+        for (int k = 0; k < 64; ++k) core[k] = xcol[(size_t)k * M + cid];
+        sc[cid] = (float)vfun(user, i, (int32_t)cid, core);
+      }
+    } else {
+      rc = ovf_score_mlp(m, weights, xcol, M, M, sc);
+      if (rc != OVF_OK) return rc;
+    }
+    /* Section 3.1: exploration adds a small random noise to the predictions */
+    if (eps != 0.0f)
+      for (int64_t cid = 0; cid < M; ++cid)
+        if (ok[cid]) {
+          float t = eps * ovf_noise(seed, rollout, i, (int32_t)cid);
+          sc[cid] = sc[cid] + t;
+        }
+  }
+  return rc;
+}
+
+
 /* Algorithm 1 over stages first..last with stages 0..first-1 already committed to
  * cids[0..first-1].  V is the MLP `m` (raw features -> normalise -> network), the
  * recurrent network `m` over the state's sequence form (model kind 1 with 64 inputs per
@@ -842,45 +902,8 @@ static int greedy_impl(const ovf_stage *stages, int S, const ovf_space *sp, cons
       continue;
     }
     decision d = { stages, S, sp, i, st, cf };
-    int32_t nb[192];
-    memset(nb, 0, sizeof nb);
-    for (int k = 1; k <= 3; ++k) {
-      if (i - k >= 0)
-        for (int t = 0; t < 48; ++t) nb[48 * (k - 1) + t] = cf[64 * (size_t)(i - k) + t];
-      if (i + k < S) intrinsic(stages, S, i + k, nb + 144 + 16 * (k - 1));
-    }
-    /* features of every candidate state, column-per-candidate for the scorer */
-    if (!recurrent) {
-#pragma omp parallel for schedule(static)
-      for (int64_t cid = 0; cid < M; ++cid) {
-        int32_t core[64];
-        ok[cid] = (uint8_t)candidate(&d, cid, NULL, core, NULL);
-        for (int k = 0; k < 64; ++k) xcol[(size_t)k * M + cid] = core[k];
-        if (F == 256)
-          for (int k = 0; k < 192; ++k) xcol[(size_t)(64 + k) * M + cid] = nb[k];
-      }
-    }
-    if (recurrent) {
-      rc = score_decision_lstm(&d, m, weights, sc, ok);
-      if (rc != OVF_OK) break;
-    } else if (vfun) {
-      for (int64_t cid = 0; cid < M; ++cid) {
-        if (!ok[cid]) { sc[cid] = INFINITY; continue; }
-        int32_t core[64];
-        for (int k = 0; k < 64; ++k) core[k] = xcol[(size_t)k * M + cid];
-        sc[cid] = (float)vfun(user, i, (int32_t)cid, core);
-      }
-    } else {
-      rc = ovf_score_mlp(m, weights, xcol, M, M, sc);
-      if (rc != OVF_OK) break;
-    }
-    /* Section 3.1: exploration adds a small random noise to the predictions */
-    if (eps != 0.0f)
-      for (int64_t cid = 0; cid < M; ++cid)
-        if (ok[cid]) {
-          float t = eps * ovf_noise(seed, rollout, i, (int32_t)cid);
-          sc[cid] = sc[cid] + t;
-        }
+    rc = decision_scores(&d, m, weights, vfun, user, recurrent, eps, seed, rollout, xcol, sc, ok);
+    if (rc != OVF_OK) break;
     /* the scan of Algorithm 1 */
     float v = INFINITY, v2 = INFINITY;
     int32_t s = -1;
@@ -933,6 +956,31 @@ int ovf_rollouts(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_
     if (rc != OVF_OK) return rc;
   }
   return OVF_OK;
+}
+
+/* The scores the scan of decision `stage` sees, given the committed prefix
+ * prefix_cids[0..stage-1]: scores[cid] (with the noise of (rollout, stage, cid) when
+ * eps != 0) and valid[cid] for every cid < M.  Same arithmetic as ovf_greedy /
+ * ovf_rollouts (it is the routine they call); lets a test look at the margin between any
+ * two candidates of a decision, not only at the two smallest. */
+int ovf_decision_scores(const ovf_stage *stages, int S, const ovf_space *sp, const ovf_model *m,
+                        const float *weights, const int32_t *prefix_cids, int stage, float eps,
+                        uint64_t seed, int32_t rollout, float *scores, uint8_t *valid) {
+  if (!space_ok(sp) || !pipeline_ok(stages, S)) return OVF_EINVAL;
+  if (stage < 0 || stage >= S) return OVF_EINVAL;
+  const int recurrent = lstm_ok(m) && m->dims[0] == 64;
+  if (!recurrent && (!mlp_ok(m) || m->dims[0] != sp->F)) return OVF_EINVAL;
+  const int64_t M = ovf_dense_count(sp);
+  ovf_state *st = (ovf_state *)calloc((size_t)S, sizeof(ovf_state));
+  int32_t *cf = (int32_t *)calloc((size_t)S * 64, sizeof(int32_t));
+  int32_t *xcol = (int32_t *)malloc(sizeof(int32_t) * (size_t)sp->F * (size_t)M);
+  int rc = (st && cf && xcol) ? replay(stages, S, sp, prefix_cids, stage, st, cf) : OVF_ENOMEM;
+  if (rc == OVF_OK) {
+    decision d = { stages, S, sp, stage, st, cf };
+    rc = decision_scores(&d, m, weights, NULL, NULL, recurrent, eps, seed, rollout, xcol, scores, valid);
+  }
+  free(st); free(cf); free(xcol);
+  return rc;
 }
 
 /* ------------------------------------------------------------ beam search */

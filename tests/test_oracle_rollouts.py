@@ -74,3 +74,29 @@ def test_rollout_is_the_scan_over_noisy_scores(ovf):
     assert np.array_equal(again["cids"], r["cids"]) and np.array_equal(again["values"], r["values"])
     shifted = ovf.rollouts(pipe, sp, m, w, float(eps), seed, 2, first_rollout=12)
     assert np.array_equal(shifted["cids"], r["cids"][2:4])                           # rollout ids, not positions
+
+
+def test_decision_scores_are_what_the_scan_sees(ovf):
+    """ovf.decision_scores exposes the per-decision scores of the greedy scan / the rollouts:
+    plain, they are score_mlp over featurize with the validity row; noisy, the first minimum and
+    the runner-up over the valid ones are what ovf.rollouts reports, layer by layer."""
+    pipe, sp, m, w = problem(4)
+    M = ovf.dense_count(sp)
+    g = ovf.greedy(pipe, sp, m, w)
+    for i in range(len(pipe)):
+        sc, ok = ovf.decision_scores(pipe, sp, m, w, g["cids"][:i], i)
+        feat = ovf.featurize(pipe, sp, g["cids"][:i], i)
+        assert np.array_equal(ok, feat[16, :M] == 1)
+        assert np.array_equal(sc[ok], ovf.score_mlp(m, w, feat, M=M)[ok])
+        best = int(np.flatnonzero(ok)[np.argmin(sc[ok])])
+        assert best == g["cids"][i] and sc[best] == g["values"][i]
+    eps, seed = 0.25, 42
+    r = ovf.rollouts(pipe, sp, m, w, eps, seed, 3, first_rollout=10)
+    for k in range(3):
+        for i in range(len(pipe)):
+            sc, ok = ovf.decision_scores(pipe, sp, m, w, r["cids"][k, :i], i, eps, seed, 10 + k)
+            s = np.where(ok, sc, np.inf)
+            assert int(np.argmin(s)) == r["cids"][k, i] and s.min() == r["values"][k, i]
+            assert np.sort(s)[1] == r["top2"][k, i]
+    with pytest.raises(ovf.OracleError):
+        ovf.decision_scores(pipe, sp, m, w, [0] * 5, 5)        # no such stage
