@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 from paper_2011_14486_amd import inputs as I
-from tests.util import TOL, score_err
+from tests.util import TOL, check_layers
 
 pytestmark = pytest.mark.gpu
 
@@ -52,22 +52,10 @@ def test_noisy_rollouts_fused_bf16(vf, ovf, B):
     eps, seed = 0.5, 2024
     ctx, cids, vals, st = gpu_rollouts(vf, pipe, sp, model, w, B, eps, seed)
     assert len({tuple(r) for r in cids}) == B                     # all different
-    forced = np.full((B, 20), -1, np.int32)
-    for _ in range(21):
-        ref = ovf.rollouts(pipe, sp, model, w, eps, seed, B, forced=forced)
-        bad = np.argwhere(ref["cids"] != cids)
-        if len(bad) == 0:
-            break
-        k, i = (int(t) for t in bad[0])
-        margin = abs(float(ref["top2"][k, i]) - float(ref["values"][k, i])) / max(abs(float(ref["values"][k, i])), 1.0)
-        assert margin <= TOL[1], f"rollout {k} layer {i}: decision differs outside the margin ({margin})"
-        forced[k, i] = cids[k, i]
-    else:
-        raise AssertionError("rollouts do not converge")
-    assert score_err(vals.ravel(), ref["values"].ravel()) <= TOL[1]
+    # every decision of every rollout under the GPU's own prefix: a valid candidate, the checker's
+    # first minimum of the noisy scores or within the tolerance of it, value and states agree
     for k in range(B):
-        rst, _ = ovf.states(pipe, sp, cids[k])
-        assert np.array_equal(rst, st[k])
+        check_layers(ovf, pipe, sp, model, w, cids[k], vals[k], st[k], TOL[1], eps=eps, seed=seed, rollout=k)
     # switching the noise off gives back the plain greedy schedule in every slot
     vf.vf_set_noise(ctx, 0.0)
     vf.vf_reset_state(ctx)
@@ -89,11 +77,8 @@ def test_noisy_rollouts_unfused_path(vf, ovf):
     model = I.model_record(I.MLP, dims, I.BF16)
     B, eps, seed = 4, 0.2, 5
     ctx, cids, vals, st = gpu_rollouts(vf, pipe, sp, model, w, B, eps, seed)
+    for k in range(B):
+        check_layers(ovf, pipe, sp, model, w, cids[k], vals[k], st[k], TOL[1], eps=eps, seed=seed, rollout=k)
     ref = ovf.rollouts(pipe, sp, model, w, eps, seed, B)
-    if not np.array_equal(cids, ref["cids"]):
-        k, i = (int(t) for t in np.argwhere(ref["cids"] != cids)[0])
-        margin = abs(float(ref["top2"][k, i]) - float(ref["values"][k, i])) / max(abs(float(ref["values"][k, i])), 1.0)
-        assert margin <= TOL[1]
-    else:
-        assert score_err(vals.ravel(), ref["values"].ravel()) <= TOL[1]
+    assert (ref["cids"] == cids).mean() > 0.5      # (and mostly the checker's own rollouts outright)
     vf.vf_destroy(ctx)

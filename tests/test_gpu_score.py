@@ -72,7 +72,7 @@ def test_mlp_padded_leading_dimension(vf, ovf):
 
 def test_raw_scoring_workload_sample(vf, ovf):
     """The 1,048,576-vector scoring workload at full size on the GPU; the checker scores a
-    sample of groups (the first 2 and 2 drawn with a seed) column by column."""
+    sample of 16 of the 256 groups (the first 8 and 8 drawn with a seed) column by column."""
     import torch
     dims = [256, 1024, 1024, 1024, 1]
     G, group = 256, 4096
@@ -87,7 +87,7 @@ def test_raw_scoring_workload_sample(vf, ovf):
     scores = scores.cpu().numpy(); bi = bi.cpu().numpy(); bv = bv.cpu().numpy()
     vf.vf_destroy(ctx)
     rng = np.random.default_rng(3)
-    sample = [0, 1] + sorted(rng.choice(np.arange(2, G), 2, replace=False).tolist())
+    sample = list(range(8)) + sorted(rng.choice(np.arange(8, G), 8, replace=False).tolist())
     for g in sample:
         blk = I.raw_feature_group(g, 256, group, seed=3)
         assert np.array_equal(blk, x[:, g * group:(g + 1) * group])
@@ -152,7 +152,7 @@ def test_lstm_bf16(vf, ovf, F, H, T, B):
 
 def test_recurrent_workload_sample(vf, ovf):
     """The 16,384-sequence LSTM workload (T = 50, F = 128, H = 256) at full size on the GPU;
-    the checker scores a sample of 256 sequences (the first 128 and one seeded block)."""
+    the checker scores a sample of 1024 sequences (the first 512 and four seeded blocks of 128)."""
     import torch
     F, H, T, B = 128, 256, 50, 16384
     w = I.lstm_weights(F, H, seed=0)
@@ -167,8 +167,8 @@ def test_recurrent_workload_sample(vf, ovf):
     s = s.cpu().numpy()
     assert np.array_equal(s, s2.cpu().numpy())            # run to run identical
     vf.vf_destroy(ctx)
-    blk = int(np.random.default_rng(4).integers(1, B // 128))
-    idx = np.concatenate([np.arange(128), np.arange(blk * 128, blk * 128 + 128)])
+    blks = np.random.default_rng(4).choice(np.arange(4, B // 128), 4, replace=False)
+    idx = np.concatenate([np.arange(512)] + [np.arange(b * 128, b * 128 + 128) for b in sorted(blks.tolist())])
     ref = ovf.score_lstm(model, w, xb[idx])
     assert score_err(s[idx], ref) <= TOL[1]
     assert np.isfinite(s).all()

@@ -37,3 +37,41 @@ def check_argmin(gpu_idx, gpu_val, ref_scores, valid, tol, lo=0):
     margin = (ref_scores[gpu_idx - lo] - vmin) / max(abs(vmin), s)
     assert margin <= tol, f"decision differs outside the margin: {gpu_idx - lo} vs {best}, margin {margin}"
     return False
+
+
+def check_layers(ovf, pipe, space, model, w, cids, vals, states, tol, layers=None, eps=0.0, seed=0, rollout=0):
+    """A schedule of the GPU against the checker, decision by decision, each under the GPU's own
+    committed prefix.  For every layer looked at: the GPU's choice must be a valid candidate; by
+    the checker's scores (exploration noise of `rollout` included) it must be the first minimum,
+    or lie within the tolerance of it - (score of the GPU's choice - minimum) / max(|minimum|,
+    RMS of the valid scores) <= tol - and the GPU's value must agree with the checker's score of
+    that same candidate.  All state records must be what the chosen ids replay to.  Returns the
+    number of decisions that differed inside the margin."""
+    cids = np.asarray(cids); vals = np.asarray(vals)
+    S = len(pipe)
+    layers = range(S) if layers is None else layers
+    n_margin = 0
+    for i in layers:
+        assert (cids[:i] >= 0).all(), "layer behind the end of the schedule"
+        sc, ok = ovf.decision_scores(pipe, space, model, w, cids[:i], i, eps, seed, rollout)
+        sc = sc.astype(np.float64)
+        cand = np.flatnonzero(ok & (sc < np.inf))
+        if len(cand) == 0:
+            assert cids[i] == -1 and vals[i] == np.inf, f"layer {i}: a winner where the checker has none"
+            continue
+        best = int(cand[np.argmin(sc[cand])])
+        g = int(cids[i])
+        assert g >= 0 and ok[g], f"layer {i}: GPU chose an invalid candidate ({g})"
+        s = max(float(np.sqrt(np.mean(sc[cand] ** 2))), 1e-30)
+        if g != best:
+            margin = (sc[g] - sc[best]) / max(abs(sc[best]), s)
+            assert margin <= tol, f"layer {i}: decision {g} vs {best} differs outside the margin ({margin})"
+            n_margin += 1
+        err = abs(float(vals[i]) - sc[g]) / max(abs(sc[g]), s)
+        assert err <= tol, f"layer {i}: value of candidate {g} off by {err}"
+    if states is not None:
+        n = int(np.argmax(cids < 0)) if (cids < 0).any() else S
+        rst, _ = ovf.states(pipe, space, cids[:n])
+        assert np.array_equal(rst, np.asarray(states)[:n]), "state records are not what the ids replay to"
+        assert not np.asarray(states)[n:].any()
+    return n_margin
