@@ -65,6 +65,8 @@ def lib():
         L.ovf_decision_scores.argtypes = [vp, i32, vp, vp, vp, vp, i32, C.c_float, C.c_uint64, i32, vp, vp]
         L.ovf_beam.argtypes = [vp, i32, vp, vp, vp, vp, vp, i32, vp, vp, vp, vp]
         L.ovf_num_threads.restype = i32
+        L.ovf_set_num_threads.argtypes = [C.c_int]
+        L.ovf_set_num_threads.restype = None
         _lib = L
     return _lib
 
@@ -263,3 +265,8 @@ def beam(stages, space, width, model=None, weights=None, vfun=None):
 
 def num_threads():
     return int(lib().ovf_num_threads())
+
+
+def set_num_threads(n):
+    """Threads used by the loops over candidates from now on (for timing)."""
+    lib().ovf_set_num_threads(int(n))

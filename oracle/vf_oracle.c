@@ -1103,3 +1103,13 @@ int ovf_num_threads(void) {
 #endif
   return n;
 }
+
+/* Caps the threads of the loops over candidates (timing a single thread next to all
+ * cores); n < 1 is ignored.  Changes no result. */
+void ovf_set_num_threads(int n) {
+#ifdef _OPENMP
+  if (n >= 1) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
