@@ -171,6 +171,23 @@ int vf_featurize(vf_ctx *ctx, int stage, int32_t *feat_dev);
 int vf_score(vf_ctx *ctx, const void *x_dev, int32_t x_kind, int64_t M, int64_t ld, int32_t group,
              float *scores_dev, int32_t *best_idx_dev, float *best_val_dev);
 
+/* vf_score for callers that cannot allocate device memory while they run: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * same kernels and bit-identical results as vf_score, but the per-workgroup minima that
+ * the scoring kernel leaves for the group scan live in a static device array of the
+ * library (512 KiB per GPU, held until the process ends) instead of a buffer that grows on
+ * demand: the call allocates and frees nothing (no per-kernel timing events either: the
+ * call is not bracketed by vf_profile_enable).  Limits: VF_BF16 models only (VF_EINVAL for
+ * VF_FP32, whose layer-by-layer kernels keep whole activation matrices in scratch), and at
+ * most vf_score_static_max() candidates per call - 65536 workgroup tiles of 64 candidates
+ * (LSTM, MLP wider than 512) or 128 (other MLPs) - else VF_EINVAL and nothing is launched.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (other
+ * streams, other contexts, other threads) race; calls in stream order on one stream do not. */
+int vf_score_static(vf_ctx *ctx, const void *x_dev, int32_t x_kind, int64_t M, int64_t ld, int32_t group,
+                    float *scores_dev, int32_t *best_idx_dev, float *best_val_dev);
+/* Largest M vf_score_static accepts with the context's model (0: no model, or not VF_BF16). */
+int64_t vf_score_static_max(const vf_ctx *ctx);
+
 /* One iteration of the outer loop of Algorithm 1 for stage `stage` ==
  * vf_n_scheduled(): enumerate, featurize, score, argmin over the valid candidates.
  * best_cid_dev[batch], best_val_dev[batch] (nullable) receive the winners.  If

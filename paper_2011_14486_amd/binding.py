@@ -22,7 +22,7 @@ VF_X_RAW_I32, VF_X_SEQ_BF16 = 0, 1
 EXPORTS = [
     "vf_create", "vf_destroy", "vf_set_space", "vf_set_pipeline", "vf_set_model", "vf_reset_state",
     "vf_set_state", "vf_n_scheduled", "vf_dense_count", "vf_padded_count", "vf_enumerate",
-    "vf_featurize", "vf_score", "vf_argmin_step", "vf_greedy_schedule", "vf_beam_search", "vf_set_noise", "vf_strerror",
+    "vf_featurize", "vf_score", "vf_score_static", "vf_score_static_max", "vf_argmin_step", "vf_greedy_schedule", "vf_beam_search", "vf_set_noise", "vf_strerror",
     "vf_last_hip_error", "vf_timer_start", "vf_timer_stop", "vf_timer_elapsed_ms",
     "vf_profile_enable", "vf_profile_read", "vf_profile_counts", "vf_set_wait_limit",
 ]
@@ -69,6 +69,9 @@ def lib():
         L.vf_enumerate.argtypes = [vp, C.c_int, vp, vp, vp]
         L.vf_featurize.argtypes = [vp, C.c_int, vp]
         L.vf_score.argtypes = [vp, vp, i32, i64, i64, i32, vp, vp, vp]
+        L.vf_score_static.argtypes = [vp, vp, i32, i64, i64, i32, vp, vp, vp]
+        L.vf_score_static_max.argtypes = [vp]
+        L.vf_score_static_max.restype = i64
         L.vf_argmin_step.argtypes = [vp, C.c_int, C.c_int, vp, vp]
         L.vf_greedy_schedule.argtypes = [vp, C.c_int, C.c_int, vp, vp, vp]
         L.vf_set_noise.argtypes = [vp, C.c_float, C.c_uint64, i32]
@@ -233,6 +236,30 @@ def vf_score(ctx, x, x_kind=VF_X_RAW_I32, M=None, group=0, want_scores=True, wan
     bv = ctx.empty((ng,), torch.float32) if want_min else None
     _check(ctx, lib().vf_score(ctx.handle, _ptr(x), x_kind, M, ld, group, _ptr(scores), _ptr(bi), _ptr(bv)))
     return scores, bi, bv
+
+
+def vf_score_static(ctx, x, x_kind=VF_X_RAW_I32, M=None, group=0, out=None):
+    """vf_score through the entry point that allocates nothing.  out = (scores or None, best_idx,
+    best_val): tensors the caller made beforehand (this wrapper makes them when out is None, which
+    is an allocation by torch, outside the library call)."""
+    torch = ctx.torch
+    assert x.is_cuda and x.is_contiguous()
+    if x_kind == VF_X_RAW_I32:
+        ld = x.shape[1]
+        M = ld if M is None else M
+    else:
+        M = x.shape[0] if M is None else M
+        ld = x.shape[1]
+    ng = 1 if group == 0 else max((M + group - 1) // group, 1)
+    if out is None:
+        out = (ctx.empty((M,), torch.float32), ctx.empty((ng,), torch.int32), ctx.empty((ng,), torch.float32))
+    scores, bi, bv = out
+    _check(ctx, lib().vf_score_static(ctx.handle, _ptr(x), x_kind, M, ld, group, _ptr(scores), _ptr(bi), _ptr(bv)))
+    return scores, bi, bv
+
+
+def vf_score_static_max(ctx):
+    return int(lib().vf_score_static_max(ctx.handle))
 
 
 def vf_argmin_step(ctx, stage, commit=True):

@@ -192,6 +192,7 @@ int vf_create(vf_ctx **out, int device, void *hip_stream) {
   if (rc == VF_OK) rc = dev_alloc(c, c->d_err, 1);
   if (rc == VF_OK) rc = dev_alloc(c, c->d_stat, 2);
   if (rc == VF_OK && hipMemsetAsync(c->d_stat, 0, 16, c->stream) != hipSuccess) rc = VF_EHIP;
+  if (rc == VF_OK) rc = vfk_static_parts(c, &c->static_parts);  // address of this device's static scratch
   if (rc == VF_OK && hipEventCreate(&c->ev0) != hipSuccess) rc = VF_EHIP;
   if (rc == VF_OK && hipEventCreate(&c->ev1) != hipSuccess) rc = VF_EHIP;
   if (rc != VF_OK) {
@@ -349,25 +350,23 @@ int vf_featurize(vf_ctx *c, int stage, int32_t *feat) {
   return vfk_featurize(c, stage, feat);
 }
 
-int vf_score(vf_ctx *c, const void *x, int32_t x_kind, int64_t M, int64_t ld, int32_t group, float *scores,
-             int32_t *best_idx, float *best_val) {
-  if (!c || M < 0 || group < 0 || (M > 0 && !x)) return VF_EINVAL;
-  if (!c->has_model) return VF_ESTATE;
-  if (M > (int64_t)1 << 30) return VF_EINVAL;
+// V(s) and the scan for given inputs.  parts == nullptr: the context's own growable buffers
+// hold the per-workgroup minima (vf_score); otherwise the given buffer does and nothing is
+// allocated (vf_score_static).
+static int score_call(vf_ctx *c, const void *x, int32_t x_kind, int64_t M, int64_t ld, int32_t group, float *scores,
+                      int32_t *best_idx, float *best_val, const vf_partbuf *parts) {
   const bool want_min = best_idx || best_val;
-  if (want_min && group > 0 && group % 128 != 0) return VF_EINVAL;
-  DeviceGuard g(c->device);
   int nparts = 0, part = 0, rc;
   if (x_kind == VF_X_RAW_I32) {
     if (c->model.kind != VF_MLP || ld < M) return VF_EINVAL;
-    rc = vfk_score_mlp(c, (const int32_t *)x, 0, 1, M, ld, 0, scores, ld, &nparts, -1);
+    rc = vfk_score_mlp(c, (const int32_t *)x, 0, 1, M, ld, 0, scores, ld, &nparts, -1, parts);
     int maxw = 0;
     for (int l = 0; l < c->model.n_layers; ++l)
       if (c->model.dims[l] > maxw) maxw = c->model.dims[l];
     part = (c->model.dtype == VF_FP32) ? VF_PART : (maxw > 512 ? 64 : 128);
   } else if (x_kind == VF_X_SEQ_BF16) {
     if (c->model.kind != VF_LSTM || ld < 0 || ld > (1 << 20)) return VF_EINVAL;
-    rc = vfk_score_lstm(c, (const uint16_t *)x, M, (int)ld, scores, &nparts);
+    rc = vfk_score_lstm(c, (const uint16_t *)x, M, (int)ld, scores, &nparts, parts);
     part = 64;
   } else {
     return VF_EINVAL;
@@ -377,9 +376,50 @@ int vf_score(vf_ctx *c, const void *x, int32_t x_kind, int64_t M, int64_t ld, in
   int ngroups = (int)((M + gsz - 1) / gsz);
   if (ngroups < 1) ngroups = 1;
   int ppg = (int)((gsz + part - 1) / part);
-  rc = vfk_ensure_parts(c, 1);
-  if (rc != VF_OK) return rc;
-  return vfk_argmin_groups(c, M, nparts, ppg, ngroups, best_idx, best_val);
+  if (!parts) {
+    rc = vfk_ensure_parts(c, 1);
+    if (rc != VF_OK) return rc;
+  }
+  return vfk_argmin_groups(c, M, nparts, ppg, ngroups, best_idx, best_val, parts);
+}
+
+int vf_score(vf_ctx *c, const void *x, int32_t x_kind, int64_t M, int64_t ld, int32_t group, float *scores,
+             int32_t *best_idx, float *best_val) {
+  if (!c || M < 0 || group < 0 || (M > 0 && !x)) return VF_EINVAL;
+  if (!c->has_model) return VF_ESTATE;
+  if (M > (int64_t)1 << 30) return VF_EINVAL;
+  if ((best_idx || best_val) && group > 0 && group % 128 != 0) return VF_EINVAL;
+  DeviceGuard g(c->device);
+  return score_call(c, x, x_kind, M, ld, group, scores, best_idx, best_val, nullptr);
+}
+
+int vf_score_static(vf_ctx *c, const void *x, int32_t x_kind, int64_t M, int64_t ld, int32_t group, float *scores,
+                    int32_t *best_idx, float *best_val) {
+  if (!c || M < 0 || group < 0 || (M > 0 && !x)) return VF_EINVAL;
+  if (!c->has_model) return VF_ESTATE;
+  if (c->model.dtype != VF_BF16) return VF_EINVAL;  // the fp32 kernels keep activation matrices in scratch
+  if (M > vf_score_static_max(c)) return VF_EINVAL;
+  if ((best_idx || best_val) && group > 0 && group % 128 != 0) return VF_EINVAL;
+  DeviceGuard g(c->device);
+  if (!c->static_parts.val) return VF_ESTATE;
+  const vf_partbuf parts = c->static_parts;
+  int rc;
+  // (event pairs of the per-kernel timing are created on demand: not in this call)
+  const bool prof = c->profiling;
+  c->profiling = false;
+  rc = score_call(c, x, x_kind, M, ld, group, scores, best_idx, best_val, &parts);
+  c->profiling = prof;
+  return rc;
+}
+
+int64_t vf_score_static_max(const vf_ctx *c) {
+  if (!c || !c->has_model || c->model.dtype != VF_BF16) return 0;
+  int maxw = 0;
+  if (c->model.kind == VF_MLP)
+    for (int l = 0; l < c->model.n_layers; ++l)
+      if (c->model.dims[l] > maxw) maxw = c->model.dims[l];
+  const int64_t tile = (c->model.kind == VF_LSTM || maxw > 512) ? 64 : 128;  // candidates per workgroup
+  return tile * VF_STATIC_PARTS;
 }
 
 int vf_argmin_step(vf_ctx *c, int stage, int commit, int32_t *best_cid, float *best_val) {

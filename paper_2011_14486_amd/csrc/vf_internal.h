@@ -11,8 +11,18 @@
 
 // candidates per partial-argmin slot (one slot per scoring workgroup)
 #define VF_PART 128
+// (value, id) pairs in the static scratch array of vf_score_static: one per scoring workgroup
+#define VF_STATIC_PARTS 65536
 // size of one packed decision context (see vf_sched_dev.h)
 #define VF_DECPACK_DWORDS 412
+
+// Where the scorers put their per-workgroup (value, id) minima when the context's own
+// growable buffers must not be used (nullable everywhere it is taken): `cap` pairs.
+struct vf_partbuf {
+  float *val;
+  int32_t *idx;
+  size_t cap;
+};
 
 struct vf_packed_model {
   // fp32 path: the caller's blob copied as is
@@ -104,6 +114,8 @@ struct vf_ctx {
   unsigned int wait_rounds = 1u << 22;  // bound of the waits between workgroups that share a problem
   int32_t *d_wlist = nullptr; size_t wlist_elems = 0;  // [B][Mpad] id lists of the whole-schedule launch
 
+  vf_partbuf static_parts = {nullptr, nullptr, 0};  // this device's static scratch array (vf_score_static)
+
   hipEvent_t ev0 = nullptr, ev1 = nullptr;
 
   // per-kernel timing (benchmarks): event pairs recorded around launches
@@ -187,7 +199,8 @@ void vfk_free_model(vf_ctx *c);
 // Writes scores (nullable, [nprob][ld_scores]) and the partial minima
 // (ctx->d_pval / d_pidx, [nprob][nparts], ids local to the problem).
 int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
-                  int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int noise_stage);
+                  int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int noise_stage,
+                  const vf_partbuf *parts = nullptr);
 // Enumerate + featurize + score + partial argmin of one stage in a single kernel (bf16
 // MLPs of uniform hidden width whose input width is the space's F).
 bool vfk_can_fuse_step(const vf_ctx *c);
@@ -206,7 +219,11 @@ int vfk_step_scores(vf_ctx *c, int stage);
 // beam search pieces (vf_sched.hip)
 int vfk_beam_init(vf_ctx *c, int first_stage);
 int vfk_beam_select_commit(vf_ctx *c, int stage);
-int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores, int *nparts_out);
+int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores, int *nparts_out,
+                   const vf_partbuf *parts = nullptr);
 int vfk_argmin_groups(vf_ctx *c, int64_t M, int nparts, int parts_per_group, int ngroups,
-                      int32_t *best_idx, float *best_val);
+                      int32_t *best_idx, float *best_val, const vf_partbuf *parts = nullptr);
+// The static scratch array of vf_score_static on the current device (looked up once per
+// device), as a partial-minima buffer; VF_EHIP if the symbol's address cannot be had.
+int vfk_static_parts(vf_ctx *c, vf_partbuf *out);
 int vfk_ensure_parts(vf_ctx *c, size_t n);

@@ -18,7 +18,17 @@
 // reduction orders by value, then by id, and NaN never wins.
 #include <stdlib.h>
 
+#include <mutex>
+
 #include "vf_internal.h"
+
+// Scratch of vf_score_static (the entry point that allocates nothing): the per-workgroup
+// (value, id) minima that the scoring kernel leaves for the group scan, VF_STATIC_PARTS
+// floats followed by as many ids.  Every GPU the library runs on holds its own copy at its
+// own address until the process ends; in host code the name below is only a handle for
+// hipGetSymbolAddress, never a device address.
+// (VF_STATIC_PARTS = 65536 pairs = 512 KiB; tiles of 64 candidates: up to 4,194,304 candidates per call)
+static __device__ __align__(256) unsigned char scratch[(size_t)VF_STATIC_PARTS * 8];
 
 namespace {
 
@@ -997,6 +1007,34 @@ int grow(vf_ctx *c, T *&p, size_t &have, size_t want) {
 
 }  // namespace
 
+int vfk_static_parts(vf_ctx *c, vf_partbuf *out) {
+  // address of this device's copy of the array, asked for once per device with that device
+  // current (the callers hold a guard on c->device)
+  constexpr int MAXDEV = 64;
+  static std::mutex mu;
+  static void *dev_ptr[MAXDEV] = {nullptr};
+  if (c->device < 0 || c->device >= MAXDEV) return VF_EINVAL;
+  void *p = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(mu);
+    if (!dev_ptr[c->device]) {
+      void *q = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&q, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !q) {
+        (void)hipGetLastError();
+        c->last_hip = (int)e;
+        return VF_EHIP;
+      }
+      dev_ptr[c->device] = q;
+    }
+    p = dev_ptr[c->device];
+  }
+  out->val = reinterpret_cast<float *>(p);
+  out->idx = reinterpret_cast<int32_t *>(reinterpret_cast<unsigned char *>(p) + (size_t)VF_STATIC_PARTS * 4);
+  out->cap = VF_STATIC_PARTS;
+  return VF_OK;
+}
+
 int vfk_ensure_parts(vf_ctx *c, size_t n) {
   if (n <= c->part_elems) return VF_OK;
   size_t h1 = c->part_elems, h2 = c->part_elems;
@@ -1122,11 +1160,13 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
 
 static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
                      int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage,
-                     int noise_stage);
+                     int noise_stage, const vf_partbuf *parts = nullptr);
 
 int vfk_score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
-                  int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int noise_stage) {
-  return score_mlp(c, x, prob_stride, nprob, M, ld, use_valid_row, scores, ld_scores, nparts_out, -1, noise_stage);
+                  int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int noise_stage,
+                  const vf_partbuf *parts) {
+  return score_mlp(c, x, prob_stride, nprob, M, ld, use_valid_row, scores, ld_scores, nparts_out, -1, noise_stage,
+                   parts);
 }
 
 bool vfk_can_fuse_step(const vf_ctx *c) {
@@ -1203,7 +1243,7 @@ void vfk_fast_dev(const vf_ctx *c, bool generating, vf_fast_dev *fd, int *ks, in
 
 static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob, int64_t M, int64_t ld,
                      int use_valid_row, float *scores, int64_t ld_scores, int *nparts_out, int gen_stage,
-                     int noise_stage) {
+                     int noise_stage, const vf_partbuf *parts) {
   NoiseArgs na;
   na.eps = noise_stage >= 0 ? c->noise_eps : 0.0f;
   na.k0 = (uint32_t)c->noise_seed; na.k1 = (uint32_t)(c->noise_seed >> 32);
@@ -1212,6 +1252,7 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
   const int L = m.n_layers;
   hipStream_t st = c->stream;
   if (m.dtype == VF_FP32) {
+    if (parts) return VF_EINVAL;  // the layer-by-layer kernels keep whole activation matrices in scratch
     int maxh = 1;
     for (int l = 1; l <= L; ++l) if (m.dims[l] > maxh) maxh = m.dims[l];
     const size_t per_prob = (size_t)maxh * ld;
@@ -1276,8 +1317,16 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
   const bool narrow = !wide && gen_stage >= 0 && c->pm.fast_rt && ((M + 127) / 128) * nprob * 2 <= ncu;
   const int NC = (wide || narrow) ? 64 : 128;
   const int nparts = (int)((M + NC - 1) / NC);
-  int rc = vfk_ensure_parts(c, (size_t)(nparts > 0 ? nparts : 1) * nprob);
-  if (rc != VF_OK) return rc;
+  float *pval = nullptr;
+  int32_t *pidx = nullptr;
+  if (parts) {
+    if ((size_t)(nparts > 0 ? nparts : 1) * nprob > parts->cap) return VF_EINVAL;
+    pval = parts->val; pidx = parts->idx;
+  } else {
+    int rc = vfk_ensure_parts(c, (size_t)(nparts > 0 ? nparts : 1) * nprob);
+    if (rc != VF_OK) return rc;
+    pval = c->d_pval; pidx = c->d_pidx;
+  }
   const size_t smem = (size_t)NC * ks * 2 + (size_t)8 * NC * 4 + (size_t)NC * 4;
   if (nparts > 0 && c->pm.fast_rt) {
     vf_prof_scope prof(c, VF_PROF_SCORE);
@@ -1302,7 +1351,7 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     }
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_fast));
     hipLaunchKernelGGL(kern, grid, dim3(512), smem_fast, st, x, prob_stride, M, ld, use_valid_row, fd, ks, scores,
-                       ld_scores, c->d_pval, c->d_pidx, nparts, nprob, ga, na);
+                       ld_scores, pval, pidx, nparts, nprob, ga, na);
     VF_HIP(c, hipGetLastError());
   } else if (nparts > 0) {
     vf_prof_scope prof(c, VF_PROF_SCORE);
@@ -1313,22 +1362,31 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     else kern = k_mlp_bf16<128, 2, 2>;
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     hipLaunchKernelGGL(kern, grid, dim3(512), smem, st, x, prob_stride, M, ld, use_valid_row, md, ks, scores,
-                       ld_scores, c->d_pval, c->d_pidx, nparts, na);
+                       ld_scores, pval, pidx, nparts, na);
     VF_HIP(c, hipGetLastError());
   }
   *nparts_out = nparts;
   return VF_OK;
 }
 
-int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores, int *nparts_out) {
+int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores, int *nparts_out,
+                   const vf_partbuf *parts) {
   const vf_model &m = c->model;
   constexpr int NC = 64;
   LstmDev md;
   md.F = m.dims[0]; md.H = m.dims[1]; md.w_pack = c->pm.w_pack; md.aux = c->pm.aux;
   const int xld = md.F + 8, hld = md.H + 8;
   const int nparts = (int)((M + NC - 1) / NC);
-  int rc = vfk_ensure_parts(c, (size_t)(nparts > 0 ? nparts : 1));
-  if (rc != VF_OK) return rc;
+  float *pval = nullptr;
+  int32_t *pidx = nullptr;
+  if (parts) {
+    if ((size_t)(nparts > 0 ? nparts : 1) > parts->cap) return VF_EINVAL;
+    pval = parts->val; pidx = parts->idx;
+  } else {
+    int rc = vfk_ensure_parts(c, (size_t)(nparts > 0 ? nparts : 1));
+    if (rc != VF_OK) return rc;
+    pval = c->d_pval; pidx = c->d_pidx;
+  }
   const size_t smem = (size_t)2 * NC * xld * 2 + (size_t)2 * NC * hld * 2 + (size_t)8 * NC * 4 +
                       (size_t)(5 * md.H + 1) * 4;
   if (nparts > 0) {
@@ -1339,7 +1397,7 @@ int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores
         k_lstm_bf16<NC, 4, 2>;
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     hipLaunchKernelGGL(kern, dim3((unsigned)nparts), dim3(512), smem, c->stream, x, M, T, md, xld, hld, scores,
-                       c->d_pval, c->d_pidx);
+                       pval, pidx);
     VF_HIP(c, hipGetLastError());
   }
   *nparts_out = nparts;
@@ -1347,9 +1405,10 @@ int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores
 }
 
 int vfk_argmin_groups(vf_ctx *c, int64_t M, int nparts, int parts_per_group, int ngroups, int32_t *best_idx,
-                      float *best_val) {
+                      float *best_val, const vf_partbuf *parts) {
   (void)M;
-  hipLaunchKernelGGL(k_argmin_groups, dim3((unsigned)ngroups), dim3(64), 0, c->stream, c->d_pval, c->d_pidx, nparts,
+  hipLaunchKernelGGL(k_argmin_groups, dim3((unsigned)ngroups), dim3(64), 0, c->stream,
+                     parts ? parts->val : c->d_pval, parts ? parts->idx : c->d_pidx, nparts,
                      parts_per_group, best_idx, best_val);
   VF_HIP(c, hipGetLastError());
   return VF_OK;
