@@ -62,12 +62,13 @@ def mlp_flops(dims):
 
 
 def fused_mlp_flops(dims):
-    """Flops per candidate the fused step executes on the matrix cores: of the 256 input
-    rows only the 64 core rows differ between the candidates of a decision; the first
-    layer's product with the other 192 is computed once per decision (a bias)."""
+    """Flops per candidate the fused step executes on the matrix cores: of the input rows only
+    16..55 and 59 differ between the candidates of a decision; the first layer's product with
+    all the others is computed once per decision (a bias), and the candidates' contraction runs
+    over rows 16..63: three k-steps of 16."""
     d = list(dims)
-    if d[0] == 256:
-        d[0] = 64
+    if d[0] in (64, 256):
+        d[0] = 48
     return mlp_flops(d)
 
 
@@ -159,6 +160,7 @@ def main():
     ms_feat, n_feat = vf.vf_profile_read(ctx, vf.VF_PROF_FEATURIZE)
     ms_score, n_score = vf.vf_profile_read(ctx, vf.VF_PROF_SCORE)
     ms_commit, n_commit = vf.vf_profile_read(ctx, vf.VF_PROF_COMMIT)
+    vf.vf_sync_status(ctx)     # raises if a whole-schedule launch gave up a wait between workgroups
     cids = out[1].cpu().numpy()
     assert (cids >= 0).all(), "a schedule ended early"
 

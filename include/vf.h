@@ -204,7 +204,16 @@ int vf_argmin_step(vf_ctx *ctx, int stage, int commit, int32_t *best_cid_dev, fl
  * from the start, with more a workgroup that has finished its own problems helps with the
  * ones still running; workgroups that share a problem meet once per layer with a bounded
  * wait.  Should such a wait ever run out (the GPU shared with work that never ends), the
- * schedules of that call are incomplete and the next vf_greedy_schedule returns VF_ESTATE. */
+ * launch still ends, and the problems it did not finish read -1 / +inf / zero state from the
+ * first unfinished layer on.  The library learns of it when the stream has got there:
+ * vf_sync_status waits for that and reports it; otherwise the next call that builds on the
+ * context's schedule state (vf_greedy_schedule / vf_beam_search from first_stage > 0,
+ * vf_argmin_step / vf_enumerate / vf_featurize for a stage > 0) waits for the verdict before
+ * it does anything, and a call that starts from s_0 looks whether the verdict is in.
+ * Whoever finds out returns VF_ESTATE after repairing what can be repaired: if the context
+ * still holds that call's state, the layers it was asked for are run again with the launches
+ * per layer, so that the tables are complete afterwards and
+ * vf_greedy_schedule(first_stage = vf_n_scheduled()) fetches them. */
 int vf_greedy_schedule(vf_ctx *ctx, int first_stage, int last_stage, vf_state *out_states_dev,
                        int32_t *out_cids_dev, float *out_values_dev);
 
@@ -262,10 +271,17 @@ int vf_profile_read(vf_ctx *ctx, int which, double *total_ms_host, int64_t *laun
  * decided without the network and are not counted).  vf_profile_counts synchronises,
  * returns both counts since the last call and clears them.  Either pointer may be NULL. */
 int vf_profile_counts(vf_ctx *ctx, int64_t *scored_host, int64_t *valid_host);
+/* Waits until everything enqueued on the context's stream has run and reports how the last
+ * whole-schedule launch of vf_greedy_schedule ended: VF_OK, or VF_ESTATE if one of its
+ * bounded waits between workgroups ran out - then, if the context still holds that call's
+ * state, the affected layers have been run again with the launches per layer before this
+ * call returns, and the tables are complete (see vf_greedy_schedule). */
+int vf_sync_status(vf_ctx *ctx);
 /* Bound of the waits between the workgroups that share a problem inside a whole-schedule
- * launch of vf_greedy_schedule, in polling rounds (default 2^22, seconds).  A wait that
- * reaches the bound gives up: the launch still ends, its schedules are incomplete and the
- * next vf_greedy_schedule returns VF_ESTATE.  A bound of 0 makes every wait that cannot be
+ * launch of vf_greedy_schedule, in polling rounds (default 2^22, seconds); a helper's wait
+ * for work starts over whenever a problem finishes anywhere, so a launch that is merely long
+ * does not run it out.  A wait that reaches the bound gives up: the launch still ends, see
+ * vf_greedy_schedule for what follows.  A bound of 0 makes every wait that cannot be
  * satisfied at once give up; meant for tests of that path. */
 int vf_set_wait_limit(vf_ctx *ctx, unsigned int rounds);
 

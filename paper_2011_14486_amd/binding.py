@@ -24,7 +24,7 @@ EXPORTS = [
     "vf_set_state", "vf_n_scheduled", "vf_dense_count", "vf_padded_count", "vf_enumerate",
     "vf_featurize", "vf_score", "vf_score_static", "vf_score_static_max", "vf_argmin_step", "vf_greedy_schedule", "vf_beam_search", "vf_set_noise", "vf_strerror",
     "vf_last_hip_error", "vf_timer_start", "vf_timer_stop", "vf_timer_elapsed_ms",
-    "vf_profile_enable", "vf_profile_read", "vf_profile_counts", "vf_set_wait_limit",
+    "vf_profile_enable", "vf_profile_read", "vf_profile_counts", "vf_set_wait_limit", "vf_sync_status",
 ]
 
 _lib = None
@@ -86,6 +86,7 @@ def lib():
         L.vf_profile_read.argtypes = [vp, C.c_int, C.POINTER(C.c_double), C.POINTER(i64)]
         L.vf_profile_counts.argtypes = [vp, C.POINTER(i64), C.POINTER(i64)]
         L.vf_set_wait_limit.argtypes = [vp, C.c_uint]
+        L.vf_sync_status.argtypes = [vp]
         _lib = L
     return _lib
 
@@ -329,6 +330,12 @@ def vf_profile_read(ctx, which):
 def vf_set_wait_limit(ctx, rounds):
     """Bound (polling rounds) of the waits between workgroups that share a problem in vf_greedy_schedule."""
     _check(ctx, lib().vf_set_wait_limit(ctx.handle, int(rounds)))
+
+
+def vf_sync_status(ctx):
+    """Waits for the context's stream; raises VfError(VF_ESTATE) if the last whole-schedule launch gave
+    up a wait (its layers have then been run again per layer where the state was still there)."""
+    _check(ctx, lib().vf_sync_status(ctx.handle))
 
 
 def vf_profile_counts(ctx):

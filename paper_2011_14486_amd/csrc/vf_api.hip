@@ -162,6 +162,8 @@ int step(vf_ctx *c, int stage, int commit, int32_t *best_cid, float *best_val) {
   return vfk_commit_from_partials(c, stage, nparts, commit, best_cid, best_val);
 }
 
+int settle_whole(vf_ctx *c, bool wait);
+
 struct DeviceGuard {
   int prev = -1;
   explicit DeviceGuard(int dev) {
@@ -173,6 +175,37 @@ struct DeviceGuard {
     if (prev >= 0) (void)hipSetDevice(prev);
   }
 };
+
+// Looks at the outcome of the last whole-schedule launch, once.  wait = false: only if the
+// launch has finished (otherwise later).  A launch in which a bounded wait between workgroups
+// ran out has left some problems' schedules incomplete (unscheduled layers read -1 / +inf /
+// zero state): if the context still holds that call's state, its layers are run again here,
+// with the launches per layer, so that the tables end up complete; VF_ESTATE either way, so
+// that the caller learns of it.
+int settle_whole(vf_ctx *c, bool wait) {
+  if (!c->whole_pending) return VF_OK;
+  if (wait) {
+    VF_HIP(c, hipEventSynchronize(c->ev_whole));
+  } else {
+    const hipError_t q = hipEventQuery(c->ev_whole);
+    if (q == hipErrorNotReady) { (void)hipGetLastError(); return VF_OK; }
+    VF_HIP(c, q);
+  }
+  c->whole_pending = false;
+  if (!c->h_team_err || *c->h_team_err == 0) return VF_OK;
+  *c->h_team_err = 0;
+  if (c->state_epoch == c->whole_epoch && c->n_sched == c->whole_last + 1) {
+    int rc = vfk_rewind(c, c->whole_first);
+    if (rc != VF_OK) return rc;
+    c->n_sched = c->whole_first;
+    for (int i = c->whole_first; i <= c->whole_last; ++i) {
+      rc = step(c, i, 1, nullptr, nullptr);
+      if (rc != VF_OK) return rc;
+      c->n_sched = i + 1;
+    }
+  }
+  return VF_ESTATE;
+}
 
 }  // namespace
 
@@ -216,6 +249,7 @@ void vf_destroy(vf_ctx *c) {
   if (c->h_team_err) (void)hipHostFree(c->h_team_err);
   if (c->ev0) (void)hipEventDestroy(c->ev0);
   if (c->ev1) (void)hipEventDestroy(c->ev1);
+  if (c->ev_whole) (void)hipEventDestroy(c->ev_whole);
   for (auto &v : c->prof_pairs)
     for (hipEvent_t e : v) (void)hipEventDestroy(e);
   for (hipEvent_t e : c->prof_free) (void)hipEventDestroy(e);
@@ -297,6 +331,7 @@ int vf_reset_state(vf_ctx *c) {
   DeviceGuard g(c->device);
   c->n_sched = 0;
   c->seq_stage = -1;
+  ++c->state_epoch;
   return vfk_reset_state(c);
 }
 
@@ -338,6 +373,8 @@ int vf_enumerate(vf_ctx *c, int stage, uint32_t *dec, uint8_t *valid, int32_t *n
   if (stage < 0 || stage >= c->S) return VF_EINVAL;
   if (stage > c->n_sched) return VF_ESTATE;
   DeviceGuard g(c->device);
+  const int rc = settle_whole(c, stage > 0);
+  if (rc != VF_OK) return rc;
   return vfk_enumerate(c, stage, dec, valid, n_valid);
 }
 
@@ -347,6 +384,8 @@ int vf_featurize(vf_ctx *c, int stage, int32_t *feat) {
   if (stage < 0 || stage >= c->S) return VF_EINVAL;
   if (stage > c->n_sched) return VF_ESTATE;
   DeviceGuard g(c->device);
+  const int rc = settle_whole(c, stage > 0);
+  if (rc != VF_OK) return rc;
   return vfk_featurize(c, stage, feat);
 }
 
@@ -429,7 +468,9 @@ int vf_argmin_step(vf_ctx *c, int stage, int commit, int32_t *best_cid, float *b
   if (stage < 0 || stage >= c->S) return VF_EINVAL;
   if (stage != c->n_sched) return VF_ESTATE;
   DeviceGuard g(c->device);
-  int rc = step(c, stage, commit, best_cid, best_val);
+  int rc = settle_whole(c, stage > 0);
+  if (rc != VF_OK) return rc;
+  rc = step(c, stage, commit, best_cid, best_val);
   if (rc == VF_OK && commit) c->n_sched = stage + 1;
   return rc;
 }
@@ -441,10 +482,12 @@ int vf_greedy_schedule(vf_ctx *c, int first, int last, vf_state *out_states, int
   if (first < 0 || last >= c->S || first > last + 1) return VF_EINVAL;
   if (first != c->n_sched) return VF_ESTATE;
   DeviceGuard g(c->device);
-  if (c->h_team_err && *c->h_team_err) {
-    // an earlier launch gave up waiting for a member of a team: its schedules are incomplete
-    *c->h_team_err = 0;
-    return VF_ESTATE;
+  {
+    // an earlier whole-schedule launch that gave up a wait: this call builds on its tables
+    // unless it starts from s_0, so it waits for that launch's verdict; from s_0 it only
+    // looks whether the verdict is in
+    const int rc = settle_whole(c, first > 0);
+    if (rc != VF_OK) return rc;
   }
   if (first <= last && vfk_whole_team(c) >= 1) {
     int rc = vfk_greedy_whole(c, first, last);
@@ -488,7 +531,9 @@ int vf_beam_search(vf_ctx *c, int first, int last, vf_state *out_states, int32_t
     c->beam_checked = true;
   }
   DeviceGuard g(c->device);
-  int rc = vfk_beam_init(c, first);
+  int rc = settle_whole(c, first > 0);
+  if (rc != VF_OK) return rc;
+  rc = vfk_beam_init(c, first);
   if (rc != VF_OK) return rc;
   for (int i = first; i <= last; ++i) {
     rc = vfk_step_scores(c, i);
@@ -577,6 +622,15 @@ int vf_profile_counts(vf_ctx *c, int64_t *scored, int64_t *valid) {
   if (scored) *scored = (int64_t)h[0];
   if (valid) *valid = (int64_t)h[1];
   return VF_OK;
+}
+
+int vf_sync_status(vf_ctx *c) {
+  if (!c) return VF_EINVAL;
+  DeviceGuard g(c->device);
+  VF_HIP(c, hipStreamSynchronize(c->stream));
+  const int rc = settle_whole(c, true);
+  if (rc == VF_ESTATE) VF_HIP(c, hipStreamSynchronize(c->stream));  // the repair, if any, has run as well
+  return rc;
 }
 
 int vf_set_wait_limit(vf_ctx *c, unsigned int rounds) {

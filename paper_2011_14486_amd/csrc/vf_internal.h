@@ -14,7 +14,7 @@
 // (value, id) pairs in the static scratch array of vf_score_static: one per scoring workgroup
 #define VF_STATIC_PARTS 65536
 // size of one packed decision context (see vf_sched_dev.h)
-#define VF_DECPACK_DWORDS 412
+#define VF_DECPACK_DWORDS 428
 
 // Where the scorers put their per-workgroup (value, id) minima when the context's own
 // growable buffers must not be used (nullable everywhere it is taken): `cap` pairs.
@@ -40,8 +40,8 @@ struct vf_packed_model {
   uint16_t *w_stream = nullptr;
   size_t wave_stride = 0;          // 16-byte units between the streams of two waves
   int fast_rt = 0;
-  // 256 input rows: rows 64..255 do not depend on the candidate.  The stream with the
-  // first layer cut to the 64 core rows
+  // 64 or 256 input rows (the search's feature layouts): only rows 16..55 and 59 depend on
+  // the candidate.  The stream with the first layer cut to k-steps 1..3 (rows 16..63)
   uint16_t *w_stream_fold = nullptr;
   size_t wave_stride_fold = 0;
   // recurrent network wired to the search: [W_ih | W_hh] transposed, bf16 values as fp32, [64+H][4H]
@@ -111,6 +111,12 @@ struct vf_ctx {
   float *d_pval = nullptr; int32_t *d_pidx = nullptr; size_t part_elems = 0;
   unsigned int *d_team = nullptr; size_t team_elems = 0;  // team meetings: counters, error flag, per-member minima
   int32_t *h_team_err = nullptr;  // pinned: the error flag of the last team launch, copied back after it
+  // the last whole-schedule launch, until somebody has looked at its error flag: the event behind
+  // the flag's copy, the layers the call was asked for, the state epoch it ran in
+  hipEvent_t ev_whole = nullptr;
+  bool whole_pending = false;
+  int whole_first = 0, whole_last = -1;
+  uint64_t state_epoch = 0, whole_epoch = 0;  // state_epoch: bumped whenever the schedule state is replaced
   unsigned int wait_rounds = 1u << 22;  // bound of the waits between workgroups that share a problem
   int32_t *d_wlist = nullptr; size_t wlist_elems = 0;  // [B][Mpad] id lists of the whole-schedule launch
 
@@ -173,14 +179,17 @@ struct vf_fast_dev {
   int naux;                // floats in aux (biases of all layers, output vector)
   size_t bias_off[8];
   size_t wl_off;
-  int k0;                  // k-steps of the first layer present in w_stream
-  const uint4 *w_full;     // nullable (fold): the stream with the whole first layer; its k-steps 4..15 of
-  size_t wave_stride_full; // layer 0 are the weights of input rows 64..255
+  int k0;                  // k-steps of the first layer present in w_stream ...
+  int k0ofs;               // ... starting with this one (fold: steps 1..3 = input rows 16..63)
+  const uint4 *w_full;     // nullable (fold): the stream with the whole first layer, for the rows that the
+  size_t wave_stride_full; // candidates of a decision share (k-steps 0, 3 and, with 256 inputs, 4..15)
 };
 void vfk_fast_dev(const vf_ctx *c, bool generating, vf_fast_dev *fd, int *ks, int *NC);
 
 int vfk_setup_tables(vf_ctx *c);
 int vfk_reset_state(vf_ctx *c);
+// stages first.. become unscheduled again (tables as after committing stages 0..first-1)
+int vfk_rewind(vf_ctx *c, int first);
 int vfk_enumerate(vf_ctx *c, int stage, uint32_t *dec, uint8_t *valid, int32_t *n_valid);
 int vfk_featurize(vf_ctx *c, int stage, int32_t *feat);
 // reduce the per-workgroup partial minima of every problem, report and optionally commit

@@ -51,6 +51,18 @@ __global__ __launch_bounds__(256) void k_reset(Tables t, int B) {
   if (i0 == 0) t.err[0] = 0;
 }
 
+// Back to the state in which stages 0..first-1 are committed and nothing behind them is:
+// one workgroup per problem.
+__global__ __launch_bounds__(256) void k_rewind(Tables t, int first) {
+  const int S = t.S, b = blockIdx.x, tid = threadIdx.x;
+  const size_t row = (size_t)b * S;
+  for (int i = first * 64 + tid; i < S * 64; i += 256) t.cf[row * 64 + i] = 0;
+  for (int i = first * 16 + tid; i < S * 16; i += 256) t.states[row * 16 + i] = 0;
+  for (int i = (first + 1) * 2 + tid; i < (S + 1) * 2; i += 256) t.prefix[(size_t)b * (S + 1) * 2 + i] = 0;
+  for (int i = first + tid; i < S; i += 256) { t.cids[row + i] = -1; t.vals[row + i] = __builtin_inff(); }
+  if (tid == 0) t.alive[b] = first == 0 || t.cids[row + first - 1] >= 0;
+}
+
 __global__ __launch_bounds__(256) void k_fill_i32(int32_t *p, size_t n, int32_t v) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -438,6 +450,13 @@ __global__ __launch_bounds__(64) void k_beam_commit(Tables t, AltTables nw, int 
 
 int vfk_setup_tables(vf_ctx *c) {
   hipLaunchKernelGGL(k_setup, dim3(c->B), dim3(64), 0, c->stream, tables_of(c), c->d_intr, c->d_suffix);
+  VF_HIP(c, hipGetLastError());
+  return VF_OK;
+}
+
+int vfk_rewind(vf_ctx *c, int first) {
+  c->dec_stage = -1;
+  hipLaunchKernelGGL(k_rewind, dim3((unsigned)c->B), dim3(256), 0, c->stream, tables_of(c), first);
   VF_HIP(c, hipGetLastError());
   return VF_OK;
 }

@@ -435,19 +435,41 @@ __device__ __forceinline__ float add_noise(const NoiseArgs &na, float s, int p, 
 // The decision context in the form the fused scorer wants it: built once per problem
 // and stage (by the commit of the stage before, or by k_prepare), fetched by every
 // scoring workgroup with one coalesced copy.
+//
+// stat: the rows of the network's input that every candidate of the decision shares,
+// normalised, as bf16 pairs, one group of 8 words per k-step of 16 rows of the first layer:
+// words [0, 8) rows 0..15 (the stage's intrinsic block), [8, 16) rows 48..63 with the rows
+// that do depend on the candidate (48..55, 59) left zero - i.e. the anchor's tile_points /
+// n_tiles / compute_at level and the four running sums - and [16, 112) rows 64..255 (the
+// neighbour stages).  Sec. 3.2 itself says that intrinsic features do not depend on the
+// schedule: their part of the first layer is computed once per decision (fold_bias).
+constexpr int VF_STAT_WORDS = 112;
 struct DecPack {
   Dec d;
   vf_space sp;
-  uint32_t nbh[96];  // rows 64..255 normalised, as bf16 pairs
-  uint32_t pad[VF_DECPACK_DWORDS - (sizeof(Dec) + sizeof(vf_space)) / 4 - 96];
+  uint32_t stat[VF_STAT_WORDS];
+  uint32_t pad[VF_DECPACK_DWORDS - (sizeof(Dec) + sizeof(vf_space)) / 4 - VF_STAT_WORDS];
 };
 static_assert(sizeof(DecPack) == VF_DECPACK_DWORDS * 4, "DecPack size");
+
+// Word q of DecPack::stat from the decision context.
+__device__ __forceinline__ uint32_t stat_word(const Dec &d, int q) {
+  if (q >= 16) return pack_bf16(plog2_dev(d.nb[2 * (q - 16)]), plog2_dev(d.nb[2 * (q - 16) + 1]));
+  if (q < 8) return pack_bf16(plog2_dev(d.intr[2 * q]), plog2_dev(d.intr[2 * q + 1]));
+  // rows 48 + 2 (q - 8), 49 + 2 (q - 8): 56 a_tp, 57 a_nt, 58 a_cat, 59 the candidate's own, 60..63 the sums
+  switch (q) {
+    case 12: return pack_bf16(plog2_dev(d.a_tp), plog2_dev(d.a_nt));
+    case 13: return pack_bf16(plog2_dev(d.a_cat), 0.0f);
+    case 14: return pack_bf16(plog2_dev(d.pm), plog2_dev(d.pb));
+    case 15: return pack_bf16(plog2_dev(d.sm), plog2_dev(d.spt));
+    default: return 0u;
+  }
+}
 
 // Builds the pack for (problem b, stage) in LDS (every thread of the block takes part).
 [[maybe_unused]] __device__ void fill_decpack(DecPack &pk, const Tables &t, int b, int stage) {
   build_dec(pk.d, pk.sp, t, b, stage);
-  for (int q = threadIdx.x; q < 96; q += blockDim.x)
-    pk.nbh[q] = pack_bf16(plog2_dev(pk.d.nb[2 * q]), plog2_dev(pk.d.nb[2 * q + 1]));
+  for (int q = threadIdx.x; q < VF_STAT_WORDS; q += blockDim.x) pk.stat[q] = stat_word(pk.d, q);
   __syncthreads();
 }
 
@@ -516,7 +538,7 @@ static_assert(sizeof(DecPack) == VF_DECPACK_DWORDS * 4, "DecPack size");
 [[maybe_unused]] __device__ void write_decpack(DecPack &pk, const Tables &t, int b, int stage, uint32_t *out) {
   fill_decpack(pk, t, b, stage);
   const uint32_t *src = reinterpret_cast<const uint32_t *>(&pk);
-  const int used = (int)((sizeof(Dec) + sizeof(vf_space)) / 4 + 96);
+  const int used = (int)((sizeof(Dec) + sizeof(vf_space)) / 4 + VF_STAT_WORDS);
   for (int i = threadIdx.x; i < VF_DECPACK_DWORDS; i += blockDim.x)
     out[(size_t)b * VF_DECPACK_DWORDS + i] = i < used ? src[i] : 0u;
 }

@@ -355,7 +355,7 @@ __global__ __launch_bounds__(512) void k_mlp_bf16(const int32_t *x, int64_t prob
 // w + 8 r; `pad` zero steps follow so that the prefetch never leaves the buffer.
 __global__ __launch_bounds__(256) void k_pack_stream(const float *blob, vf_fast_dev md, int RT, int steps_total,
                                                      int pad, uint16_t *out) {
-  // md.k0: only the first md.k0 k-steps of the first layer are packed
+  // of the first layer only md.k0 k-steps are packed, starting with step md.k0ofs
   const size_t per_wave = (size_t)(steps_total + pad) * RT * 512;
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   if (i >= per_wave * 8) return;
@@ -371,7 +371,8 @@ __global__ __launch_bounds__(256) void k_pack_stream(const float *blob, vf_fast_
     for (int l = 0; l < md.L - 1; ++l) {
       const int K = md.dims[l], N = md.dims[l + 1], ksteps = l == 0 ? md.k0 : K / 16;
       if (step < ksteps) {
-        const int row = (w + 8 * r) * 32 + (lane & 31), k = step * 16 + 8 * (lane >> 5) + e;
+        const int kstep = l == 0 ? step + md.k0ofs : step;
+        const int row = (w + 8 * r) * 32 + (lane & 31), k = kstep * 16 + 8 * (lane >> 5) + e;
         v = (uint16_t)bf16_bits(blob[off + (size_t)row * K + k]);
         break;
       }
@@ -390,30 +391,33 @@ __global__ __launch_bounds__(256) void k_pack_stream(const float *blob, vf_fast_
 // GEN = false: the tile's features are read from x (raw int32, feature-major).
 // GEN = true: the tile's candidates are enumerated and featurized right here from
 // the scheduling tables of problem blockIdx.y (x is not used): the features go
-// straight into LDS as normalised bf16 and never touch HBM.
+// straight into LDS as normalised bf16 and never touch HBM.  Of the network's input rows
+// only 16..55 and 59 depend on the candidate: the product of the first layer with all the
+// others (the intrinsic block, the context rows, with 256 inputs the neighbour stages) is
+// computed once per decision and enters as the accumulators' starting value (fold_bias), and
+// the candidates' contraction runs over rows 16..63 (three k-steps) with zeros in the shared
+// rows among them.
 struct GenArgs {
   const uint32_t *decpack;  // [problem][VF_DECPACK_DWORDS], built for the stage being decided
   unsigned long long *stat; // nullable: [0] += ids pushed through the network, [1] += valid ones
 };
 
-template <int NC, int RT, int PD, bool GEN>
+// ONE (with GEN): the network has a single hidden layer.
+template <int NC, int RT, int PD, bool GEN, bool ONE = false>
 __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
                                                   int use_valid_row, vf_fast_dev md, int ks, float *scores,
                                                   int64_t ld_scores, float *pval, int32_t *pidx, int nparts,
                                                   int nprob, GenArgs ga, NoiseArgs na) {
   constexpr int CT = NC / 32;
   constexpr int SEGS = 512 / NC;
+  constexpr int ROT = GEN ? VF_K0_OWN % PD : 0;  // ring slot of the first k-step behind the first layer
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t *act = reinterpret_cast<uint16_t *>(smem);                   // [NC][ks]
   float *red = reinterpret_cast<float *>(smem + (size_t)NC * ks * 2);   // [8][NC]
   int32_t *okf = reinterpret_cast<int32_t *>(red + 8 * NC);             // [NC]
   float *auxs = reinterpret_cast<float *>(okf + NC);                    // [naux] biases, output vector
-  float *b1s = auxs + ((md.naux + 3) & ~3);                             // [dims[1]] folded first-layer bias
+  float *b1s = auxs + ((md.naux + 3) & ~3);                             // [dims[1]] folded first-layer bias (GEN)
   __shared__ DecPack pk;
-  // GEN with 256 input rows: rows 64..255 are the same for all candidates of a decision
-  // (neighbour stages), so their part of the first layer is a per-decision bias and the
-  // contraction runs over the 64 core rows only
-  const bool fold = GEN && md.w_full != nullptr;
   int b1_p = -1;
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -430,14 +434,14 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       if (tid + q * 512 < md.naux) auxs[tid + q * 512] = auxv[q];
     for (int i = tid + 2048; i < md.naux; i += 512) auxs[i] = md.aux[i];
   }
-  const uint4 *const wbase = md.w_stream + (size_t)w * md.wave_stride + lane;
-  const uint4 *wp = wbase;
+  const __amdgpu_buffer_rsrc_t ws = stream_rsrc(md.w_stream + (size_t)w * md.wave_stride);
+  const int voff = 16 * lane;
+  int wstep = PD;
   uint4 ring[PD][RT];
 #pragma unroll
   for (int j = 0; j < PD; ++j)
 #pragma unroll
-    for (int r = 0; r < RT; ++r) ring[j][r] = wp[(j * RT + r) * 64];
-  wp += PD * RT * 64;
+    for (int r = 0; r < RT; ++r) ring[j][r] = stream_load(ws, voff, j * RT + r);
 
   // ---- persistent loop: this workgroup's share of the (problem, tile) pairs, in
   // problem-major order so that consecutive tiles mostly share the decision context
@@ -470,49 +474,15 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       __syncthreads();  // the next tile may bring another problem's context
       continue;
     }
-    if (fold && b1_p != p) {
-      // the first layer's product with the 192 rows that all candidates of the decision
-      // share, once per decision: the same contraction with the shared vector in every
-      // column (twelve k-steps, one column tile); column 0 of the result plus the layer's
-      // bias is what the candidates' accumulators start from
-      floatx16 fa[RT];
-#pragma unroll
-      for (int r = 0; r < RT; ++r)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) fa[r][q] = 0.0f;
-      const uint4 *wf = md.w_full + (size_t)w * md.wave_stride_full + lane + (size_t)4 * RT * 64;
-#pragma unroll 4
-      for (int sk = 0; sk < 12; ++sk) {
-        uint4 a[RT];
-#pragma unroll
-        for (int r = 0; r < RT; ++r) a[r] = wf[((size_t)sk * RT + r) * 64];
-        const uint32_t *xb = pk.nbh + 8 * sk + 4 * (lane >> 5);
-        uint4 bv;
-        bv.x = xb[0]; bv.y = xb[1]; bv.z = xb[2]; bv.w = xb[3];
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-          fa[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[r]),
-                                                         __builtin_bit_cast(bf16x8, bv), fa[r], 0, 0, 0);
-      }
-      if ((lane & 31) == 0) {
-#pragma unroll
-        for (int r = 0; r < RT; ++r) {
-          const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
-#pragma unroll
-          for (int g = 0; g < 4; ++g)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              b1s[mbase + 8 * g + e] = auxs[md.bias_off[0] + mbase + 8 * g + e] + fa[r][4 * g + e];
-        }
-      }
+    if (b1_p != p) {
+      fold_bias<RT>(stream_rsrc(md.w_full + (size_t)w * md.wave_stride_full), pk.stat, md.dims[0] == 256, w, lane,
+                    auxs + md.bias_off[0], b1s);
       b1_p = p;
     }
     // ---- enumerate + featurize the tile: thread n < NC owns candidate n0 + n
     const Dec &dctx = pk.d;
     const vf_space &sp = pk.sp;
-    const uint32_t *nbh = pk.nbh;
-    const int F = md.dims[0];
-    // four threads per candidate, each producing 16 of the 64 core rows: the parts a
+    // four threads per candidate, each producing part of the rows 16..63: the parts a
     // thread does not store are dead code in its copy of the evaluation
     {
       const int n = tid % NC, part = tid / NC;
@@ -520,60 +490,35 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       const uint32_t cid = (uint32_t)(n0 + n);
       int32_t core[64];
       uint32_t dec;
-      auto put = [&](const int32_t *v, int row0) {
-        uint4 q0, q1;
-        q0.x = pack_bf16(plog2_dev(v[0]), plog2_dev(v[1]));
-        q0.y = pack_bf16(plog2_dev(v[2]), plog2_dev(v[3]));
-        q0.z = pack_bf16(plog2_dev(v[4]), plog2_dev(v[5]));
-        q0.w = pack_bf16(plog2_dev(v[6]), plog2_dev(v[7]));
-        q1.x = pack_bf16(plog2_dev(v[8]), plog2_dev(v[9]));
-        q1.y = pack_bf16(plog2_dev(v[10]), plog2_dev(v[11]));
-        q1.z = pack_bf16(plog2_dev(v[12]), plog2_dev(v[13]));
-        q1.w = pack_bf16(plog2_dev(v[14]), plog2_dev(v[15]));
-        if (!inb) q0 = q1 = make_uint4(0u, 0u, 0u, 0u);
-        uint4 *dst = reinterpret_cast<uint4 *>(act + (size_t)n * ks + row0);
-        dst[0] = q0;
-        dst[1] = q1;
+      // eight rows at a time: rows 16 + 8 q .. 23 + 8 q go to elements 8 q .. 8 q + 7 of the column
+      auto put8 = [&](const int32_t *v, int q) {
+        uint4 o;
+        o.x = pack_bf16(plog2_dev(v[0]), plog2_dev(v[1]));
+        o.y = pack_bf16(plog2_dev(v[2]), plog2_dev(v[3]));
+        o.z = pack_bf16(plog2_dev(v[4]), plog2_dev(v[5]));
+        o.w = pack_bf16(plog2_dev(v[6]), plog2_dev(v[7]));
+        if (!inb) o = make_uint4(0u, 0u, 0u, 0u);
+        *reinterpret_cast<uint4 *>(act + (size_t)n * ks + 8 * q) = o;
       };
-      // eight rows at a time; the row groups are dealt out so that the four copies cost
-      // about the same (rows 0..15 and 56..63 are copies of the context, 48..55 the dearest)
-      auto put8 = [&](const int32_t *v, int row0) {
-        uint4 q;
-        q.x = pack_bf16(plog2_dev(v[0]), plog2_dev(v[1]));
-        q.y = pack_bf16(plog2_dev(v[2]), plog2_dev(v[3]));
-        q.z = pack_bf16(plog2_dev(v[4]), plog2_dev(v[5]));
-        q.w = pack_bf16(plog2_dev(v[6]), plog2_dev(v[7]));
-        if (!inb) q = make_uint4(0u, 0u, 0u, 0u);
-        *reinterpret_cast<uint4 *>(act + (size_t)n * ks + row0) = q;
-      };
+      // the row groups are dealt out so that the four copies cost about the same
       if (part == 0) {
-        // evaluated for padding ids too: core must be defined before put reads it
+        // evaluated for padding ids too: core must be defined before it is packed
         const bool valid = eval_candidate<true>(dctx, sp, cid, dec, core);
         okf[n] = inb && valid;
-        put(core, 0);
-        put8(core + 40, 40);
+        put8(core + 16, 0);
+        put8(core + 24, 1);
       } else if (part == 1) {
         eval_candidate<true>(dctx, sp, cid, dec, core);
-        put(core + 16, 16);
+        put8(core + 32, 2);
+        // rows 56..63: only row 59 is the candidate's own, the others are part of the bias
+        uint4 o = make_uint4(0u, inb ? pack_bf16(0.0f, plog2_dev(core[59])) : 0u, 0u, 0u);
+        *reinterpret_cast<uint4 *>(act + (size_t)n * ks + 40) = o;
       } else if (part == 2) {
         eval_candidate<true>(dctx, sp, cid, dec, core);
-        put8(core + 32, 32);
-        put8(core + 56, 56);
+        put8(core + 40, 3);
       } else if (part == 3) {
         eval_candidate<true>(dctx, sp, cid, dec, core);
-        put8(core + 48, 48);
-      }
-    }
-    if (F == 256 && !fold) {
-      // the 192 neighbour rows are the same for every candidate id below M
-      const int n = tid % NC, part = tid / NC;
-      const bool inb = (n0 + n) < M;
-      constexpr int PER = 24 / SEGS;
-      const uint4 *src = reinterpret_cast<const uint4 *>(nbh);
-#pragma unroll
-      for (int q = 0; q < PER; ++q) {
-        const uint4 v = inb ? src[part * PER + q] : make_uint4(0u, 0u, 0u, 0u);
-        *reinterpret_cast<uint4 *>(act + (size_t)n * ks + 64 + (part * PER + q) * 8) = v;
+        put8(core + 48, 4);
       }
     }
   } else {
@@ -614,11 +559,8 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
 #pragma unroll
   for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
   const uint16_t *brow = act + (size_t)(lane & 31) * ks + 8 * (lane >> 5);
-  for (int l = 0; l < NH; ++l) {
-    const int ksteps = l == 0 ? md.k0 : md.dims[l] / 16;
-    // the accumulators start from the bias of their output row
-    const float *bias = (l == 0 && fold) ? b1s : auxs + md.bias_off[l];
-    floatx16 acc[RT][CT];
+  // the accumulators start from the bias of their output row
+  auto start_from_bias = [&](floatx16 (&acc)[RT][CT], const float *bias) __attribute__((always_inline)) {
 #pragma unroll
     for (int r = 0; r < RT; ++r) {
       const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
@@ -632,43 +574,14 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
         }
       }
     }
-    uint4 bcur[CT];
-#pragma unroll
-    for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ks);
-    // Nothing but this loop's own loads may be in flight when it starts: with a store to
-    // scratch or a scalar load still counted, the compiler can no longer tell the order in
-    // which the counters come down and waits for every load at the top of each round instead
-    // of for the oldest one.  (vmcnt 0, lgkmcnt 0; the ring's loads were issued a tile ago.)
-    __builtin_amdgcn_s_waitcnt(0x0070);
-    for (int s0 = 0; s0 < ksteps; s0 += PD) {
-      // the last PD steps of a tile prefetch the first PD steps of the next one
-      if (l == NH - 1 && s0 + PD >= ksteps) wp = wbase;
-#pragma unroll
-      for (int j = 0; j < PD; ++j) {
-        // One memory instruction behind each product: behind the first CT products the
-        // activation fragments of the next k-step (one step past the end stays inside the
-        // tile's LDS), behind the last product that reads a weight fragment its refill, in
-        // place, PD k-steps ahead of its next use - so only the oldest slot is ever waited for
-        uint4 bnext[CT];
-#pragma unroll
-        for (int i = 0; i < RT * CT; ++i) {
-          const int r = i / CT, c = i % CT;
-          acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-              __builtin_bit_cast(bf16x8, ring[j][r]), __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
-          if (i < CT) bnext[i] = *reinterpret_cast<const uint4 *>(brow + (size_t)i * 32 * ks + (s0 + j + 1) * 16);
-          if (i >= CT && c == 0) ring[j][r - 1] = wp[(r - 1) * 64];
-          if (i == RT * CT - 1) ring[j][RT - 1] = wp[(RT - 1) * 64];
-          __builtin_amdgcn_sched_barrier(0);
-        }
-        wp += RT * 64;
-#pragma unroll
-        for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
-      }
-    }
-    if (l < NH - 1) {
+  };
+  // what follows a layer's contraction: the last hidden layer is rounded to bf16 and multiplied
+  // with the output vector at once; any other one becomes the next layer's input - rounded to
+  // bfloat16, ReLU on the pairs, the two lane halves trade their row groups so that every lane
+  // writes 8 consecutive rows of its column at once
+  auto finish_layer = [&](floatx16 (&acc)[RT][CT], bool lastl) __attribute__((always_inline)) {
+    if (!lastl) {
       __syncthreads();  // every wave has read the layer's input: it can be overwritten
-      // rounded to bfloat16, ReLU on the pairs; the two lane halves then trade their row
-      // groups so that every lane writes 8 consecutive rows of its column at once
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
         const int m0 = (w + r * 8) * 32 + 8 * (lane >> 5);
@@ -688,7 +601,6 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       }
       __syncthreads();
     } else {
-      // last hidden layer: round to bf16 and multiply with the output vector at once
       const float *wl = auxs + md.wl_off;
 #pragma unroll
       for (int r = 0; r < RT; ++r) {
@@ -710,7 +622,23 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
         }
       }
     }
+  };
+  if constexpr (GEN) {
+    // the first layer over the candidates' own rows
+    floatx16 acc[RT][CT];
+    start_from_bias(acc, b1s);
+    contract_own_rows<RT, CT, PD, ONE>(acc, ring, ws, voff, brow, 32 * ks);
+    wstep = VF_K0_OWN + PD;
+    finish_layer(acc, ONE);
   }
+  for (int l = GEN ? 1 : 0; l < NH; ++l) {
+    floatx16 acc[RT][CT];
+    start_from_bias(acc, auxs + md.bias_off[l]);
+    // (the last PD steps of a tile prefetch the first PD steps of the next one)
+    contract_layer<RT, CT, PD, ROT>(acc, ring, ws, wstep, voff, l == NH - 1, md.dims[l] / 16, brow, 32 * ks);
+    finish_layer(acc, l == NH - 1);
+  }
+  if (!GEN) wstep = PD;
 
 #pragma unroll
   for (int c = 0; c < CT; ++c) {
@@ -1117,17 +1045,21 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
       fd.L = L;
       for (int l = 0; l < 8; ++l) fd.dims[l] = m.dims[l];
       fd.k0 = m.dims[0] / 16;
+      fd.k0ofs = 0;
       hipLaunchKernelGGL(k_pack_stream, blocks(per_wave * 8), dim3(256), 0, st, wdev, fd, rt, steps, pad, pm.w_stream);
       VF_HIP(c, hipGetLastError());
       pm.wave_stride = per_wave / 8;
       pm.fast_rt = rt;
-      if (m.dims[0] == 256) {
-        // the same stream with the first layer cut down to the 64 core rows, for the scorer
-        // that generates its candidates (the other rows' weights are read from the whole stream)
-        const int fsteps = steps - (m.dims[0] / 16 - 4);
+      if (m.dims[0] == 64 || m.dims[0] == 256) {
+        // the input widths of the search's feature layouts: the same stream with the first layer
+        // cut down to the k-steps of the rows that depend on the candidate (16..63), for the
+        // scorers that generate their candidates (the other rows' weights are read from the
+        // whole stream, once per decision)
+        const int fsteps = steps - (m.dims[0] / 16 - VF_K0_OWN);
         const size_t per_wave_f = (size_t)(fsteps + pad) * rt * 512;
         VF_HIP(c, hipMalloc((void **)&pm.w_stream_fold, per_wave_f * 8 * sizeof(uint16_t)));
-        fd.k0 = 4;
+        fd.k0 = VF_K0_OWN;
+        fd.k0ofs = 1;
         hipLaunchKernelGGL(k_pack_stream, blocks(per_wave_f * 8), dim3(256), 0, st, wdev, fd, rt, fsteps, pad,
                            pm.w_stream_fold);
         VF_HIP(c, hipGetLastError());
@@ -1213,9 +1145,9 @@ int vfk_step_scores(vf_ctx *c, int stage) {
   return VF_OK;
 }
 
-// The packed bf16 MLP as the fused kernels take it.  generating: the candidates' 64 core
-// rows are produced in the kernel, so with 256 input rows the first layer is cut down to
-// them (k0 = 4) and the other rows' weights are handed over separately (w_full).
+// The packed bf16 MLP as the fused kernels take it.  generating: the candidates' features are
+// produced in the kernel, so the first layer is cut down to the rows that depend on the
+// candidate (k-steps 1..3) and the other rows' weights are handed over separately (w_full).
 // ks / NC (nullable): row stride of the activation tile in LDS, candidates per tile.
 void vfk_fast_dev(const vf_ctx *c, bool generating, vf_fast_dev *fd, int *ks, int *NC) {
   const vf_model &m = c->model;
@@ -1226,12 +1158,14 @@ void vfk_fast_dev(const vf_ctx *c, bool generating, vf_fast_dev *fd, int *ks, in
   fd->wave_stride = c->pm.wave_stride; fd->aux = c->pm.aux; fd->wl_off = c->pm.aux_off[7];
   fd->naux = (int)(c->pm.aux_off[7] + m.dims[L - 1]);
   fd->k0 = m.dims[0] / 16;
+  fd->k0ofs = 0;
   fd->w_full = nullptr;
   fd->wave_stride_full = 0;
   if (generating && c->pm.w_stream_fold) {
     fd->w_stream = reinterpret_cast<const uint4 *>(c->pm.w_stream_fold);
     fd->wave_stride = c->pm.wave_stride_fold;
-    fd->k0 = 4;
+    fd->k0 = VF_K0_OWN;
+    fd->k0ofs = 1;
     fd->w_full = reinterpret_cast<const uint4 *>(c->pm.w_stream);
     fd->wave_stride_full = c->pm.wave_stride;
   }
@@ -1345,7 +1279,10 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     if (gen_stage >= 0) {
       int rc2 = vfk_prepare(c, gen_stage);
       if (rc2 != VF_OK) return rc2;
-      kern = wide ? k_mlp_fast<64, 4, 2, true> : narrow ? k_mlp_fast<64, 2, 4, true> : k_mlp_fast<128, 2, 4, true>;
+      if (L == 2)
+        kern = wide ? k_mlp_fast<64, 4, 2, true, true> : narrow ? k_mlp_fast<64, 2, 4, true, true> : k_mlp_fast<128, 2, 4, true, true>;
+      else
+        kern = wide ? k_mlp_fast<64, 4, 2, true> : narrow ? k_mlp_fast<64, 2, 4, true> : k_mlp_fast<128, 2, 4, true>;
     } else {
       kern = wide ? k_mlp_fast<64, 4, 2, false> : k_mlp_fast<128, 2, 4, false>;
     }

@@ -73,4 +73,150 @@ __device__ __forceinline__ void wave_min(float &v, int32_t &c) {
 __device__ __forceinline__ float sigmoid_dev(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
 __device__ __forceinline__ float tanh_dev(float z) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * z)); }
 
+// ---- pieces of the fused bf16 MLP that the per-layer scorer and the whole-schedule kernel share
+
+// k-steps (16 input rows each) of the first layer that a candidate's own rows 16..63 take
+constexpr int VF_K0_OWN = 3;
+
+// A wave's weight stream as a buffer: the base address sits in scalar registers, a lane adds
+// its own 16 bytes (voff = 16 * lane) and the fragment's position comes as a scalar byte offset,
+// so that no vector register holds an address and no vector instruction computes one.  Fragment
+// i of the stream (64 lanes x 16 bytes) starts at byte 1024 * i.
+typedef unsigned int vf_u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t stream_rsrc(const void *p) {
+  // no stride, no bound that could clip (the callers stay inside the stream), raw 32-bit format
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, -1, 0x00020000);
+}
+__device__ __forceinline__ uint4 stream_load(__amdgpu_buffer_rsrc_t rs, int voff, int frag) {
+  return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(rs, voff, frag * 1024, 0));
+}
+
+// The first layer's product with the input rows that all candidates of a decision share, once
+// per decision: the same contraction as for the candidates, with the shared vector in every
+// column of one column tile, over k-steps 0 and 3 of the whole first layer (rows 0..15, and
+// rows 48..63 with the candidates' own rows zero) and, with 256 inputs, k-steps 4..15 (rows
+// 64..255).  Column 0 of the result plus the layer's bias is what the candidates'
+// accumulators start from.  wf: this wave's fragments of the whole stream; stat:
+// DecPack::stat; wide: 256 input rows.  Every wave of the workgroup calls it for its RT row tiles.
+template <int RT>
+__device__ __forceinline__ void fold_bias(__amdgpu_buffer_rsrc_t wf, const uint32_t *stat, bool wide, int w, int lane,
+                                          const float *bias_in, float *bias_out) {
+  floatx16 fa[RT];
+#pragma unroll
+  for (int r = 0; r < RT; ++r)
+#pragma unroll
+    for (int q = 0; q < 16; ++q) fa[r][q] = 0.0f;
+  const int n = wide ? 14 : 2;
+#pragma unroll 2
+  for (int q = 0; q < n; ++q) {
+    const int sk = q == 0 ? 0 : q + 2;  // k-step of the whole first layer: 0, 3, 4, 5, ...
+    uint4 a[RT];
+#pragma unroll
+    for (int r = 0; r < RT; ++r) a[r] = stream_load(wf, 16 * lane, sk * RT + r);
+    const uint32_t *xb = stat + 8 * q + 4 * (lane >> 5);
+    uint4 bv;
+    bv.x = xb[0]; bv.y = xb[1]; bv.z = xb[2]; bv.w = xb[3];
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+      fa[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[r]), __builtin_bit_cast(bf16x8, bv),
+                                                     fa[r], 0, 0, 0);
+  }
+  if ((lane & 31) == 0) {
+#pragma unroll
+    for (int r = 0; r < RT; ++r) {
+      const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+      for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bias_out[mbase + 8 * g + e] = bias_in[mbase + 8 * g + e] + fa[r][4 * g + e];
+    }
+  }
+}
+
+// The contraction of one layer for a wave: RT row tiles x CT column tiles of 32 x 32, weights
+// (A operand) from a ring of PD k-steps of fragments in registers, activations (B operand) from
+// LDS one k-step ahead.  One memory instruction behind each product, so that a wave that has its
+// SIMD's matrix core to itself never leaves it waiting for the issue of a burst of loads: behind
+// the first CT products the activation fragments of the next k-step (one step past the end stays
+// inside LDS), behind the last product that reads a weight fragment its refill, in place, PD
+// k-steps ahead of its next use - so only the oldest slot is ever waited for.
+//
+// ws: the wave's weight stream; k-step n of a tile (its layers' k-steps counted through) is
+// fragments n * RT .. n * RT + RT - 1 of it and lives in ring slot n % PD; a layer that starts
+// at step n0 passes ROT = n0 % PD and wstep = n0 + PD, the step that refills the first slot
+// (advanced as the loop goes).  ksteps is a multiple of PD.  wrap: the last PD steps are a
+// tile's last ones and refill their slots with the next tile's first PD steps (step m into slot m).
+// bb: this lane's B operand base (column lane & 31 of column tile 0, k half lane >> 5), cstride:
+// elements between column tiles; consecutive k-steps are 16 elements apart.
+template <int RT, int CT, int PD, int ROT>
+__device__ __forceinline__ void contract_layer(floatx16 (&acc)[RT][CT], uint4 (&ring)[PD][RT],
+                                               __amdgpu_buffer_rsrc_t ws, int &wstep, int voff, bool wrap, int ksteps,
+                                               const uint16_t *bb, int cstride) {
+  uint4 bcur[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(bb + (size_t)c * cstride);
+  // Nothing but this loop's own loads may be in flight when it starts: with a store to scratch
+  // or a scalar load still counted, the compiler can no longer tell the order in which the
+  // counters come down and waits for every load at the top of each round instead of for the
+  // oldest one.  (vmcnt 0, lgkmcnt 0; the ring's loads were issued long before.)
+  __builtin_amdgcn_s_waitcnt(0x0070);
+  for (int s0 = 0; s0 < ksteps; s0 += PD) {
+    const bool last = wrap && s0 + PD >= ksteps;
+#pragma unroll
+    for (int j = 0; j < PD; ++j) {
+      const int slot = (ROT + j) % PD;
+      const int frag = (last ? slot : wstep + j) * RT;
+      uint4 bnext[CT];
+#pragma unroll
+      for (int i = 0; i < RT * CT; ++i) {
+        const int r = i / CT, c = i % CT;
+        acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[slot][r]),
+                                                           __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
+        if (i < CT) bnext[i] = *reinterpret_cast<const uint4 *>(bb + (size_t)i * cstride + (s0 + j + 1) * 16);
+        if (i >= CT && c == 0) ring[slot][r - 1] = stream_load(ws, voff, frag + r - 1);
+        if (i == RT * CT - 1) ring[slot][RT - 1] = stream_load(ws, voff, frag + RT - 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+#pragma unroll
+      for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
+    }
+    wstep += PD;
+  }
+}
+
+// The first layer over a candidate's own rows: VF_K0_OWN k-steps, steps 0.. of the tile; slot
+// n % PD is refilled with step n + PD of the tile.  ONLY: the network has no other hidden
+// layer, so these steps are the whole tile - a slot is then refilled with the step that uses it
+// next, in this tile or in the next one (possibly the very step it holds: the same fragments
+// tile after tile).
+template <int RT, int CT, int PD, bool ONLY>
+__device__ __forceinline__ void contract_own_rows(floatx16 (&acc)[RT][CT], uint4 (&ring)[PD][RT],
+                                                  __amdgpu_buffer_rsrc_t ws, int voff, const uint16_t *bb,
+                                                  int cstride) {
+  uint4 bcur[CT];
+#pragma unroll
+  for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(bb + (size_t)c * cstride);
+  __builtin_amdgcn_s_waitcnt(0x0070);
+#pragma unroll
+  for (int n = 0; n < VF_K0_OWN; ++n) {
+    const int slot = n % PD;
+    const int next = (!ONLY || n + PD < VF_K0_OWN) ? n + PD : slot;
+    uint4 bnext[CT];
+#pragma unroll
+    for (int i = 0; i < RT * CT; ++i) {
+      const int r = i / CT, c = i % CT;
+      acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[slot][r]),
+                                                         __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
+      if (i < CT && n + 1 < VF_K0_OWN) bnext[i] = *reinterpret_cast<const uint4 *>(bb + (size_t)i * cstride + (n + 1) * 16);
+      if (i >= CT && c == 0) ring[slot][r - 1] = stream_load(ws, voff, next * RT + r - 1);
+      if (i == RT * CT - 1) ring[slot][RT - 1] = stream_load(ws, voff, next * RT + RT - 1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (n + 1 < VF_K0_OWN) {
+#pragma unroll
+      for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
+    }
+  }
+}
+
 #endif  // VF_SCORE_DEV_H

@@ -8,8 +8,8 @@
 // The MLP is the same contraction as in the per-layer scorer: weights are the MFMA A
 // operand and stream from L2 through a ring of registers, activations are the B operand
 // in LDS, a wave owns RT row tiles of every hidden layer and all NC / 32 column tiles.
-// What differs is the tile pipeline.  The features of a tile (the 64 core rows; the other
-// 192 rows are the same for all candidates of a decision and enter as a bias, see below)
+// What differs is the tile pipeline.  The features of a tile (rows 16..63 of the input; all
+// other rows are the same for all candidates of a decision and enter as a bias, see below)
 // go to an input buffer of their own, so the first layer does not have to share the
 // activation buffer with the layers behind it, and they are produced one tile ahead:
 // waves 4..7 evaluate the next tile's candidates before their share of the last hidden
@@ -39,10 +39,10 @@ namespace {
 // finished its own problems (or never had one) becomes a helper: it queues up in a pool.
 // An owner that starts a layer with enough tiles takes up to VF_MAX_HELPERS workgroups out
 // of the pool and sends each of them the layer (problem, layer, team size, member index)
-// through its mailbox; the helper builds the layer's context from the tables the owner's
-// commits have left in memory, scores tiles member, member + team, ..., publishes its
-// minimum, reports its arrival and queues up again - it neither waits for anybody nor
-// commits.  The owner waits (bounded) for the arrivals of the helpers it sent for and commits
+// through its mailbox; the helper fetches what the owner has worked out for the layer and
+// left in memory (decision context, quotient tables, folded bias, the candidate list),
+// scores tiles member, member + team, ..., publishes its minimum, reports its arrival and
+// queues up again - it neither waits for anybody nor commits.  The owner waits (bounded) for the arrivals of the helpers it sent for and commits
 // alone.  The grid is one workgroup per compute unit, so every workgroup that is waited
 // for is resident; helpers leave when every problem is done.
 struct WholeArgs {
@@ -62,7 +62,15 @@ struct WholeArgs {
   unsigned int *pool;                // [0] entries taken, [1] entries put, [2] problems done
   unsigned int *pool_q;              // [VF_POOL_SLOTS] workgroup id + 1 of a queued helper, 0 = empty
   unsigned long long *mailbox;       // [grid] the layer a helper is sent: see mail_pack
+  uint32_t *pub;                     // [nprob][VF_PUB_WORDS] what an owner leaves for its helpers: the layer's
+                                     // decision context, quotient tables, folded bias and candidate count
 };
+// words of an owner's published layer: DecPack, EvalTabs, first-layer bias (up to 1024 rows), count
+constexpr int VF_PUB_TABS = VF_DECPACK_DWORDS;
+constexpr int VF_PUB_BIAS = VF_PUB_TABS + (int)(sizeof(EvalTabs) / 4);
+constexpr int VF_PUB_COUNT = VF_PUB_BIAS + 1024;
+constexpr int VF_PUB_WORDS = VF_PUB_COUNT + 4;
+constexpr int VF_XIN_STRIDE = 56;  // elements between the columns of the input buffer (48 used)
 constexpr int VF_MAX_HELPERS = 3;
 constexpr int VF_POOL_SLOTS = 1024;       // more than the workgroups of a launch
 constexpr int VF_TILES_PER_MEMBER = 4;    // a helper is sent for when every member gets at least this many tiles
@@ -76,16 +84,18 @@ __device__ __forceinline__ unsigned long long mail_pack(int unit, int stage, int
 // NC candidates per tile, RT row tiles per wave (hidden width 256 * RT), PD k-steps of
 // weight fragments in flight per wave.  stat: nullable, [0] += candidates pushed through
 // the network, [1] += valid ones (the same here: only valid ids are listed).
-template <int NC, int RT, int PD>
+// ONE: the network has a single hidden layer (otherwise two).
+template <int NC, int RT, int PD, bool ONE>
 __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M, int nprob,
                                                unsigned long long *stat, NoiseArgs na, WholeArgs wa) {
   constexpr int CT = NC / 32;
   constexpr int NWS = NC / 64;  // waves that scan the tile's scores: wave w owns columns 64 w ...
+  constexpr int XS = VF_XIN_STRIDE;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t *act = reinterpret_cast<uint16_t *>(smem);          // [NC][ks] hidden activations
-  uint16_t *xin = act + (size_t)NC * ks;                       // [NC][64] the tile's core rows, 16-byte
-                                                               // chunk q of column n at chunk q ^ ((n >> 1) & 7)
-  float *red = reinterpret_cast<float *>(xin + (size_t)NC * 64);  // [8][NC] partial output dots
+  uint16_t *xin = act + (size_t)NC * ks;                       // [NC][XS] rows 16..63 of the tile's candidates
+                                                               // (48 values, columns 112 bytes apart)
+  float *red = reinterpret_cast<float *>(xin + (size_t)NC * XS);  // [8][NC] partial output dots
   int32_t *okf = reinterpret_cast<int32_t *>(red + 8 * NC);    // [2][NC] candidate id + 1 of a valid column, else 0
   float *auxs = reinterpret_cast<float *>(okf + 2 * NC);       // biases; output vector as bfloat16 pairs
   __shared__ DecPack pk;
@@ -94,10 +104,10 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
   __shared__ float sv[NWS];      // per scanning wave: the minimum over its columns at the end of a layer
   __shared__ int32_t sc[NWS];
   __shared__ unsigned int sn[2];  // what the layer counted (candidates, valid ones)
-  // with 256 input rows, rows 64..255 are the same for all candidates of a decision
-  // (neighbour stages): their part of the first layer is a per-decision bias, which
-  // replaces the layer's bias in LDS, and the contraction runs over the 64 core rows only
-  const bool fold = md.w_full != nullptr;
+  // Only rows 16..55 and 59 of the network's input depend on the candidate; the part of the
+  // first layer that belongs to all the other rows (intrinsic block, context rows, with 256
+  // inputs the neighbour stages) is a per-decision bias, which replaces the layer's bias in
+  // LDS, and the contraction runs over rows 16..63 with zeros in the shared rows among them
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -108,14 +118,15 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
   for (int i = tid; i < (int)md.wl_off; i += 512) auxs[i] = md.aux[i];
   for (int i = tid; i < md.dims[NH] / 2; i += 512)
     reinterpret_cast<uint32_t *>(auxs + md.wl_off)[i] = pack_bf16(md.aux[md.wl_off + 2 * i], md.aux[md.wl_off + 2 * i + 1]);
-  const uint4 *const wbase = md.w_stream + (size_t)w * md.wave_stride + lane;
-  const uint4 *wp = wbase;
+  const __amdgpu_buffer_rsrc_t ws = stream_rsrc(md.w_stream + (size_t)w * md.wave_stride);
+  const __amdgpu_buffer_rsrc_t wf = stream_rsrc(md.w_full + (size_t)w * md.wave_stride_full);
+  const int voff = 16 * lane;
+  int wstep = 0;
   uint4 ring[PD][RT];
 #pragma unroll
   for (int j = 0; j < PD; ++j)
 #pragma unroll
-    for (int r = 0; r < RT; ++r) ring[j][r] = wp[(j * RT + r) * 64];
-  wp += PD * RT * 64;
+    for (int r = 0; r < RT; ++r) ring[j][r] = stream_load(ws, voff, j * RT + r);
 
   if (tid == 0) team_failed = 0;
   // what this workgroup does next: a layer of one of its own problems (owner), or a layer it
@@ -137,7 +148,9 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
         const unsigned int slot = atomicAdd(&wa.pool[1], 1u);
         __hip_atomic_store(&wa.pool_q[slot % VF_POOL_SLOTS], (unsigned int)blockIdx.x + 1u, __ATOMIC_RELAXED,
                            __HIP_MEMORY_SCOPE_AGENT);
-        unsigned int spins = 0;
+        // (the bound counts rounds without any problem finishing anywhere: a launch that is merely
+        // long - very many problems, a GPU shared with other work - does not run it out)
+        unsigned int spins = 0, seen_done = 0;
         for (;;) {
           const unsigned long long m = __hip_atomic_load(&wa.mailbox[blockIdx.x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
           if (m != 0ull) {
@@ -147,7 +160,9 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
             __hip_atomic_store(&wa.mailbox[blockIdx.x], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             break;
           }
-          if (__hip_atomic_load(&wa.pool[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= (unsigned int)nprob) break;
+          const unsigned int done = __hip_atomic_load(&wa.pool[2], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          if (done >= (unsigned int)nprob) break;
+          if (done != seen_done) { seen_done = done; spins = 0; }
           if (++spins > wa.wait_rounds) { team_failed = 1; wa.team_err[0] = 1; break; }
           __builtin_amdgcn_s_sleep(8);
         }
@@ -159,16 +174,24 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       unit = job_unit; stage = job_stage; team = job_team; member = job_member;
     }
     uint32_t *const idlist = wa.list + (size_t)unit * wa.Mpad;
-    build_dec(pk.d, pk.sp, wa.t, unit, stage);
     na.stage = stage;
+    __shared__ int ncand, g_npairs;
+    __shared__ unsigned int job_helper[VF_MAX_HELPERS];
+    uint32_t *const pub = wa.pub + (size_t)unit * VF_PUB_WORDS;
+    if (helping) {
+      // the owner has left the layer in memory before it sent the mail
+      for (int i = tid; i < VF_DECPACK_DWORDS; i += 512) reinterpret_cast<uint32_t *>(&pk)[i] = pub[i];
+      for (int i = tid; i < (int)(sizeof(EvalTabs) / 4); i += 512) reinterpret_cast<uint32_t *>(&tabs)[i] = pub[VF_PUB_TABS + i];
+      for (int i = tid; i < md.dims[1]; i += 512) auxs[md.bias_off[0] + i] = __uint_as_float(pub[VF_PUB_BIAS + i]);
+      if (tid == 0) ncand = (int)pub[VF_PUB_COUNT];
+      __syncthreads();
+    } else {
+    build_dec(pk.d, pk.sp, wa.t, unit, stage);
     // three small jobs side by side, on different waves: the quotient tables (waves 0, 1), the
-    // neighbour rows as the first layer wants them (waves 2, 3), the split factors that fit
+    // shared input rows as the first layer wants them (waves 2, 3), the split factors that fit
     // (wave 4)
     fill_evaltabs(tabs, pk.d, pk.sp);
-    if (tid >= 128 && tid < 224) {
-      const int q = tid - 128;
-      pk.nbh[q] = pack_bf16(plog2_dev(pk.d.nb[2 * q]), plog2_dev(pk.d.nb[2 * q + 1]));
-    }
+    if (tid >= 128 && tid < 128 + VF_STAT_WORDS) pk.stat[tid - 128] = stat_word(pk.d, tid - 128);
     // Ordered list of the decision's valid ids, written down directly from the validity
     // rules: per (compute_at, store_at) digit pair that is open - the level is offered and
     // the hoist does not exceed it - the valid ids are the products of the split factors
@@ -176,7 +199,6 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     // an inlining pair has the single id with every other digit zero.  The list holds the
     // digits, packed, rather than the id: the evaluation works on digits, and putting an id
     // together takes a few multiplications where taking it apart takes as many divisions.
-    __shared__ int ncand, g_npairs;
     __shared__ int g_pos[13], g_cat[12], g_dec[12];
     __shared__ int g_nok[3][3], g_ok[3][3][8];
     __shared__ float g_rcp[3][3];  // 1 / g_nok, for div_small
@@ -225,42 +247,8 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
         ncand = pos;
       }
     }
-    if (fold) {
-      // the first layer's product with the 192 rows that all candidates of the decision
-      // share, once per decision: the same contraction with the shared vector in every
-      // column (twelve k-steps, one column tile); column 0 of the result plus the layer's
-      // bias is what the candidates' accumulators start from
-      floatx16 fa[RT];
-#pragma unroll
-      for (int r = 0; r < RT; ++r)
-#pragma unroll
-        for (int q = 0; q < 16; ++q) fa[r][q] = 0.0f;
-      const uint4 *wf = md.w_full + (size_t)w * md.wave_stride_full + lane + (size_t)4 * RT * 64;
-#pragma unroll 4
-      for (int sk = 0; sk < 12; ++sk) {
-        uint4 a[RT];
-#pragma unroll
-        for (int r = 0; r < RT; ++r) a[r] = wf[((size_t)sk * RT + r) * 64];
-        const uint32_t *xb = pk.nbh + 8 * sk + 4 * (lane >> 5);
-        uint4 bv;
-        bv.x = xb[0]; bv.y = xb[1]; bv.z = xb[2]; bv.w = xb[3];
-#pragma unroll
-        for (int r = 0; r < RT; ++r)
-          fa[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[r]),
-                                                         __builtin_bit_cast(bf16x8, bv), fa[r], 0, 0, 0);
-      }
-      if ((lane & 31) == 0) {
-#pragma unroll
-        for (int r = 0; r < RT; ++r) {
-          const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
-#pragma unroll
-          for (int g = 0; g < 4; ++g)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              auxs[md.bias_off[0] + mbase + 8 * g + e] = md.aux[md.bias_off[0] + mbase + 8 * g + e] + fa[r][4 * g + e];
-        }
-      }
-    }
+    fold_bias<RT>(wf, pk.stat, md.dims[0] == 256, w, lane,
+                  md.aux + md.bias_off[0], auxs + md.bias_off[0]);
     __syncthreads();  // the pairs are numbered, the bias is complete
     // (the pairs' first positions into registers: the pair of an entry is then found without
     // a chain of dependent reads)
@@ -287,9 +275,14 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       }
       idlist[k] = dec;
     }
-    if (wa.helpers && !helping) {
-      // owner: with enough tiles, take helpers out of the pool and send them this layer
+    if (wa.helpers) {
+      // owner: what a helper needs of this layer goes to memory (the list is there already) ...
+      for (int i = tid; i < VF_DECPACK_DWORDS; i += 512) pub[i] = reinterpret_cast<const uint32_t *>(&pk)[i];
+      for (int i = tid; i < (int)(sizeof(EvalTabs) / 4); i += 512) pub[VF_PUB_TABS + i] = reinterpret_cast<const uint32_t *>(&tabs)[i];
+      for (int i = tid; i < md.dims[1]; i += 512) pub[VF_PUB_BIAS + i] = __float_as_uint(auxs[md.bias_off[0] + i]);
+      // ... and, with enough tiles, up to VF_MAX_HELPERS workgroups are taken out of the pool
       if (tid == 0) {
+        pub[VF_PUB_COUNT] = (uint32_t)ncand;
         int n = 0;
         int want = (ncand + NC - 1) / NC / VF_TILES_PER_MEMBER - 1;
         if (want > VF_MAX_HELPERS) want = VF_MAX_HELPERS;
@@ -309,8 +302,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
             }
             if (id == 0u) break;
             __hip_atomic_store(q, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(&wa.mailbox[id - 1u], mail_pack(unit, stage, take + 1, i + 1), __ATOMIC_RELAXED,
-                               __HIP_MEMORY_SCOPE_AGENT);
+            job_helper[i] = id - 1u;
           }
           n = take;
         }
@@ -318,25 +310,38 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
         owner_target += (unsigned int)n;
       }
     }
+    }  // (not helping)
     __syncthreads();  // the id list (written by this workgroup) is complete
     if (team_failed) return;
-    if (wa.helpers && !helping) team = job_team;
+    if (wa.helpers && !helping) {
+      team = job_team;
+      if (team > 1) {
+        // the helpers are sent for once everything this workgroup has written for them has
+        // arrived in memory: every thread waits for its own stores, then thread 0 sends the mail
+        __threadfence();
+        __syncthreads();
+        if (tid == 0)
+          for (int i = 0; i + 1 < team; ++i)
+            __hip_atomic_store(&wa.mailbox[job_helper[i]], mail_pack(unit, stage, team, i + 1), __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
     const int ncands = ncand;
     const int ntiles = (ncands + NC - 1) / NC;
 
     // Thread tid evaluates the candidate of column tid % NC of the tile that starts at list
-    // entry nb and stores its share of the 64 core rows, normalised, as bf16: part 0 rows
-    // 0..15 and 40..47, part 1 rows 16..31, part 2 rows 32..39 and 56..63, part 3 rows
-    // 48..55 - dealt out so that the four copies cost about the same (rows 0..15 and 56..63
-    // are copies of the context, 48..55 the dearest); the rows a part does not store are
-    // dead code in its copy of the evaluation.  Padding columns evaluate id 0 and store zeros.
+    // entry nb and stores its share of rows 16..63, normalised, as bf16 (8 rows = one 16-byte
+    // chunk): part 0 rows 16..31, part 1 rows 32..39 and 56..63 (of which only row 59 is the
+    // candidate's own: the others belong to the bias and stay zero), part 2 rows 40..47, part
+    // 3 rows 48..55 - dealt out so that the four copies cost about the same; the rows a part
+    // does not store are dead code in its copy of the evaluation.  Padding columns evaluate id
+    // 0 and store zeros.
     auto featurize = [&](int nb, int par) __attribute__((always_inline)) {
       const int n = tid % NC, part = tid / NC;
       const bool inb = (nb + n) < ncands;
       const Digits dg = unpack_digits(inb ? idlist[nb + n] : 0u);
       int32_t core[64];
-      uint16_t *const col = xin + (size_t)n * 64;
-      const int sw = (n >> 1) & 7;
+      uint16_t *const col = xin + (size_t)n * XS;
       auto put8 = [&](const int32_t *v, int chunk) {
         uint4 q;
         q.x = pack_bf16(plog2_dev(v[0]), plog2_dev(v[1]));
@@ -344,178 +349,175 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
         q.z = pack_bf16(plog2_dev(v[4]), plog2_dev(v[5]));
         q.w = pack_bf16(plog2_dev(v[6]), plog2_dev(v[7]));
         if (!inb) q = make_uint4(0u, 0u, 0u, 0u);
-        *reinterpret_cast<uint4 *>(col + ((chunk ^ sw) << 3)) = q;
+        *reinterpret_cast<uint4 *>(col + (chunk << 3)) = q;
       };
       if (part == 0) {
         // evaluated for padding ids too: core must be defined before it is packed
         const bool valid = eval_digits<true>(pk.d, pk.sp, dg, &tabs, core);
         okf[par * NC + n] = (inb && valid) ? (int32_t)id_of(pk.sp, dg) + 1 : 0;
-        put8(core, 0);
-        put8(core + 8, 1);
-        put8(core + 40, 5);
+        put8(core + 16, 0);
+        put8(core + 24, 1);
       } else if (part == 1) {
         eval_digits<true>(pk.d, pk.sp, dg, &tabs, core);
-        put8(core + 16, 2);
-        put8(core + 24, 3);
+        put8(core + 32, 2);
+        *reinterpret_cast<uint4 *>(col + 40) = make_uint4(0u, inb ? pack_bf16(0.0f, plog2_dev(core[59])) : 0u, 0u, 0u);
       } else if (part == 2) {
         eval_digits<true>(pk.d, pk.sp, dg, &tabs, core);
-        put8(core + 32, 4);
-        put8(core + 56, 7);
+        put8(core + 40, 3);
       } else if (part == 3) {
         eval_digits<true>(pk.d, pk.sp, dg, &tabs, core);
-        put8(core + 48, 6);
+        put8(core + 48, 4);
       }
     };
 
     // Waves below NWS scan the scores: thread tid keeps the incumbent of column tid over the
     // tiles of the layer (and counts, candidates in the low half, valid ones in the high half),
-    // the columns are reduced once per layer.
+    // the columns are reduced once per layer.  Behind the barrier that ends a tile these
+    // threads only add up their column's partial dots; the rest of the scan - noise, the
+    // comparison with the incumbent - waits until they have nothing else to do: the end of
+    // their part of the next tile, where they would otherwise wait for the other waves.
     float col_v = __builtin_inff();
     int32_t col_c = -1;
     unsigned int col_n = 0u;
+    float pend_s = 0.0f;     // a tile's score of this thread's column that has not been scanned yet
+    int32_t pend_flag = -1;  // its candidate id + 1, 0 = not a valid column, -1 = nothing pending
+    auto scan_pending = [&]() __attribute__((always_inline)) {
+      if (pend_flag < 0) return;
+      float sv_ = pend_s;
+      const int32_t colid = pend_flag - 1;
+      if (pend_flag != 0) {
+        if (na.eps != 0.0f) sv_ = add_noise(na, sv_, unit, colid);
+        // (+inf and NaN never win: Algorithm 1 compares with a strict "<" from +inf)
+        if (sv_ < __builtin_inff()) take_min(col_v, col_c, sv_, colid);
+      }
+      pend_flag = -1;
+    };
     if (tid == 0) sn[0] = sn[1] = 0u;
+    const uint16_t *const bx = xin + (size_t)(lane & 31) * XS + 8 * (lane >> 5);
+    const uint16_t *const ba = act + (size_t)(lane & 31) * ks + 8 * (lane >> 5);
+    // the accumulators start from the bias of their output row
+    auto start_from_bias = [&](floatx16 (&acc)[RT][CT], const float *bias) __attribute__((always_inline)) {
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+        const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
+#pragma unroll
+          for (int c = 0; c < CT; ++c) {
+            acc[r][c][4 * g + 0] = bv.x; acc[r][c][4 * g + 1] = bv.y;
+            acc[r][c][4 * g + 2] = bv.z; acc[r][c][4 * g + 3] = bv.w;
+          }
+        }
+      }
+    };
+    // a hidden layer's output becomes the next one's input: rounded to bfloat16, ReLU on the
+    // pairs; the two lane halves then trade their row groups so that every lane writes 8
+    // consecutive rows of its column at once
+    auto write_back = [&](floatx16 (&acc)[RT][CT]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+        const int m0 = (w + r * 8) * 32 + 8 * (lane >> 5);
+#pragma unroll
+        for (int g = 0; g < 4; g += 2) {
+#pragma unroll
+          for (int c = 0; c < CT; ++c) {
+            uint32_t x0 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 0], acc[r][c][4 * g + 1]));
+            uint32_t x1 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 2], acc[r][c][4 * g + 3]));
+            uint32_t y0 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 4], acc[r][c][4 * g + 5]));
+            uint32_t y1 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 6], acc[r][c][4 * g + 7]));
+            swap_halves(x0, y0);
+            swap_halves(x1, y1);
+            *reinterpret_cast<uint4 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + m0 + 8 * g) = make_uint4(x0, x1, y0, y1);
+          }
+        }
+      }
+    };
+    // the last hidden layer is never written back: rounded to bf16, it is multiplied with the
+    // output vector at once
+    auto output_dots = [&](floatx16 (&acc)[RT][CT], float (&dot)[CT]) __attribute__((always_inline)) {
+      const uint32_t *wl = reinterpret_cast<const uint32_t *>(auxs + md.wl_off);
+#pragma unroll
+      for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
+#pragma unroll
+      for (int r = 0; r < RT; ++r) {
+        const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const uint2 wpair = *reinterpret_cast<const uint2 *>(wl + (mbase + 8 * g) / 2);
+          float4 wv;
+          wv.x = __uint_as_float(wpair.x << 16); wv.y = __uint_as_float(wpair.x & 0xffff0000u);
+          wv.z = __uint_as_float(wpair.y << 16); wv.w = __uint_as_float(wpair.y & 0xffff0000u);
+#pragma unroll
+          for (int c = 0; c < CT; ++c) {
+            uint32_t q0 = pack_bf16(relu_bits(acc[r][c][4 * g + 0]), relu_bits(acc[r][c][4 * g + 1]));
+            uint32_t q1 = pack_bf16(relu_bits(acc[r][c][4 * g + 2]), relu_bits(acc[r][c][4 * g + 3]));
+            float d = dot[c];
+            d = fmaf(__uint_as_float(q0 << 16), wv.x, d);
+            d = fmaf(__uint_as_float(q0 & 0xffff0000u), wv.y, d);
+            d = fmaf(__uint_as_float(q1 << 16), wv.z, d);
+            d = fmaf(__uint_as_float(q1 & 0xffff0000u), wv.w, d);
+            dot[c] = d;
+          }
+        }
+      }
+    };
+
     // the loop starts one tile early: that round only produces the first tile's features
     int par = 1;
     for (int t = member - team; t < ntiles; t += team, par ^= 1) {
       const bool real = t >= member;
       const bool has_next = t + team < ntiles;
       float dot[CT];
-      for (int l = 0; l < NH; ++l) {
-        const bool lastl = l == NH - 1;
-        // with a single hidden layer the next tile's features would land in the buffer this
-        // very layer reads: then every wave finishes the layer first
-        const bool feat_first = NH > 1 && w >= 4;
-        for (int ph = 0; ph < (lastl ? 2 : 1); ++ph) {
-          if (lastl && (ph == 0) == feat_first) {
-            if (NH == 1) __syncthreads();
+      // ---- first layer, over the candidates' own rows in the input buffer.  (The matrix
+      // loops go first on their SIMD: the other wave's vector work fills the gaps.)
+      if constexpr (ONE) {
+        // a single hidden layer: its output goes straight into the output dots; the next
+        // tile's features land in the buffer that the layer has read, so every wave finishes
+        // the layer first
+        if (real) {
+          floatx16 acc[RT][CT];
+          start_from_bias(acc, auxs + md.bias_off[0]);
+          __builtin_amdgcn_s_setprio(2);
+          contract_own_rows<RT, CT, PD, true>(acc, ring, ws, voff, bx, 32 * XS);
+          __builtin_amdgcn_s_setprio(0);
+          output_dots(acc, dot);
+        }
+        __syncthreads();
+        if (has_next) featurize((t + team) * NC, par ^ 1);
+      } else {
+        if (real) {
+          floatx16 acc[RT][CT];
+          start_from_bias(acc, auxs + md.bias_off[0]);
+          __builtin_amdgcn_s_setprio(2);
+          contract_own_rows<RT, CT, PD, false>(acc, ring, ws, voff, bx, 32 * XS);
+          __builtin_amdgcn_s_setprio(0);
+          wstep = VF_K0_OWN + PD;
+          // (nobody reads the activations of the tile before any more: barrier behind its dots)
+          write_back(acc);
+          __syncthreads();
+        }
+        // ---- last hidden layer and the output dots; the next tile's features.  Waves 4..7
+        // produce their share of the features before the layer, waves 0..3 after it, so that
+        // on every SIMD one wave's integer work runs under the other wave's matrix work.  The
+        // last PD steps of the contraction prefetch the first PD steps of the next tile.
+        for (int ph = 0; ph < 2; ++ph) {
+          if ((ph == 0) == (w >= 4)) {
             if (has_next) featurize((t + team) * NC, par ^ 1);
             continue;
           }
           if (!real) continue;
-          const int ksteps = l == 0 ? md.k0 : md.dims[l] / 16;
-          // the accumulators start from the bias of their output row
-          const float *bias = auxs + md.bias_off[l];
           floatx16 acc[RT][CT];
-#pragma unroll
-          for (int r = 0; r < RT; ++r) {
-            const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-              const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
-#pragma unroll
-              for (int c = 0; c < CT; ++c) {
-                acc[r][c][4 * g + 0] = bv.x; acc[r][c][4 * g + 1] = bv.y;
-                acc[r][c][4 * g + 2] = bv.z; acc[r][c][4 * g + 3] = bv.w;
-              }
-            }
-          }
-          // The contraction.  One memory instruction behind each product, so that a wave
-          // that has its SIMD's matrix core to itself never leaves it waiting for the issue
-          // of a burst of loads: behind the first CT products the activation fragments of
-          // the next k-step (one step past the end stays inside LDS), behind the last
-          // product that reads a weight fragment its refill, in place, PD k-steps ahead of
-          // its next use - so only the oldest slot is ever waited for.  The last PD steps of
-          // a tile prefetch the first PD steps of the next one.
-          {
-            // B operand of this lane: column (lane & 31) of a column tile, k half lane >> 5; the
-            // first layer reads the input buffer (chunks swapped around by column), the others
-            // the activations
-            const bool first = l == 0;
-            const uint16_t *const bb = first ? xin + (size_t)(lane & 31) * 64 : act + (size_t)(lane & 31) * ks;
-            const int cstride = first ? 32 * 64 : 32 * ks;
-            const int h8 = 8 * (lane >> 5), xorv = first ? (((lane & 31) >> 1) & 7) << 3 : 0;
-            auto bfrag = [&](int c, int s) -> const uint4 * {
-              return reinterpret_cast<const uint4 *>(bb + (size_t)c * cstride + ((s * 16 + h8) ^ xorv));
-            };
-            uint4 bcur[CT];
-#pragma unroll
-            for (int c = 0; c < CT; ++c) bcur[c] = *bfrag(c, 0);
-            // Nothing but this loop's own loads may be in flight when it starts: with a store to
-            // scratch or a scalar load still counted, the compiler can no longer tell the order
-            // in which the counters come down and waits for every load at the top of each round
-            // instead of for the oldest one.  (vmcnt 0, lgkmcnt 0; the ring's loads were issued
-            // a tile ago.)
-            __builtin_amdgcn_s_waitcnt(0x0070);
-            // the matrix loop goes first on its SIMD: the other wave's vector work fills the gaps
-            __builtin_amdgcn_s_setprio(2);
-            for (int s0 = 0; s0 < ksteps; s0 += PD) {
-              if (lastl && s0 + PD >= ksteps) wp = wbase;
-#pragma unroll
-              for (int j = 0; j < PD; ++j) {
-                uint4 bnext[CT];
-#pragma unroll
-                for (int i = 0; i < RT * CT; ++i) {
-                  const int r = i / CT, c = i % CT;
-                  acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                      __builtin_bit_cast(bf16x8, ring[j][r]), __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
-                  if (i < CT) bnext[i] = *bfrag(i, s0 + j + 1);
-                  if (i >= CT && c == 0) ring[j][r - 1] = wp[(r - 1) * 64];
-                  if (i == RT * CT - 1) ring[j][RT - 1] = wp[(RT - 1) * 64];
-                  __builtin_amdgcn_sched_barrier(0);
-                }
-                wp += RT * 64;
-#pragma unroll
-                for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
-              }
-            }
-            __builtin_amdgcn_s_setprio(0);
-          }
-
-          if (!lastl) {
-            // every wave has read the layer's input before it is overwritten: the first
-            // layer reads the input buffer, and nobody reads the activations of the tile
-            // before any more (barrier behind its output dots)
-            if (l > 0) __syncthreads();
-            // rounded to bfloat16, ReLU on the pairs; the two lane halves then trade their row
-            // groups so that every lane writes 8 consecutive rows of its column at once
-#pragma unroll
-            for (int r = 0; r < RT; ++r) {
-              const int m0 = (w + r * 8) * 32 + 8 * (lane >> 5);
-#pragma unroll
-              for (int g = 0; g < 4; g += 2) {
-#pragma unroll
-                for (int c = 0; c < CT; ++c) {
-                  uint32_t x0 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 0], acc[r][c][4 * g + 1]));
-                  uint32_t x1 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 2], acc[r][c][4 * g + 3]));
-                  uint32_t y0 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 4], acc[r][c][4 * g + 5]));
-                  uint32_t y1 = relu_bf16x2(pack_bf16(acc[r][c][4 * g + 6], acc[r][c][4 * g + 7]));
-                  swap_halves(x0, y0);
-                  swap_halves(x1, y1);
-                  *reinterpret_cast<uint4 *>(act + (size_t)(c * 32 + (lane & 31)) * ks + m0 + 8 * g) = make_uint4(x0, x1, y0, y1);
-                }
-              }
-            }
-            __syncthreads();
-          } else {
-            // last hidden layer: round to bf16 and multiply with the output vector at once
-            const uint32_t *wl = reinterpret_cast<const uint32_t *>(auxs + md.wl_off);
-#pragma unroll
-            for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
-#pragma unroll
-            for (int r = 0; r < RT; ++r) {
-              const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
-#pragma unroll
-              for (int g = 0; g < 4; ++g) {
-                const uint2 wpair = *reinterpret_cast<const uint2 *>(wl + (mbase + 8 * g) / 2);
-                float4 wv;
-                wv.x = __uint_as_float(wpair.x << 16); wv.y = __uint_as_float(wpair.x & 0xffff0000u);
-                wv.z = __uint_as_float(wpair.y << 16); wv.w = __uint_as_float(wpair.y & 0xffff0000u);
-#pragma unroll
-                for (int c = 0; c < CT; ++c) {
-                  uint32_t q0 = pack_bf16(relu_bits(acc[r][c][4 * g + 0]), relu_bits(acc[r][c][4 * g + 1]));
-                  uint32_t q1 = pack_bf16(relu_bits(acc[r][c][4 * g + 2]), relu_bits(acc[r][c][4 * g + 3]));
-                  float d = dot[c];
-                  d = fmaf(__uint_as_float(q0 << 16), wv.x, d);
-                  d = fmaf(__uint_as_float(q0 & 0xffff0000u), wv.y, d);
-                  d = fmaf(__uint_as_float(q1 << 16), wv.z, d);
-                  d = fmaf(__uint_as_float(q1 & 0xffff0000u), wv.w, d);
-                  dot[c] = d;
-                }
-              }
-            }
-          }
+          start_from_bias(acc, auxs + md.bias_off[1]);
+          __builtin_amdgcn_s_setprio(2);
+          contract_layer<RT, CT, PD, VF_K0_OWN % PD>(acc, ring, ws, wstep, voff, true, md.dims[1] / 16, ba, 32 * ks);
+          __builtin_amdgcn_s_setprio(0);
+          output_dots(acc, dot);
         }
       }
+      // the scan of the tile before, by the waves that hold its scores (nothing left to do
+      // for them before the barrier)
+      if (w < NWS) scan_pending();
 
       // ---- value: the partial dots of the two lane halves, then of the waves in order
       if (real) {
@@ -529,20 +531,18 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       }
       __syncthreads();
       if (real && w < NWS) {
-        float s = auxs[md.bias_off[md.L - 1]];
+        float sacc = auxs[md.bias_off[md.L - 1]];
 #pragma unroll
-        for (int g = 0; g < 8; ++g) s += red[g * NC + tid];
-        const int32_t flag = okf[par * NC + tid];
-        const int32_t colid = flag - 1;
-        if (na.eps != 0.0f) s = add_noise(na, s, unit, colid);
-        // (+inf and NaN never win: Algorithm 1 compares with a strict "<" from +inf)
-        if (flag != 0 && s < __builtin_inff()) take_min(col_v, col_c, s, colid);
-        col_n += (t * NC + tid < ncands ? 1u : 0u) + (flag != 0 ? 0x10000u : 0u);
+        for (int g = 0; g < 8; ++g) sacc += red[g * NC + tid];
+        pend_s = sacc;
+        pend_flag = okf[par * NC + tid];
+        col_n += (t * NC + tid < ncands ? 1u : 0u) + (pend_flag != 0 ? 0x10000u : 0u);
       }
       // no barrier here: the next tile's first layer reads the input buffer and the bias
       // only; its activations are written behind this barrier, the partial dots and the
       // flags of the other parity behind the next tile's first one
     }
+    if (w < NWS) scan_pending();
 
     if (w < NWS) {
       wave_min(col_v, col_c);
@@ -637,8 +637,9 @@ static whole_kernel whole_launch_shape(const vf_ctx *c, vf_fast_dev *fd, int *ks
   int NC = 0;
   vfk_fast_dev(c, true, fd, ks, &NC);
   const size_t aux_words = fd->wl_off + (size_t)(fd->naux - (int)fd->wl_off + 1) / 2;  // output vector: two to a word
-  *smem = (size_t)NC * *ks * 2 + (size_t)NC * 64 * 2 + (size_t)8 * NC * 4 + (size_t)2 * NC * 4 + aux_words * 4;
-  return NC == 64 ? k_whole<64, 4, 2> : k_whole<128, 2, 4>;
+  *smem = (size_t)NC * *ks * 2 + (size_t)NC * VF_XIN_STRIDE * 2 + (size_t)8 * NC * 4 + (size_t)2 * NC * 4 + aux_words * 4;
+  if (fd->L == 2) return NC == 64 ? k_whole<64, 4, 2, true> : k_whole<128, 2, 4, true>;
+  return NC == 64 ? k_whole<64, 4, 2, false> : k_whole<128, 2, 4, false>;
 }
 
 // Workgroups per problem for a whole-schedule launch, 0 = use the per-layer launches
@@ -662,10 +663,12 @@ int vfk_whole_team(const vf_ctx *c) {
     hipFuncAttributes attr;
     if (hipFuncGetAttributes(&attr, (const void *)kern) != hipSuccess) { (void)hipGetLastError(); return 0; }
     (void)hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, c->device);
-    if (fd.k0 != 4 || smem + attr.sharedSizeBytes > (size_t)lds_max) return 0;
+    if (fd.k0 != VF_K0_OWN || !fd.w_full || fd.L > 3 || smem + attr.sharedSizeBytes > (size_t)lds_max) return 0;
   }
   int ncu = 256;
   (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
+  // (a mailbox names a problem in 23 bits, a layer's tiles are counted in 16)
+  if (c->B >= (1 << 23) || (c->M + 63) / 64 > 65535) return 0;
   if (c->B > ncu / 2) return 1;
   if (c->B < 24) return 0;  // a handful of problems: the per-layer launches are faster (16: 1.3 against 1.6 ms)
   int maxw = 0;
@@ -690,7 +693,8 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
     c->wlist_elems = want;
   }
   // meetings: [arrivals B][err 1][pool counters 3][pool queue][mailboxes, 8 bytes per compute unit]
-  // [values 2*B*T][ids 2*B*T], T slots per problem; everything before the values starts at zero
+  // [values 2*B*T][ids 2*B*T][published layers B*VF_PUB_WORDS], T slots per problem; everything
+  // before the values starts at zero
   int ncu = 256;
   (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
   if (ncu >= VF_POOL_SLOTS) return VF_ESTATE;
@@ -699,7 +703,7 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
   const size_t off_mail = (off_q + VF_POOL_SLOTS + 1) & ~(size_t)1;  // 8-byte aligned
   const size_t nzero = off_mail + (size_t)2 * ncu;
   {
-    const size_t twant = nzero + (size_t)4 * c->B * tstride;
+    const size_t twant = nzero + (size_t)4 * c->B * tstride + (team == 1 ? (size_t)c->B * VF_PUB_WORDS : 0);
     if (twant > c->team_elems) {
       if (c->d_team) { VF_HIP(c, hipStreamSynchronize(c->stream)); (void)hipFree(c->d_team); c->d_team = nullptr; }
       c->team_elems = 0;
@@ -737,6 +741,7 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
   wa.mailbox = reinterpret_cast<unsigned long long *>(c->d_team + off_mail);
   wa.team_val = reinterpret_cast<float *>(c->d_team) + nzero;
   wa.team_idx = reinterpret_cast<int32_t *>(c->d_team) + nzero + (size_t)2 * c->B * tstride;
+  wa.pub = c->d_team + nzero + (size_t)4 * c->B * tstride;
   // persistent: at most one workgroup per compute unit; with helpers exactly one, so that
   // compute units without a problem of their own help from the start
   const dim3 grid = team > 1 ? dim3((unsigned)(c->B * team)) : dim3((unsigned)ncu);
@@ -748,8 +753,15 @@ int vfk_greedy_whole(vf_ctx *c, int first, int last) {
     VF_HIP(c, hipGetLastError());
   }
   c->dec_stage = -1;
-  // the flag of a wait that ran out, for the next call to look at
+  // the flag of a wait that ran out, and an event behind its copy: whoever looks at the flag
+  // waits for (or polls) the event first
   VF_HIP(c, hipMemcpyAsync(c->h_team_err, reinterpret_cast<int32_t *>(c->d_team) + c->B, sizeof(int32_t),
                              hipMemcpyDeviceToHost, c->stream));
+  if (!c->ev_whole) VF_HIP(c, hipEventCreateWithFlags(&c->ev_whole, hipEventDisableTiming));
+  VF_HIP(c, hipEventRecord(c->ev_whole, c->stream));
+  c->whole_pending = true;
+  c->whole_first = first;
+  c->whole_last = last;
+  c->whole_epoch = c->state_epoch;
   return VF_OK;
 }

@@ -494,8 +494,10 @@ def test_wait_between_workgroups_that_runs_out_is_reported(vf, ovf, B):
     """Workgroups that share a problem wait for each other with a bound (B = 24: a fixed team
     per problem meets once per layer; B = 200: helpers wait for mail, owners for the helpers
     they sent for).  With the bound set to zero from the host every wait that is not satisfied
-    at once gives up: the launch must still end, the next call must report VF_ESTATE, and with
-    the default bound the same context must give the schedules of the per-layer launches."""
+    at once gives up: the launch must still end; vf_sync_status must report VF_ESTATE and leave
+    complete tables behind (the layers run again per layer), equal to those of the per-layer
+    launches; without the status call the next call that builds on the state reports it; and
+    with the default bound the same context gives those schedules in one launch."""
     import torch
     pipes = I.resnet18_batch(B, seed=40)
     sp = I.make_space([1, 2, 4], [1, 4], [4, 8], [(0, 1, 2), (2, 1, 0)], 2, 2,
@@ -506,20 +508,41 @@ def test_wait_between_workgroups_that_runs_out_is_reported(vf, ovf, B):
     S = pipes.shape[1]
     ctx = vf.vf_create(0)
     vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipes); vf.vf_set_model(ctx, model, w)
-    vf.vf_set_wait_limit(ctx, 0)
-    vf.vf_greedy_schedule(ctx)
-    torch.cuda.synchronize()
-    with pytest.raises(vf.VfError) as e:
-        vf.vf_greedy_schedule(ctx, first=S)
-    assert e.value.code == vf.VF_ESTATE
-    vf.vf_set_wait_limit(ctx, 1 << 22)
-    vf.vf_reset_state(ctx)
-    whole = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
-    vf.vf_reset_state(ctx)
     for i in range(S):
         vf.vf_argmin_step(ctx, i, True)
     steps = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=S)]
+    assert (steps[1] >= 0).all()
+    vf.vf_sync_status(ctx)                                  # nothing to report so far
+
+    vf.vf_set_wait_limit(ctx, 0)
+    vf.vf_reset_state(ctx)
+    broken = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
+    done = broken[1] >= 0                                   # in-band: what was not finished reads -1 / +inf
+    assert np.array_equal(broken[1][done], steps[1][done]) and np.isinf(broken[2][~done]).all()
+    with pytest.raises(vf.VfError) as e:
+        vf.vf_sync_status(ctx)
+    assert e.value.code == vf.VF_ESTATE
+    vf.vf_sync_status(ctx)                                  # reported once
+    repaired = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=S)]
+    for a, b in zip(repaired, steps):
+        assert np.array_equal(a, b)
+
+    # without the status call: the next call that builds on the state waits for the verdict
+    vf.vf_reset_state(ctx)
+    vf.vf_greedy_schedule(ctx, last=9)
+    with pytest.raises(vf.VfError) as e:
+        vf.vf_greedy_schedule(ctx, first=10)
+    assert e.value.code == vf.VF_ESTATE
+    assert vf.vf_n_scheduled(ctx) == 10                     # layers 0..9 were run again per layer
+    vf.vf_set_wait_limit(ctx, 1 << 22)
+    pieces = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=10)]
+    for a, b in zip(pieces, steps):
+        assert np.array_equal(a, b)
+
+    vf.vf_reset_state(ctx)
+    whole = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
+    vf.vf_sync_status(ctx)
     for a, b in zip(whole, steps):
         assert np.array_equal(a, b)
-    assert (whole[1] >= 0).all()
+    torch.cuda.synchronize()
     vf.vf_destroy(ctx)
