@@ -121,10 +121,8 @@ __global__ __launch_bounds__(1024) void k_seq_advance(Tables t, int stage, SeqWe
   for (int i = tid; i < SEQ_PB * H; i += 1024) {
     const int pb = i / H, u = i % H, b = b0 + pb, from = from_s[pb];
     if (mode_s[pb] == 2) {
-      const float ig = sigmoid_dev(z[pb][u]), fg = sigmoid_dev(z[pb][H + u]);
-      const float gg = tanh_dev(z[pb][2 * H + u]), og = sigmoid_dev(z[pb][3 * H + u]);
-      const float cn = fg * src.cpre[(size_t)from * H + u] + ig * gg;
-      const float h = og * tanh_dev(cn);
+      float cn = src.cpre[(size_t)from * H + u];
+      const float h = lstm_cell(z[pb][u], z[pb][H + u], z[pb][2 * H + u], z[pb][3 * H + u], cn);
       dst.cpre[(size_t)b * H + u] = cn;
       hraw[pb][u] = h;
       hn[pb][u] = bf16_val(h);
@@ -307,15 +305,16 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
   const bool active = w < H / 32;
   const int wu = active ? w : 0;  // idle waves shadow tile 0 but never store
   const int ksh = H / 16, ksteps = 4 + ksh;
-  const uint4 *const wx = reinterpret_cast<const uint4 *>(md.w_pack) + (size_t)wu * ksteps * 4 * 64 + lane;
-  const uint4 *const whp = wx + 4 * 4 * 64;
-  const uint4 *wp = wx;
+  // the wave's weight stream (4 k-steps of x part, then the h part): base in scalar registers,
+  // 16 bytes per lane, fragment i at byte 1024 i
+  const __amdgpu_buffer_rsrc_t ws = stream_rsrc(reinterpret_cast<const uint4 *>(md.w_pack) + (size_t)wu * ksteps * 4 * 64);
+  const int voff = 16 * lane;
+  int wstep = PD;  // the k-step of the stream that refills the next slot
   uint4 ring[PD][4];
 #pragma unroll
   for (int j = 0; j < PD; ++j)
 #pragma unroll
-    for (int g = 0; g < 4; ++g) ring[j][g] = wp[(j * 4 + g) * 64];
-  wp += PD * 4 * 64;
+    for (int g = 0; g < 4; ++g) ring[j][g] = stream_load(ws, voff, j * 4 + g);
 
   for (int i = tid; i < H4; i += 512) gls[i] = md.P[(size_t)b * H4 + i];
   for (int i = tid; i < H; i += 512) whs[i] = md.aux[H4 + i];
@@ -366,27 +365,24 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
 #pragma unroll
       for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ld);
       for (int s0 = 0; s0 < nsteps; s0 += PD) {
-        if (s0 + PD >= nsteps) wp = whp;  // the next step's first fragments (always an h step)
+        if (s0 + PD >= nsteps) wstep = 4;  // the next step's first fragments (always an h step)
 #pragma unroll
         for (int j = 0; j < PD; ++j) {
-          // one memory instruction behind each product: the activation fragments of the next
-          // k-step (one k-step past the end stays inside the row's padding or the next row),
-          // then the refill, in place, of each weight fragment behind its last use
-          uint4 bnext[CT];
+          // column by column; every operand register is refilled in place behind the last product
+          // that reads it: a column's activation fragment with the next k-step's (one k-step
+          // past the end stays inside the row's padding or the next row), a weight fragment
+          // with the one PD k-steps ahead
 #pragma unroll
           for (int i = 0; i < 4 * CT; ++i) {
-            const int g = i / CT, c = i % CT;
+            const int c = i / 4, g = i % 4;
             acc[g][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                 __builtin_bit_cast(bf16x8, ring[j][g]), __builtin_bit_cast(bf16x8, bcur[c]), acc[g][c], 0, 0, 0);
-            if (i < CT) bnext[i] = *reinterpret_cast<const uint4 *>(brow + (size_t)i * 32 * ld + (s0 + j + 1) * 16);
-            if (i >= CT && c == 0) ring[j][g - 1] = wp[(g - 1) * 64];
-            if (i == 4 * CT - 1) ring[j][3] = wp[3 * 64];
+            if (g == 3) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ld + (s0 + j + 1) * 16);
+            if (c == CT - 1) ring[j][g] = stream_load(ws, voff, (wstep + j) * 4 + g);
             __builtin_amdgcn_sched_barrier(0);
           }
-          wp += 4 * 64;
-#pragma unroll
-          for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
         }
+        wstep += PD;
       }
     }
     if (fetch_g) reinterpret_cast<float4 *>(gls + (size_t)((k + 1) & 1) * H4)[tid] = gnext;
@@ -403,13 +399,9 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int j = 4 * q + e;
-          const float ig = sigmoid_dev(acc[0][c][j]);
-          const float fg = sigmoid_dev(acc[1][c][j]);
-          const float gg = tanh_dev(acc[2][c][j]);
-          const float og = sigmoid_dev(acc[3][c][j]);
-          const float cn = fg * cst[c][j] + ig * gg;
+          float cn = cst[c][j];
+          hv[e] = lstm_cell(acc[0][c][j], acc[1][c][j], acc[2][c][j], acc[3][c][j], cn);
           cst[c][j] = cn;
-          hv[e] = og * tanh_dev(cn);
           vsum[c] = fmaf(whq[e], hv[e], vsum[c]);
         }
         if (active) {

@@ -726,18 +726,20 @@ __global__ __launch_bounds__(256) void k_lstm_aux(const float *bih, const float 
 
 // One workgroup walks NC sequences through all T steps.  Wave w owns hidden units
 // 32w..32w+31: the four gate row tiles of those units for every candidate column.
-// Per step: the x_t part of the contraction (it does not depend on h_{t-1}), one
-// barrier, the h_{t-1} part, the gates.  h is double-buffered in LDS so that h_t is
-// written as it is produced; x_{t+1} is fetched a step ahead; the weight fragments
-// of a timestep are one contiguous stream per wave, kept PD k-steps ahead in a
-// register ring that wraps at the end of the step.
+// Per step a wave has three pieces of work: the x_t part of the contraction (it does not
+// depend on h_{t-1}), the h_{t-1} part, and the gates (5 exponentials and 3 reciprocals per
+// cell, on the vector ALUs, about as long as both contractions together).  Per step: the x_t
+// part, one barrier (h_{t-1} complete), the h_{t-1} part, the gates.  h is double-buffered
+// in LDS so that h_t is written as it is produced; x_{t+1} is fetched a step ahead; the
+// weight fragments of a timestep are one contiguous stream per wave, kept PD k-steps ahead
+// in a register ring that wraps at the end of the step.
 template <int NC, int XPT, int PD>
 __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M, int T, LstmDev md, int xld,
                                                    int hld, float *scores, float *pval, int32_t *pidx) {
   constexpr int CT = NC / 32;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   uint16_t *xs = reinterpret_cast<uint16_t *>(smem);                  // [2][NC][xld]
-  uint16_t *hs = xs + (size_t)2 * NC * xld;                           // [2][NC][hld]
+  uint16_t *hs = xs + (size_t)2 * NC * xld;                          // [2][NC][hld]
   float *red = reinterpret_cast<float *>(hs + (size_t)2 * NC * hld);  // [8][NC]
   float *auxs = red + 8 * NC;                                         // [5H+1]
 
@@ -750,15 +752,16 @@ __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M,
   const int ksx = F / 16, ksh = H / 16, ksteps = ksx + ksh;
   const bool active = w < H / 32;
   const int wu = active ? w : 0;         // idle waves shadow tile 0 but never store
-  const uint4 *const wbase = reinterpret_cast<const uint4 *>(md.w_pack) + (size_t)wu * ksteps * 4 * 64 + lane;
-  const uint4 *wp = wbase;
+  // the wave's weight stream: base in scalar registers, 16 bytes per lane, fragment i at byte 1024 i
+  const __amdgpu_buffer_rsrc_t ws = stream_rsrc(reinterpret_cast<const uint4 *>(md.w_pack) + (size_t)wu * ksteps * 4 * 64);
+  const int voff = 16 * lane;
+  int wstep = PD;  // the k-step of the timestep's stream that refills the next slot
 
   uint4 ring[PD][4];
 #pragma unroll
   for (int j = 0; j < PD; ++j)
 #pragma unroll
-    for (int g = 0; g < 4; ++g) ring[j][g] = wp[(j * 4 + g) * 64];
-  wp += PD * 4 * 64;
+    for (int g = 0; g < 4; ++g) ring[j][g] = stream_load(ws, voff, j * 4 + g);
 
   for (int i = tid; i < NC * hld; i += 512) reinterpret_cast<uint32_t *>(hs)[i] = 0u;  // both h buffers
   for (int i = tid; i < 8 * NC; i += 512) red[i] = 0.0f;
@@ -796,19 +799,12 @@ __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M,
 #pragma unroll
     for (int j = 0; j < 16; ++j) cst[c][j] = 0.0f;
   }
-  fetch(0);
-  stash(0);
-  fetch(1);
-  __syncthreads();
 
   const float *bias = auxs, *wh = auxs + 4 * H;
   const int rowoff = (lane & 31), koff = 8 * (lane >> 5);
-  for (int t = 0; t < T; ++t) {
-    // x_{t+1} (fetched during the previous step) goes to the buffer last read at t-1
-    stash((t + 1) & 1);
-    fetch(t + 2);
-
-    floatx16 acc[4][CT];
+  floatx16 acc[4][CT];
+  // the accumulators start from the gate biases
+  auto start = [&]() __attribute__((always_inline)) {
 #pragma unroll
     for (int g = 0; g < 4; ++g)
 #pragma unroll
@@ -820,43 +816,37 @@ __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M,
           acc[g][c][4 * q + 2] = bv.z; acc[g][c][4 * q + 3] = bv.w;
         }
       }
-
-    auto kloop = [&](const uint16_t *src, int ld, int nsteps, bool last_part) {
-      const uint16_t *brow = src + (size_t)rowoff * ld + koff;
-      uint4 bcur[CT];
+  };
+  auto kloop = [&](const uint16_t *src, int ld, int nsteps, bool last_part) __attribute__((always_inline)) {
+    const uint16_t *brow = src + (size_t)rowoff * ld + koff;
+    uint4 bcur[CT];
 #pragma unroll
-      for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ld);
-      // (nothing but the ring's loads in flight at the loop's entry: the compiler then waits for
-      // the oldest weight fragment only, not for all of them at the top of every round)
-      __builtin_amdgcn_s_waitcnt(0x0070);
-      for (int s0 = 0; s0 < nsteps; s0 += PD) {
-        if (last_part && s0 + PD >= nsteps) wp = wbase;  // wrap: next timestep's first fragments
+    for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ld);
+    // (nothing but the ring's loads in flight at the loop's entry: the compiler then waits for
+    // the oldest weight fragment only, not for all of them at the top of every round)
+    __builtin_amdgcn_s_waitcnt(0x0070);
+    for (int s0 = 0; s0 < nsteps; s0 += PD) {
+      if (last_part && s0 + PD >= nsteps) wstep = 0;  // wrap: next timestep's first fragments
 #pragma unroll
-        for (int j = 0; j < PD; ++j) {
-          // one memory instruction behind each product: the activation fragments of the next
-          // k-step, then the refill, in place, of each weight fragment behind its last use
-          uint4 bnext[CT];
+      for (int j = 0; j < PD; ++j) {
+        // column by column; every operand register is refilled in place behind the last product
+        // that reads it: a column's activation fragment with the next k-step's, a weight
+        // fragment with the one PD k-steps ahead
 #pragma unroll
-          for (int i = 0; i < 4 * CT; ++i) {
-            const int g = i / CT, c = i % CT;
-            acc[g][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                __builtin_bit_cast(bf16x8, ring[j][g]), __builtin_bit_cast(bf16x8, bcur[c]), acc[g][c], 0, 0, 0);
-            if (i < CT) bnext[i] = *reinterpret_cast<const uint4 *>(brow + (size_t)i * 32 * ld + (s0 + j + 1) * 16);
-            if (i >= CT && c == 0) ring[j][g - 1] = wp[(g - 1) * 64];
-            if (i == 4 * CT - 1) ring[j][3] = wp[3 * 64];
-            __builtin_amdgcn_sched_barrier(0);
-          }
-          wp += 4 * 64;
-#pragma unroll
-          for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
+        for (int i = 0; i < 4 * CT; ++i) {
+          const int c = i / 4, g = i % 4;
+          acc[g][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+              __builtin_bit_cast(bf16x8, ring[j][g]), __builtin_bit_cast(bf16x8, bcur[c]), acc[g][c], 0, 0, 0);
+          if (g == 3) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ld + (s0 + j + 1) * 16);
+          if (c == CT - 1) ring[j][g] = stream_load(ws, voff, (wstep + j) * 4 + g);
+          __builtin_amdgcn_sched_barrier(0);
         }
       }
-    };
-
-    kloop(xs + (size_t)(t & 1) * NC * xld, xld, ksx, false);
-    __syncthreads();  // h_{t-1} is complete; x_{t+1} is visible for the next step
-    kloop(hs + (size_t)(t & 1) * NC * hld, hld, ksh, true);
-
+      wstep += PD;
+    }
+  };
+  // gates and cell update of step t from the accumulators; h_t goes to the other h buffer
+  auto gates = [&](int t) __attribute__((always_inline)) {
     uint16_t *hout = hs + (size_t)((t + 1) & 1) * NC * hld;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -868,13 +858,9 @@ __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M,
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int j = 4 * q + e;
-          float ig = sigmoid_dev(acc[0][c][j]);
-          float fg = sigmoid_dev(acc[1][c][j]);
-          float gg = tanh_dev(acc[2][c][j]);
-          float og = sigmoid_dev(acc[3][c][j]);
-          float cn = fg * cst[c][j] + ig * gg;
+          float cn = cst[c][j];
+          hv[e] = lstm_cell(acc[0][c][j], acc[1][c][j], acc[2][c][j], acc[3][c][j], cn);
           cst[c][j] = cn;
-          hv[e] = og * tanh_dev(cn);
           vsum[c] = fmaf(whq[e], hv[e], vsum[c]);
         }
         if (active) {
@@ -885,6 +871,21 @@ __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M,
         }
       }
     }
+  };
+
+  fetch(0);
+  stash(0);
+  fetch(1);
+  __syncthreads();
+  for (int t = 0; t < T; ++t) {
+    // x_{t+1} (fetched during the previous step) goes to the buffer last read at t-1
+    stash((t + 1) & 1);
+    fetch(t + 2);
+    start();
+    kloop(xs + (size_t)(t & 1) * NC * xld, xld, ksx, false);
+    __syncthreads();  // h_{t-1} is complete; x_{t+1} is visible for the next step
+    kloop(hs + (size_t)(t & 1) * NC * hld, hld, ksh, true);
+    gates(t);
   }
 
   // v = sum_t (w . h_t + b): add the two lane halves, then the waves in order
@@ -1284,7 +1285,7 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
       else
         kern = wide ? k_mlp_fast<64, 4, 2, true> : narrow ? k_mlp_fast<64, 2, 4, true> : k_mlp_fast<128, 2, 4, true>;
     } else {
-      kern = wide ? k_mlp_fast<64, 4, 2, false> : k_mlp_fast<128, 2, 4, false>;
+      kern = wide ? k_mlp_fast<64, 4, 4, false> : k_mlp_fast<128, 2, 4, false>;
     }
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_fast));
     hipLaunchKernelGGL(kern, grid, dim3(512), smem_fast, st, x, prob_stride, M, ld, use_valid_row, fd, ks, scores,
@@ -1331,7 +1332,7 @@ int vfk_score_lstm(vf_ctx *c, const uint16_t *x, int64_t M, int T, float *scores
     // ring depth 2: F and H are multiples of 32, so both parts have an even number of
     // k-steps (depth 4 spills registers and measured slower)
     void (*kern)(const uint16_t *, int64_t, int, LstmDev, int, int, float *, float *, int32_t *) =
-        k_lstm_bf16<NC, 4, 2>;
+        md.F <= 128 ? k_lstm_bf16<NC, 2, 2> : k_lstm_bf16<NC, 4, 2>;
     VF_HIP(c, hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem));
     hipLaunchKernelGGL(kern, dim3((unsigned)nparts), dim3(512), smem, c->stream, x, M, T, md, xld, hld, scores,
                        pval, pidx);

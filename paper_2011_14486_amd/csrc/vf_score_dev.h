@@ -69,9 +69,27 @@ __device__ __forceinline__ void wave_min(float &v, int32_t &c) {
   c = rc;
 }
 
-// gate non-linearities of the recurrent network, fp32
-__device__ __forceinline__ float sigmoid_dev(float z) { return __builtin_amdgcn_rcpf(1.0f + __expf(-z)); }
-__device__ __forceinline__ float tanh_dev(float z) { return 1.0f - 2.0f * __builtin_amdgcn_rcpf(1.0f + __expf(2.0f * z)); }
+// One cell of the recurrent network in fp32: gate pre-activations ai, af, ag, ao and the old cell
+// state give the new cell state (returned through c) and the new hidden value (returned).
+//   c' = sigma(af) c + sigma(ai) tanh(ag),   h' = sigma(ao) tanh(c')
+// A product sigma(a) tanh(b) is one quotient (e^{2b} - 1) / ((1 + e^{2b}) (1 + e^{-a})): two
+// exponentials and one reciprocal instead of two and two, which matters because these run at a
+// quarter of the rate of ordinary instructions (8 instead of 10 per cell).  Exponents are cut
+// off at 60 binary orders, where tanh is 1 and sigma is 0 to far below fp32 resolution, so that
+// the product of the two denominators stays finite; a NaN passes the cut-off and comes out.
+__device__ __forceinline__ float exp2_cut(float x) { return __builtin_amdgcn_exp2f(x > 60.0f ? 60.0f : x); }
+__device__ __forceinline__ float sig_tanh(float a, float b) {
+  constexpr float LOG2E = 1.44269504088896340736f;
+  const float ea = exp2_cut(a * -LOG2E), eb = exp2_cut(b * (2.0f * LOG2E));
+  return (eb - 1.0f) * __builtin_amdgcn_rcpf((1.0f + eb) * (1.0f + ea));
+}
+__device__ __forceinline__ float lstm_cell(float ai, float af, float ag, float ao, float &c) {
+  constexpr float LOG2E = 1.44269504088896340736f;
+  const float fg = __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(af * -LOG2E));
+  const float cn = fg * c + sig_tanh(ai, ag);
+  c = cn;
+  return sig_tanh(ao, cn);
+}
 
 // ---- pieces of the fused bf16 MLP that the per-layer scorer and the whole-schedule kernel share
 
@@ -107,7 +125,7 @@ __device__ __forceinline__ void fold_bias(__amdgpu_buffer_rsrc_t wf, const uint3
 #pragma unroll
     for (int q = 0; q < 16; ++q) fa[r][q] = 0.0f;
   const int n = wide ? 14 : 2;
-#pragma unroll 2
+#pragma unroll 7
   for (int q = 0; q < n; ++q) {
     const int sk = q == 0 ? 0 : q + 2;  // k-step of the whole first layer: 0, 3, 4, 5, ...
     uint4 a[RT];
@@ -135,11 +153,13 @@ __device__ __forceinline__ void fold_bias(__amdgpu_buffer_rsrc_t wf, const uint3
 
 // The contraction of one layer for a wave: RT row tiles x CT column tiles of 32 x 32, weights
 // (A operand) from a ring of PD k-steps of fragments in registers, activations (B operand) from
-// LDS one k-step ahead.  One memory instruction behind each product, so that a wave that has its
-// SIMD's matrix core to itself never leaves it waiting for the issue of a burst of loads: behind
-// the first CT products the activation fragments of the next k-step (one step past the end stays
-// inside LDS), behind the last product that reads a weight fragment its refill, in place, PD
-// k-steps ahead of its next use - so only the oldest slot is ever waited for.
+// LDS.  With at least as many column tiles as row tiles (the tile of 128 candidates) the products
+// of a k-step go column by column, and every operand register is refilled in place right behind
+// the last product that reads it: a column's activation fragment with that of
+// the next k-step (one step past the end stays inside LDS), a weight fragment with the one PD
+// k-steps ahead - so there is at most one memory instruction behind a product (two behind the
+// last one), the loads of a k-step are spread evenly over it, no second set of fragment
+// registers is needed, and only the oldest slot of the ring is ever waited for.
 //
 // ws: the wave's weight stream; k-step n of a tile (its layers' k-steps counted through) is
 // fragments n * RT .. n * RT + RT - 1 of it and lives in ring slot n % PD; a layer that starts
@@ -166,19 +186,32 @@ __device__ __forceinline__ void contract_layer(floatx16 (&acc)[RT][CT], uint4 (&
     for (int j = 0; j < PD; ++j) {
       const int slot = (ROT + j) % PD;
       const int frag = (last ? slot : wstep + j) * RT;
-      uint4 bnext[CT];
+      if constexpr (RT <= CT) {
 #pragma unroll
-      for (int i = 0; i < RT * CT; ++i) {
-        const int r = i / CT, c = i % CT;
-        acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[slot][r]),
-                                                           __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
-        if (i < CT) bnext[i] = *reinterpret_cast<const uint4 *>(bb + (size_t)i * cstride + (s0 + j + 1) * 16);
-        if (i >= CT && c == 0) ring[slot][r - 1] = stream_load(ws, voff, frag + r - 1);
-        if (i == RT * CT - 1) ring[slot][RT - 1] = stream_load(ws, voff, frag + RT - 1);
-        __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < RT * CT; ++i) {
+          const int c = i / RT, r = i % RT;
+          acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[slot][r]),
+                                                             __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
+          if (r == RT - 1) bcur[c] = *reinterpret_cast<const uint4 *>(bb + (size_t)c * cstride + (s0 + j + 1) * 16);
+          if (c == CT - 1) ring[slot][r] = stream_load(ws, voff, frag + r);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      } else {
+        // more row tiles than column tiles: row by row, the few activation fragments of the next
+        // k-step in a second set of registers (measured: the better order for this shape)
+        uint4 bnext[CT];
+#pragma unroll
+        for (int i = 0; i < RT * CT; ++i) {
+          const int r = i / CT, c = i % CT;
+          acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[slot][r]),
+                                                             __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
+          if (i < CT) bnext[i] = *reinterpret_cast<const uint4 *>(bb + (size_t)i * cstride + (s0 + j + 1) * 16);
+          if (c == CT - 1) ring[slot][r] = stream_load(ws, voff, frag + r);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
       }
-#pragma unroll
-      for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
     }
     wstep += PD;
   }
@@ -201,20 +234,14 @@ __device__ __forceinline__ void contract_own_rows(floatx16 (&acc)[RT][CT], uint4
   for (int n = 0; n < VF_K0_OWN; ++n) {
     const int slot = n % PD;
     const int next = (!ONLY || n + PD < VF_K0_OWN) ? n + PD : slot;
-    uint4 bnext[CT];
 #pragma unroll
     for (int i = 0; i < RT * CT; ++i) {
-      const int r = i / CT, c = i % CT;
+      const int c = i / RT, r = i % RT;
       acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[slot][r]),
                                                          __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
-      if (i < CT && n + 1 < VF_K0_OWN) bnext[i] = *reinterpret_cast<const uint4 *>(bb + (size_t)i * cstride + (n + 1) * 16);
-      if (i >= CT && c == 0) ring[slot][r - 1] = stream_load(ws, voff, next * RT + r - 1);
-      if (i == RT * CT - 1) ring[slot][RT - 1] = stream_load(ws, voff, next * RT + RT - 1);
+      if (r == RT - 1 && n + 1 < VF_K0_OWN) bcur[c] = *reinterpret_cast<const uint4 *>(bb + (size_t)c * cstride + (n + 1) * 16);
+      if (c == CT - 1) ring[slot][r] = stream_load(ws, voff, next * RT + r);
       __builtin_amdgcn_sched_barrier(0);
-    }
-    if (n + 1 < VF_K0_OWN) {
-#pragma unroll
-      for (int c = 0; c < CT; ++c) bcur[c] = bnext[c];
     }
   }
 }
