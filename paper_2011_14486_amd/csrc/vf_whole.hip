@@ -276,13 +276,8 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       idlist[k] = dec;
     }
     if (wa.helpers) {
-      // owner: what a helper needs of this layer goes to memory (the list is there already) ...
-      for (int i = tid; i < VF_DECPACK_DWORDS; i += 512) pub[i] = reinterpret_cast<const uint32_t *>(&pk)[i];
-      for (int i = tid; i < (int)(sizeof(EvalTabs) / 4); i += 512) pub[VF_PUB_TABS + i] = reinterpret_cast<const uint32_t *>(&tabs)[i];
-      for (int i = tid; i < md.dims[1]; i += 512) pub[VF_PUB_BIAS + i] = __float_as_uint(auxs[md.bias_off[0] + i]);
-      // ... and, with enough tiles, up to VF_MAX_HELPERS workgroups are taken out of the pool
+      // owner: with enough tiles, up to VF_MAX_HELPERS workgroups are taken out of the pool
       if (tid == 0) {
-        pub[VF_PUB_COUNT] = (uint32_t)ncand;
         int n = 0;
         int want = (ncand + NC - 1) / NC / VF_TILES_PER_MEMBER - 1;
         if (want > VF_MAX_HELPERS) want = VF_MAX_HELPERS;
@@ -316,8 +311,13 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     if (wa.helpers && !helping) {
       team = job_team;
       if (team > 1) {
-        // the helpers are sent for once everything this workgroup has written for them has
-        // arrived in memory: every thread waits for its own stores, then thread 0 sends the mail
+        // what a helper needs of this layer goes to memory (the list is there already); the
+        // helpers are sent for once all of it has arrived: every thread waits for its own
+        // stores, then thread 0 sends the mail
+        for (int i = tid; i < VF_DECPACK_DWORDS; i += 512) pub[i] = reinterpret_cast<const uint32_t *>(&pk)[i];
+        for (int i = tid; i < (int)(sizeof(EvalTabs) / 4); i += 512) pub[VF_PUB_TABS + i] = reinterpret_cast<const uint32_t *>(&tabs)[i];
+        for (int i = tid; i < md.dims[1]; i += 512) pub[VF_PUB_BIAS + i] = __float_as_uint(auxs[md.bias_off[0] + i]);
+        if (tid == 0) pub[VF_PUB_COUNT] = (uint32_t)ncand;
         __threadfence();
         __syncthreads();
         if (tid == 0)
