@@ -297,6 +297,30 @@ def main():
              "roofline": {"bound": "mfma", "achieved": tf3, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                           "frac": tf3 / PEAK_BF16_TFLOPS},
              "hbm_read_gbs": 4 * 256 * G * group / (k3 * 1e-3) / 1e9}
+        # the other design for this width, as a ceiling: one library GEMM per layer (the three
+        # contractions alone, bf16 in and out, with nothing of what the fused kernel also does:
+        # quantisation, bias, ReLU, output dot, argmin)
+        def library_gemm_ms(K):
+            a = torch.randn(G * group, K, device="cuda", dtype=torch.bfloat16)
+            wt = torch.randn(1024, K, device="cuda", dtype=torch.bfloat16) * 0.03
+            out = torch.empty(G * group, 1024, device="cuda", dtype=torch.bfloat16)
+            for _ in range(3):
+                torch.matmul(a, wt.t(), out=out)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                torch.matmul(a, wt.t(), out=out)
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / 10
+        g256, g1024 = library_gemm_ms(256), library_gemm_ms(1024)
+        gsum = g256 + 2 * g1024
+        e["per_layer_library_gemm"] = {
+            "what": "torch.matmul (the vendor GEMM library) on [1048576, K] x [K, 1024] bf16: the first layer's "
+                    "contraction (K = 256) and the two hidden ones (K = 1024), contractions only",
+            "ms_k256": g256, "ms_k1024": g1024, "ms_three_contractions": gsum,
+            "frac_of_peak": G * group * 2.0 * (256 * 1024 + 2 * 1024 * 1024) / (gsum * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+            "fused_kernel_ms": k3}
         if cpu:
             def f3(single):
                 n = 256 if single else 4096

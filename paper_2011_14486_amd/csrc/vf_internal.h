@@ -117,6 +117,10 @@ struct vf_ctx {
   bool whole_pending = false;
   int whole_first = 0, whole_last = -1;
   uint64_t state_epoch = 0, whole_epoch = 0;  // state_epoch: bumped whenever the schedule state is replaced
+  // the last occupancy answer for the whole-schedule kernel (kernel, dynamic LDS -> workgroups per CU)
+  mutable const void *occ_kern = nullptr;
+  mutable size_t occ_smem = 0;
+  mutable int occ_blocks = 0;
   unsigned int wait_rounds = 1u << 22;  // bound of the waits between workgroups that share a problem
   int32_t *d_wlist = nullptr; size_t wlist_elems = 0;  // [B][Mpad] id lists of the whole-schedule launch
 

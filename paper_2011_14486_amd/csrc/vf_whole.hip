@@ -664,6 +664,21 @@ int vfk_whole_team(const vf_ctx *c) {
     if (hipFuncGetAttributes(&attr, (const void *)kern) != hipSuccess) { (void)hipGetLastError(); return 0; }
     (void)hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, c->device);
     if (fd.k0 != VF_K0_OWN || !fd.w_full || fd.L > 3 || smem + attr.sharedSizeBytes > (size_t)lds_max) return 0;
+    // The workgroups of this launch wait for each other, so all of them have to be resident at
+    // once: the grid is one workgroup per compute unit, and the runtime must say that a compute
+    // unit can hold one with this much LDS and these registers (asked once per kernel shape).
+    if (c->occ_kern != (const void *)kern || c->occ_smem != smem) {
+      int nb = 0;
+      if (hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem) != hipSuccess ||
+          hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, (const void *)kern, 512, smem) != hipSuccess) {
+        (void)hipGetLastError();
+        nb = 0;
+      }
+      c->occ_kern = (const void *)kern;
+      c->occ_smem = smem;
+      c->occ_blocks = nb;
+    }
+    if (c->occ_blocks < 1) return 0;
   }
   int ncu = 256;
   (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
