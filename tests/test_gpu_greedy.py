@@ -157,10 +157,11 @@ def test_mobilenet_shaped_all_stages(vf, ovf):
     vf.vf_destroy(ctx)
 
 
-@pytest.mark.parametrize("B,eps", [(100, 0.3), (160, 0.3), (130, 0.0)])
+@pytest.mark.parametrize("B,eps", [(100, 0.3), (64, 0.3), (160, 0.3), (130, 0.0)])
 def test_whole_schedule_launch_100_stages_16384_ids(vf, ovf, B, eps):
     """The whole-schedule launch on the 100-stage pipeline with 16384 candidate ids per decision,
-    as the benchmark times it: 100 noisy rollouts (a fixed team of two workgroups per problem),
+    as the benchmark times it: 100 noisy rollouts (owners, and the compute units that fixed teams
+    of two would leave idle as their helpers), 64 (fixed teams of four workgroups per problem),
     160 (more problems than half the compute units: owners and helpers), and 130 copies without
     noise.  The checker looks at layers sampled over the whole schedule for a few rollouts, each
     decision under the GPU's own prefix; every rollout must replay to its state records."""
