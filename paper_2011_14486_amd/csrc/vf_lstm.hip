@@ -341,20 +341,10 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
     float4 gnext = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
     if (fetch_g) gnext = reinterpret_cast<const float4 *>(md.G + ((size_t)b * S + t + 1) * H4)[tid];
 
-    // the accumulators start from the step's gate biases (staged in LDS one step ahead)
+    // the step's gate biases (staged in LDS one step ahead) are the addends of the first k-step:
+    // gate by gate, so that one bias vector is in registers at a time
     const float *bias = gls + (size_t)(k & 1) * H4;
     floatx16 acc[4][CT];
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float4 bv = *reinterpret_cast<const float4 *>(bias + g * H + wu * 32 + 4 * (lane >> 5) + 8 * q);
-#pragma unroll
-        for (int c = 0; c < CT; ++c) {
-          acc[g][c][4 * q + 0] = bv.x; acc[g][c][4 * q + 1] = bv.y;
-          acc[g][c][4 * q + 2] = bv.z; acc[g][c][4 * q + 3] = bv.w;
-        }
-      }
 
     const uint16_t *src = (k == 0) ? xs : hs + (size_t)(k & 1) * NC * hld;
     const int ld = (k == 0) ? XLD : hld;
@@ -364,10 +354,34 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
       uint4 bcur[CT];
 #pragma unroll
       for (int c = 0; c < CT; ++c) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ld);
-      for (int s0 = 0; s0 < nsteps; s0 += PD) {
+      auto round = [&](int s0, auto startc) __attribute__((always_inline)) {
+        constexpr bool starts = decltype(startc)::value;
         if (s0 + PD >= nsteps) wstep = 4;  // the next step's first fragments (always an h step)
 #pragma unroll
         for (int j = 0; j < PD; ++j) {
+          if constexpr (starts) {
+            if (j == 0) {
+              int boff = wu * 32 + 4 * (lane >> 5);
+              asm volatile("" : "+v"(boff));  // (read afresh every step, not kept across them)
+#pragma unroll
+              for (int g = 0; g < 4; ++g) {
+                floatx16 bg;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                  const float4 bv = *reinterpret_cast<const float4 *>(bias + g * H + boff + 8 * q);
+                  bg[4 * q + 0] = bv.x; bg[4 * q + 1] = bv.y; bg[4 * q + 2] = bv.z; bg[4 * q + 3] = bv.w;
+                }
+#pragma unroll
+                for (int c = 0; c < CT; ++c) {
+                  acc[g][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                      __builtin_bit_cast(bf16x8, ring[0][g]), __builtin_bit_cast(bf16x8, bcur[c]), bg, 0, 0, 0);
+                  if (g == 3) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ld + 16);
+                }
+                ring[0][g] = stream_load(ws, voff, wstep * 4 + g);
+              }
+              continue;
+            }
+          }
           // column by column; every operand register is refilled in place behind the last product
           // that reads it: a column's activation fragment with the next k-step's (one k-step
           // past the end stays inside the row's padding or the next row), a weight fragment
@@ -383,7 +397,9 @@ __global__ __launch_bounds__(512) void k_seq_step(SeqDev md, int stage, int64_t 
           }
         }
         wstep += PD;
-      }
+      };
+      round(0, vf_tag<true>{});
+      for (int s0 = PD; s0 < nsteps; s0 += PD) round(s0, vf_tag<false>{});
     }
     if (fetch_g) reinterpret_cast<float4 *>(gls + (size_t)((k + 1) & 1) * H4)[tid] = gnext;
 

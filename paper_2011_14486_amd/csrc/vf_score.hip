@@ -559,22 +559,6 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
 #pragma unroll
   for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
   const uint16_t *brow = act + (size_t)(lane & 31) * ks + 8 * (lane >> 5);
-  // the accumulators start from the bias of their output row
-  auto start_from_bias = [&](floatx16 (&acc)[RT][CT], const float *bias) __attribute__((always_inline)) {
-#pragma unroll
-    for (int r = 0; r < RT; ++r) {
-      const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
-#pragma unroll
-        for (int c = 0; c < CT; ++c) {
-          acc[r][c][4 * g + 0] = bv.x; acc[r][c][4 * g + 1] = bv.y;
-          acc[r][c][4 * g + 2] = bv.z; acc[r][c][4 * g + 3] = bv.w;
-        }
-      }
-    }
-  };
   // what follows a layer's contraction: the last hidden layer is rounded to bf16 and multiplied
   // with the output vector at once; any other one becomes the next layer's input - rounded to
   // bfloat16, ReLU on the pairs, the two lane halves trade their row groups so that every lane
@@ -625,17 +609,17 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   };
   if constexpr (GEN) {
     // the first layer over the candidates' own rows
-    floatx16 acc[RT][CT];
-    start_from_bias(acc, b1s);
-    contract_own_rows<RT, CT, PD, ONE>(acc, ring, ws, voff, brow, 32 * ks);
+    floatx16 acc[RT][CT], bv[RT];
+    load_bias<RT>(bv, b1s, w, lane);
+    contract_own_rows<RT, CT, PD, ONE>(acc, bv, ring, ws, voff, brow, 32 * ks);
     wstep = VF_K0_OWN + PD;
     finish_layer(acc, ONE);
   }
   for (int l = GEN ? 1 : 0; l < NH; ++l) {
-    floatx16 acc[RT][CT];
-    start_from_bias(acc, auxs + md.bias_off[l]);
+    floatx16 acc[RT][CT], bv[RT];
+    load_bias<RT>(bv, auxs + md.bias_off[l], w, lane);
     // (the last PD steps of a tile prefetch the first PD steps of the next one)
-    contract_layer<RT, CT, PD, ROT>(acc, ring, ws, wstep, voff, l == NH - 1, md.dims[l] / 16, brow, 32 * ks);
+    contract_layer<RT, CT, PD, ROT>(acc, bv, ring, ws, wstep, voff, l == NH - 1, md.dims[l] / 16, brow, 32 * ks);
     finish_layer(acc, l == NH - 1);
   }
   if (!GEN) wstep = PD;
@@ -803,21 +787,11 @@ __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M,
   const float *bias = auxs, *wh = auxs + 4 * H;
   const int rowoff = (lane & 31), koff = 8 * (lane >> 5);
   floatx16 acc[4][CT];
-  // the accumulators start from the gate biases
-  auto start = [&]() __attribute__((always_inline)) {
-#pragma unroll
-    for (int g = 0; g < 4; ++g)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const float4 bv = *reinterpret_cast<const float4 *>(bias + g * H + wu * 32 + 4 * (lane >> 5) + 8 * q);
-#pragma unroll
-        for (int c = 0; c < CT; ++c) {
-          acc[g][c][4 * q + 0] = bv.x; acc[g][c][4 * q + 1] = bv.y;
-          acc[g][c][4 * q + 2] = bv.z; acc[g][c][4 * q + 3] = bv.w;
-        }
-      }
-  };
-  auto kloop = [&](const uint16_t *src, int ld, int nsteps, bool last_part) __attribute__((always_inline)) {
+  // firstc: the timestep's first round - its first k-step starts the accumulators: the products of
+  // a gate's row tile with every column tile take the gate's bias as their addend (gate by gate,
+  // so that one bias vector is in registers at a time), and no accumulator is filled beforehand
+  auto kloop = [&](const uint16_t *src, int ld, int nsteps, bool last_part, auto firstc) __attribute__((always_inline)) {
+    constexpr bool first = decltype(firstc)::value;
     const uint16_t *brow = src + (size_t)rowoff * ld + koff;
     uint4 bcur[CT];
 #pragma unroll
@@ -825,10 +799,36 @@ __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M,
     // (nothing but the ring's loads in flight at the loop's entry: the compiler then waits for
     // the oldest weight fragment only, not for all of them at the top of every round)
     __builtin_amdgcn_s_waitcnt(0x0070);
-    for (int s0 = 0; s0 < nsteps; s0 += PD) {
+    auto round = [&](int s0, auto startc) __attribute__((always_inline)) {
+      constexpr bool starts = decltype(startc)::value;
       if (last_part && s0 + PD >= nsteps) wstep = 0;  // wrap: next timestep's first fragments
 #pragma unroll
       for (int j = 0; j < PD; ++j) {
+        if constexpr (starts) {
+          if (j == 0) {
+            // (read afresh every timestep: kept in registers across the steps, the four bias
+            // vectors would take 64 of them)
+            int boff = wu * 32 + 4 * (lane >> 5);
+            asm volatile("" : "+v"(boff));
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+              floatx16 bg;
+#pragma unroll
+              for (int q = 0; q < 4; ++q) {
+                const float4 bv = *reinterpret_cast<const float4 *>(bias + g * H + boff + 8 * q);
+                bg[4 * q + 0] = bv.x; bg[4 * q + 1] = bv.y; bg[4 * q + 2] = bv.z; bg[4 * q + 3] = bv.w;
+              }
+#pragma unroll
+              for (int c = 0; c < CT; ++c) {
+                acc[g][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, ring[0][g]), __builtin_bit_cast(bf16x8, bcur[c]), bg, 0, 0, 0);
+                if (g == 3) bcur[c] = *reinterpret_cast<const uint4 *>(brow + (size_t)c * 32 * ld + 16);
+              }
+              ring[0][g] = stream_load(ws, voff, wstep * 4 + g);
+            }
+            continue;
+          }
+        }
         // column by column; every operand register is refilled in place behind the last product
         // that reads it: a column's activation fragment with the next k-step's, a weight
         // fragment with the one PD k-steps ahead
@@ -843,7 +843,10 @@ __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M,
         }
       }
       wstep += PD;
-    }
+    };
+    int s0 = 0;
+    if constexpr (first) { round(0, vf_tag<true>{}); s0 = PD; }
+    for (; s0 < nsteps; s0 += PD) round(s0, vf_tag<false>{});
   };
   // gates and cell update of step t from the accumulators; h_t goes to the other h buffer
   auto gates = [&](int t) __attribute__((always_inline)) {
@@ -881,10 +884,9 @@ __global__ __launch_bounds__(512) void k_lstm_bf16(const uint16_t *x, int64_t M,
     // x_{t+1} (fetched during the previous step) goes to the buffer last read at t-1
     stash((t + 1) & 1);
     fetch(t + 2);
-    start();
-    kloop(xs + (size_t)(t & 1) * NC * xld, xld, ksx, false);
+    kloop(xs + (size_t)(t & 1) * NC * xld, xld, ksx, false, vf_tag<true>{});
     __syncthreads();  // h_{t-1} is complete; x_{t+1} is visible for the next step
-    kloop(hs + (size_t)(t & 1) * NC * hld, hld, ksh, true);
+    kloop(hs + (size_t)(t & 1) * NC * hld, hld, ksh, true, vf_tag<false>{});
     gates(t);
   }
 

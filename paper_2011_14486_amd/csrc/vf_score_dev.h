@@ -151,6 +151,26 @@ __device__ __forceinline__ void fold_bias(__amdgpu_buffer_rsrc_t wf, const uint3
   }
 }
 
+// The bias of a wave's output rows, as the accumulator of one column tile holds them (row tile r
+// of the wave = rows (w + 8 r) * 32 ..; a lane has rows 4 (lane >> 5) + 8 g + 0..3 of it).  The
+// contractions take it as the addend of a layer's first k-step, for every column tile alike, so
+// that no accumulator has to be filled with it beforehand.
+template <int RT>
+__device__ __forceinline__ void load_bias(floatx16 (&bv)[RT], const float *bias, int w, int lane) {
+#pragma unroll
+  for (int r = 0; r < RT; ++r) {
+    const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const float4 v = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
+      bv[r][4 * g + 0] = v.x; bv[r][4 * g + 1] = v.y; bv[r][4 * g + 2] = v.z; bv[r][4 * g + 3] = v.w;
+    }
+  }
+}
+
+template <bool V>
+struct vf_tag { static constexpr bool value = V; };
+
 // The contraction of one layer for a wave: RT row tiles x CT column tiles of 32 x 32, weights
 // (A operand) from a ring of PD k-steps of fragments in registers, activations (B operand) from
 // LDS.  With at least as many column tiles as row tiles (the tile of 128 candidates) the products
@@ -167,9 +187,10 @@ __device__ __forceinline__ void fold_bias(__amdgpu_buffer_rsrc_t wf, const uint3
 // (advanced as the loop goes).  ksteps is a multiple of PD.  wrap: the last PD steps are a
 // tile's last ones and refill their slots with the next tile's first PD steps (step m into slot m).
 // bb: this lane's B operand base (column lane & 31 of column tile 0, k half lane >> 5), cstride:
-// elements between column tiles; consecutive k-steps are 16 elements apart.
+// elements between column tiles; consecutive k-steps are 16 elements apart.  bv: the bias
+// (load_bias): the accumulators come out of the first k-step as product + bias.
 template <int RT, int CT, int PD, int ROT>
-__device__ __forceinline__ void contract_layer(floatx16 (&acc)[RT][CT], uint4 (&ring)[PD][RT],
+__device__ __forceinline__ void contract_layer(floatx16 (&acc)[RT][CT], const floatx16 (&bv)[RT], uint4 (&ring)[PD][RT],
                                                __amdgpu_buffer_rsrc_t ws, int &wstep, int voff, bool wrap, int ksteps,
                                                const uint16_t *bb, int cstride) {
   uint4 bcur[CT];
@@ -180,7 +201,9 @@ __device__ __forceinline__ void contract_layer(floatx16 (&acc)[RT][CT], uint4 (&
   // counters come down and waits for every load at the top of each round instead of for the
   // oldest one.  (vmcnt 0, lgkmcnt 0; the ring's loads were issued long before.)
   __builtin_amdgcn_s_waitcnt(0x0070);
-  for (int s0 = 0; s0 < ksteps; s0 += PD) {
+  // one round of PD k-steps; the layer's first round apart, since its first step starts the accumulators
+  auto round = [&](int s0, auto firstc) __attribute__((always_inline)) {
+    constexpr bool first = decltype(firstc)::value;
     const bool last = wrap && s0 + PD >= ksteps;
 #pragma unroll
     for (int j = 0; j < PD; ++j) {
@@ -191,7 +214,8 @@ __device__ __forceinline__ void contract_layer(floatx16 (&acc)[RT][CT], uint4 (&
         for (int i = 0; i < RT * CT; ++i) {
           const int c = i / RT, r = i % RT;
           acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[slot][r]),
-                                                             __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
+                                                             __builtin_bit_cast(bf16x8, bcur[c]),
+                                                             (first && j == 0) ? bv[r] : acc[r][c], 0, 0, 0);
           if (r == RT - 1) bcur[c] = *reinterpret_cast<const uint4 *>(bb + (size_t)c * cstride + (s0 + j + 1) * 16);
           if (c == CT - 1) ring[slot][r] = stream_load(ws, voff, frag + r);
           __builtin_amdgcn_sched_barrier(0);
@@ -204,7 +228,8 @@ __device__ __forceinline__ void contract_layer(floatx16 (&acc)[RT][CT], uint4 (&
         for (int i = 0; i < RT * CT; ++i) {
           const int r = i / CT, c = i % CT;
           acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[slot][r]),
-                                                             __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
+                                                             __builtin_bit_cast(bf16x8, bcur[c]),
+                                                             (first && j == 0) ? bv[r] : acc[r][c], 0, 0, 0);
           if (i < CT) bnext[i] = *reinterpret_cast<const uint4 *>(bb + (size_t)i * cstride + (s0 + j + 1) * 16);
           if (c == CT - 1) ring[slot][r] = stream_load(ws, voff, frag + r);
           __builtin_amdgcn_sched_barrier(0);
@@ -214,7 +239,9 @@ __device__ __forceinline__ void contract_layer(floatx16 (&acc)[RT][CT], uint4 (&
       }
     }
     wstep += PD;
-  }
+  };
+  round(0, vf_tag<true>{});
+  for (int s0 = PD; s0 < ksteps; s0 += PD) round(s0, vf_tag<false>{});
 }
 
 // The first layer over a candidate's own rows: VF_K0_OWN k-steps, steps 0.. of the tile; slot
@@ -223,7 +250,7 @@ __device__ __forceinline__ void contract_layer(floatx16 (&acc)[RT][CT], uint4 (&
 // next, in this tile or in the next one (possibly the very step it holds: the same fragments
 // tile after tile).
 template <int RT, int CT, int PD, bool ONLY>
-__device__ __forceinline__ void contract_own_rows(floatx16 (&acc)[RT][CT], uint4 (&ring)[PD][RT],
+__device__ __forceinline__ void contract_own_rows(floatx16 (&acc)[RT][CT], const floatx16 (&bv)[RT], uint4 (&ring)[PD][RT],
                                                   __amdgpu_buffer_rsrc_t ws, int voff, const uint16_t *bb,
                                                   int cstride) {
   uint4 bcur[CT];
@@ -238,7 +265,7 @@ __device__ __forceinline__ void contract_own_rows(floatx16 (&acc)[RT][CT], uint4
     for (int i = 0; i < RT * CT; ++i) {
       const int c = i / RT, r = i % RT;
       acc[r][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, ring[slot][r]),
-                                                         __builtin_bit_cast(bf16x8, bcur[c]), acc[r][c], 0, 0, 0);
+                                                         __builtin_bit_cast(bf16x8, bcur[c]), n == 0 ? bv[r] : acc[r][c], 0, 0, 0);
       if (r == RT - 1 && n + 1 < VF_K0_OWN) bcur[c] = *reinterpret_cast<const uint4 *>(bb + (size_t)c * cstride + (n + 1) * 16);
       if (c == CT - 1) ring[slot][r] = stream_load(ws, voff, next * RT + r);
       __builtin_amdgcn_sched_barrier(0);

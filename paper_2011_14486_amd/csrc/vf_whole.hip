@@ -395,22 +395,6 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     if (tid == 0) sn[0] = sn[1] = 0u;
     const uint16_t *const bx = xin + (size_t)(lane & 31) * XS + 8 * (lane >> 5);
     const uint16_t *const ba = act + (size_t)(lane & 31) * ks + 8 * (lane >> 5);
-    // the accumulators start from the bias of their output row
-    auto start_from_bias = [&](floatx16 (&acc)[RT][CT], const float *bias) __attribute__((always_inline)) {
-#pragma unroll
-      for (int r = 0; r < RT; ++r) {
-        const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const float4 bv = *reinterpret_cast<const float4 *>(bias + mbase + 8 * g);
-#pragma unroll
-          for (int c = 0; c < CT; ++c) {
-            acc[r][c][4 * g + 0] = bv.x; acc[r][c][4 * g + 1] = bv.y;
-            acc[r][c][4 * g + 2] = bv.z; acc[r][c][4 * g + 3] = bv.w;
-          }
-        }
-      }
-    };
     // a hidden layer's output becomes the next one's input: rounded to bfloat16, ReLU on the
     // pairs; the two lane halves then trade their row groups so that every lane writes 8
     // consecutive rows of its column at once
@@ -476,10 +460,10 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
         // tile's features land in the buffer that the layer has read, so every wave finishes
         // the layer first
         if (real) {
-          floatx16 acc[RT][CT];
-          start_from_bias(acc, auxs + md.bias_off[0]);
+          floatx16 acc[RT][CT], bv[RT];
+          load_bias<RT>(bv, auxs + md.bias_off[0], w, lane);
           __builtin_amdgcn_s_setprio(2);
-          contract_own_rows<RT, CT, PD, true>(acc, ring, ws, voff, bx, 32 * XS);
+          contract_own_rows<RT, CT, PD, true>(acc, bv, ring, ws, voff, bx, 32 * XS);
           __builtin_amdgcn_s_setprio(0);
           output_dots(acc, dot);
         }
@@ -487,10 +471,10 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
         if (has_next) featurize((t + team) * NC, par ^ 1);
       } else {
         if (real) {
-          floatx16 acc[RT][CT];
-          start_from_bias(acc, auxs + md.bias_off[0]);
+          floatx16 acc[RT][CT], bv[RT];
+          load_bias<RT>(bv, auxs + md.bias_off[0], w, lane);
           __builtin_amdgcn_s_setprio(2);
-          contract_own_rows<RT, CT, PD, false>(acc, ring, ws, voff, bx, 32 * XS);
+          contract_own_rows<RT, CT, PD, false>(acc, bv, ring, ws, voff, bx, 32 * XS);
           __builtin_amdgcn_s_setprio(0);
           wstep = VF_K0_OWN + PD;
           // (nobody reads the activations of the tile before any more: barrier behind its dots)
@@ -507,10 +491,10 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
             continue;
           }
           if (!real) continue;
-          floatx16 acc[RT][CT];
-          start_from_bias(acc, auxs + md.bias_off[1]);
+          floatx16 acc[RT][CT], bv[RT];
+          load_bias<RT>(bv, auxs + md.bias_off[1], w, lane);
           __builtin_amdgcn_s_setprio(2);
-          contract_layer<RT, CT, PD, VF_K0_OWN % PD>(acc, ring, ws, wstep, voff, true, md.dims[1] / 16, ba, 32 * ks);
+          contract_layer<RT, CT, PD, VF_K0_OWN % PD>(acc, bv, ring, ws, wstep, voff, true, md.dims[1] / 16, ba, 32 * ks);
           __builtin_amdgcn_s_setprio(0);
           output_dots(acc, dot);
         }
