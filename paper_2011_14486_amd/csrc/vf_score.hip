@@ -585,26 +585,9 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
       }
       __syncthreads();
     } else {
+      // (the output vector sits in LDS as floats that are bfloat16 values: packing is exact)
       const float *wl = auxs + md.wl_off;
-#pragma unroll
-      for (int r = 0; r < RT; ++r) {
-        const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const float4 wv = *reinterpret_cast<const float4 *>(wl + mbase + 8 * g);
-#pragma unroll
-          for (int c = 0; c < CT; ++c) {
-            uint32_t q0 = pack_bf16(relu_bits(acc[r][c][4 * g + 0]), relu_bits(acc[r][c][4 * g + 1]));
-            uint32_t q1 = pack_bf16(relu_bits(acc[r][c][4 * g + 2]), relu_bits(acc[r][c][4 * g + 3]));
-            float d = dot[c];
-            d = fmaf(__uint_as_float(q0 << 16), wv.x, d);
-            d = fmaf(__uint_as_float(q0 & 0xffff0000u), wv.y, d);
-            d = fmaf(__uint_as_float(q1 << 16), wv.z, d);
-            d = fmaf(__uint_as_float(q1 & 0xffff0000u), wv.w, d);
-            dot[c] = d;
-          }
-        }
-      }
+      output_dots_mfma<RT, CT>(acc, dot, [&](int u) { const float2 p = *reinterpret_cast<const float2 *>(wl + u); return pack_bf16(p.x, p.y); }, w, lane);
     }
   };
   if constexpr (GEN) {
@@ -625,12 +608,8 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   if (!GEN) wstep = PD;
 
 #pragma unroll
-  for (int c = 0; c < CT; ++c) {
-    uint32_t own = __float_as_uint(dot[c]), other = own;
-    swap_halves(own, other);  // lanes below 32: the dot of lane + 32
-    float v = dot[c] + __uint_as_float(other);
-    if (lane < 32) red[w * NC + c * 32 + lane] = v;
-  }
+  for (int c = 0; c < CT; ++c)
+    if (lane < 32) red[w * NC + c * 32 + lane] = dot[c];  // (lanes 0..31 hold the wave's part of the dot)
   __syncthreads();
   {
     float v = __builtin_inff();

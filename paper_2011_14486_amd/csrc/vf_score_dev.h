@@ -244,6 +244,74 @@ __device__ __forceinline__ void contract_layer(floatx16 (&acc)[RT][CT], const fl
   for (int s0 = PD; s0 < ksteps; s0 += PD) round(s0, vf_tag<false>{});
 }
 
+// The output layer on the matrix core.  The last hidden layer is never written back: rounded
+// to bfloat16 (ReLU on the packed pairs), a lane's 8 accumulator values of one half of a row tile
+// (rows 16 s + 4 h + 0..3 and 16 s + 8 + 4 h + 0..3 of it, h = lane >> 5) are already what a B
+// operand wants of a lane - column lane & 31, eight of a k-step's sixteen rows - up to the order of
+// the rows inside the k-step, and that order is free as long as the A operand follows it.  A = the
+// output vector's entries for those rows in row 0 of the tile (lanes 0 and 32), zeros elsewhere;
+// row 0 of the product (accumulator element 0 of lanes 0..31) is the wave's part of the dot for
+// column lane & 31, both lane halves' rows included.  wl2(u), u even: the output vector's entries
+// for hidden units u and u + 1 as a packed bfloat16 pair.  dot[c] is valid in lanes 0..31.
+template <int RT, int CT, typename WL>
+__device__ __forceinline__ void output_dots_mfma(const floatx16 (&acc)[RT][CT], float (&dot)[CT], WL wl2, int w, int lane) {
+  uint4 af[RT][2];
+#pragma unroll
+  for (int r = 0; r < RT; ++r)
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2) {
+      const int base = (w + r * 8) * 32 + 16 * s2 + 4 * (lane >> 5);
+      uint4 a;
+      a.x = wl2(base + 0);
+      a.y = wl2(base + 2);
+      a.z = wl2(base + 8);
+      a.w = wl2(base + 10);
+      if ((lane & 31) != 0) a = make_uint4(0u, 0u, 0u, 0u);
+      af[r][s2] = a;
+    }
+  auto bfrag = [&](int r, int c, int s2) __attribute__((always_inline)) {
+    uint4 b;
+    b.x = relu_bf16x2(pack_bf16(acc[r][c][8 * s2 + 0], acc[r][c][8 * s2 + 1]));
+    b.y = relu_bf16x2(pack_bf16(acc[r][c][8 * s2 + 2], acc[r][c][8 * s2 + 3]));
+    b.z = relu_bf16x2(pack_bf16(acc[r][c][8 * s2 + 4], acc[r][c][8 * s2 + 5]));
+    b.w = relu_bf16x2(pack_bf16(acc[r][c][8 * s2 + 6], acc[r][c][8 * s2 + 7]));
+    return b;
+  };
+  // (a column's products depend on each other: with few column tiles they are interleaved; the
+  // order of a column's own products is the same either way)
+  if constexpr (CT <= 2) {
+    floatx16 d[CT];
+#pragma unroll
+    for (int c = 0; c < CT; ++c)
+#pragma unroll
+      for (int j = 0; j < 16; ++j) d[c][j] = 0.0f;
+#pragma unroll
+    for (int r = 0; r < RT; ++r)
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int c = 0; c < CT; ++c)
+          d[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[r][s2]),
+                                                        __builtin_bit_cast(bf16x8, bfrag(r, c, s2)), d[c], 0, 0, 0);
+#pragma unroll
+    for (int c = 0; c < CT; ++c) dot[c] = d[c][0];
+  } else {
+#pragma unroll
+    for (int c = 0; c < CT; ++c) {
+      floatx16 d;
+#pragma unroll
+      for (int j = 0; j < 16; ++j) d[j] = 0.0f;
+#pragma unroll
+      for (int r = 0; r < RT; ++r)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+          d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[r][s2]),
+                                                     __builtin_bit_cast(bf16x8, bfrag(r, c, s2)), d, 0, 0, 0);
+      dot[c] = d[0];
+    }
+  }
+}
+
 // The first layer over a candidate's own rows: VF_K0_OWN k-steps, steps 0.. of the tile; slot
 // n % PD is refilled with step n + PD of the tile.  ONLY: the network has no other hidden
 // layer, so these steps are the whole tile - a slot is then refilled with the step that uses it

@@ -421,30 +421,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
     // output vector at once
     auto output_dots = [&](floatx16 (&acc)[RT][CT], float (&dot)[CT]) __attribute__((always_inline)) {
       const uint32_t *wl = reinterpret_cast<const uint32_t *>(auxs + md.wl_off);
-#pragma unroll
-      for (int c = 0; c < CT; ++c) dot[c] = 0.0f;
-#pragma unroll
-      for (int r = 0; r < RT; ++r) {
-        const int mbase = (w + r * 8) * 32 + 4 * (lane >> 5);
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const uint2 wpair = *reinterpret_cast<const uint2 *>(wl + (mbase + 8 * g) / 2);
-          float4 wv;
-          wv.x = __uint_as_float(wpair.x << 16); wv.y = __uint_as_float(wpair.x & 0xffff0000u);
-          wv.z = __uint_as_float(wpair.y << 16); wv.w = __uint_as_float(wpair.y & 0xffff0000u);
-#pragma unroll
-          for (int c = 0; c < CT; ++c) {
-            uint32_t q0 = pack_bf16(relu_bits(acc[r][c][4 * g + 0]), relu_bits(acc[r][c][4 * g + 1]));
-            uint32_t q1 = pack_bf16(relu_bits(acc[r][c][4 * g + 2]), relu_bits(acc[r][c][4 * g + 3]));
-            float d = dot[c];
-            d = fmaf(__uint_as_float(q0 << 16), wv.x, d);
-            d = fmaf(__uint_as_float(q0 & 0xffff0000u), wv.y, d);
-            d = fmaf(__uint_as_float(q1 << 16), wv.z, d);
-            d = fmaf(__uint_as_float(q1 & 0xffff0000u), wv.w, d);
-            dot[c] = d;
-          }
-        }
-      }
+      output_dots_mfma<RT, CT>(acc, dot, [&](int u) { return wl[u >> 1]; }, w, lane);
     };
 
     // the loop starts one tile early: that round only produces the first tile's features
@@ -506,12 +483,8 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       // ---- value: the partial dots of the two lane halves, then of the waves in order
       if (real) {
 #pragma unroll
-        for (int c = 0; c < CT; ++c) {
-          uint32_t own = __float_as_uint(dot[c]), other = own;
-          swap_halves(own, other);  // lanes below 32: the dot of lane + 32
-          float v = dot[c] + __uint_as_float(other);
-          if (lane < 32) red[w * NC + c * 32 + lane] = v;
-        }
+        for (int c = 0; c < CT; ++c)
+          if (lane < 32) red[w * NC + c * 32 + lane] = dot[c];
       }
       __syncthreads();
       if (real && w < NWS) {
