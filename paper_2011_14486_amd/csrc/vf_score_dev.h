@@ -277,38 +277,18 @@ __device__ __forceinline__ void output_dots_mfma(const floatx16 (&acc)[RT][CT], 
     b.w = relu_bf16x2(pack_bf16(acc[r][c][8 * s2 + 6], acc[r][c][8 * s2 + 7]));
     return b;
   };
-  // (a column's products depend on each other: with few column tiles they are interleaved; the
-  // order of a column's own products is the same either way)
-  if constexpr (CT <= 2) {
-    floatx16 d[CT];
 #pragma unroll
-    for (int c = 0; c < CT; ++c)
+  for (int c = 0; c < CT; ++c) {
+    floatx16 d;
 #pragma unroll
-      for (int j = 0; j < 16; ++j) d[c][j] = 0.0f;
+    for (int j = 0; j < 16; ++j) d[j] = 0.0f;
 #pragma unroll
     for (int r = 0; r < RT; ++r)
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-        for (int c = 0; c < CT; ++c)
-          d[c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[r][s2]),
-                                                        __builtin_bit_cast(bf16x8, bfrag(r, c, s2)), d[c], 0, 0, 0);
-#pragma unroll
-    for (int c = 0; c < CT; ++c) dot[c] = d[c][0];
-  } else {
-#pragma unroll
-    for (int c = 0; c < CT; ++c) {
-      floatx16 d;
-#pragma unroll
-      for (int j = 0; j < 16; ++j) d[j] = 0.0f;
-#pragma unroll
-      for (int r = 0; r < RT; ++r)
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-          d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[r][s2]),
-                                                     __builtin_bit_cast(bf16x8, bfrag(r, c, s2)), d, 0, 0, 0);
-      dot[c] = d[0];
-    }
+        d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, af[r][s2]),
+                                                   __builtin_bit_cast(bf16x8, bfrag(r, c, s2)), d, 0, 0, 0);
+    dot[c] = d[0];
   }
 }
 
