@@ -480,7 +480,7 @@ __global__ __launch_bounds__(512) void k_whole(vf_fast_dev md, int ks, int64_t M
       // for them before the barrier)
       if (w < NWS) scan_pending();
 
-      // ---- value: the partial dots of the two lane halves, then of the waves in order
+      // ---- value: the waves' parts of the dots (lanes 0..31 hold them), summed in order behind the barrier
       if (real) {
 #pragma unroll
         for (int c = 0; c < CT; ++c)
