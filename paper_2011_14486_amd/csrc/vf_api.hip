@@ -89,6 +89,7 @@ void free_pipeline(vf_ctx *c) {
   c->d_alive = c->d_forced = nullptr;
   c->d_vals = nullptr;
   c->d_decpack = nullptr;
+  c->d_decpack2 = nullptr;
   c->dec_stage = -1;
   void *alt[] = {c->d_alt_states, c->d_alt_cf, c->d_alt_prefix, c->d_alt_cids, c->d_alt_vals, c->d_alt_alive,
                  c->d_sel_val,    c->d_sel_idx, c->d_sel_n};
@@ -293,7 +294,8 @@ int vf_set_pipeline(vf_ctx *c, const vf_stage *st, int S, int B) {
   if (rc == VF_OK) rc = dev_alloc(c, c->d_vals, n);
   if (rc == VF_OK) rc = dev_alloc(c, c->d_alive, (size_t)B);
   if (rc == VF_OK) rc = dev_alloc(c, c->d_forced, n);
-  if (rc == VF_OK) rc = dev_alloc(c, c->d_decpack, (size_t)B * VF_DECPACK_DWORDS);
+  if (rc == VF_OK) rc = dev_alloc(c, c->d_decpack, (size_t)2 * B * VF_DECPACK_DWORDS);
+  if (rc == VF_OK) c->d_decpack2 = c->d_decpack + (size_t)B * VF_DECPACK_DWORDS;
   if (rc != VF_OK) {
     free_pipeline(c);
     return rc;
@@ -491,6 +493,11 @@ int vf_greedy_schedule(vf_ctx *c, int first, int last, vf_state *out_states, int
   }
   if (first <= last && vfk_whole_team(c) >= 1) {
     int rc = vfk_greedy_whole(c, first, last);
+    if (rc != VF_OK) return rc;
+    c->n_sched = last + 1;
+  } else if (first <= last && vfk_can_chain(c)) {
+    // a few problems: one launch per layer, each taking the decision of the layer before
+    int rc = vfk_greedy_chain(c, first, last);
     if (rc != VF_OK) return rc;
     c->n_sched = last + 1;
   } else {

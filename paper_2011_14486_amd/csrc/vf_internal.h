@@ -75,6 +75,12 @@ struct vf_ctx {
   int32_t *d_forced = nullptr;  // [B][S] staging for vf_set_state
   uint32_t *d_decpack = nullptr; // [B][VF_DECPACK_DWORDS] decision context of stage dec_stage
   int dec_stage = -1;            // stage d_decpack was built for, -1: none
+  uint32_t *d_decpack2 = nullptr; // second context buffer (behind the first in the same allocation), for chained layers
+  // chained layers of a greedy schedule (vfk_greedy_chain): every fused launch but the first also
+  // takes the decision of the stage before it
+  bool chain_on = false;
+  int chain_prev = -1;           // stage whose decision the next launch takes, -1: none
+  int chain_par = 0;             // which context buffer / partial-minima set the next launch writes
 
   // beam search: a second set of state tables (the survivors of a layer are written
   // there, then the two sets swap), masked scores, selection scratch
@@ -226,6 +232,13 @@ int vfk_seq_advance_beam(vf_ctx *c, int stage);
 int vfk_seq_step(vf_ctx *c, int stage, float *scores, int64_t ld_scores, int noise_stage, int *nparts_out);
 int vfk_greedy_whole(vf_ctx *c, int first, int last);
 int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out);
+// Algorithm 1 over stages first..last with one launch per layer (the fused scorer also decides
+// the stage before it) and one commit at the end; VF_ESTATE if the model or space does not
+// take the fused path.
+bool vfk_can_chain(const vf_ctx *c);
+int vfk_greedy_chain(vf_ctx *c, int first, int last);
+// k_commit on given partial minima and a given context buffer (nullable: rebuilt from the tables)
+int vfk_commit_from(vf_ctx *c, int stage, int nparts, const float *pval, const int32_t *pidx, const uint32_t *decpack_cur);
 // Scores of every candidate of `stage` for all problems into d_scores [B][Mpad]; invalid
 // candidates and padding columns get +inf.
 int vfk_step_scores(vf_ctx *c, int stage);

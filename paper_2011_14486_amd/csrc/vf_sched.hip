@@ -502,6 +502,16 @@ int vfk_commit_from_partials(vf_ctx *c, int stage, int nparts, int commit, int32
   return VF_OK;
 }
 
+int vfk_commit_from(vf_ctx *c, int stage, int nparts, const float *pval, const int32_t *pidx, const uint32_t *decpack_cur) {
+  vf_prof_scope prof(c, VF_PROF_COMMIT);
+  hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(256), 0, c->stream, tables_of(c), stage, nparts, pval, pidx,
+                     (const int32_t *)nullptr, 1, (uint32_t)c->M, (int32_t *)nullptr, (float *)nullptr, decpack_cur,
+                     c->d_decpack);
+  VF_HIP(c, hipGetLastError());
+  c->dec_stage = stage + 1 < c->S ? stage + 1 : -1;
+  return VF_OK;
+}
+
 int vfk_commit_forced(vf_ctx *c, int stage) {
   hipLaunchKernelGGL(k_commit, dim3(c->B), dim3(256), 0, c->stream, tables_of(c), stage, 0,
                      (const float *)nullptr, (const int32_t *)nullptr, (const int32_t *)c->d_forced, 1,

@@ -84,7 +84,146 @@ __device__ void needed(const int32_t *srec, const int32_t *arec, const uint32_t 
   E[2] = (arec[0] == VF_CONV) ? (uint32_t)srec[3] : umin((uint32_t)srec[3], box[2]);
 }
 
-// Cooperative set-up of the decision context for problem b, stage `stage`.
+// What the decision for one stage has just produced, for a caller that builds the next
+// stage's context before those rows are in memory (they are in LDS): the stage's 64 committed
+// features, its state record, the running sums behind it, and whether the problem goes on.
+// stage < 0: nothing is overridden.
+struct FreshRows {
+  int stage;
+  const int32_t *cf;   // [64]
+  const int32_t *st;   // [16]
+  int32_t pm, pb, alive;
+};
+
+// One thread: what the decision context derives from the rows it was given - the regions and
+// instance counts per compute_at level from the anchor's committed loop structure, the levels
+// on offer, the anchor's context features, the running sums.  ast / arec: the anchor's state
+// record and stage record (read only if the stage has an anchor before it); acf: its committed
+// features, all 64 or (packed) just entries 42, 54, 32, 23.
+__device__ __forceinline__ void dec_derive(Dec &d, const vf_space &sp, int stage, int alive, const int32_t *ast,
+                                           const int32_t *arec, const int32_t *acf, bool packed, int32_t pm, int32_t pb,
+                                           int32_t sm, int32_t spt) {
+  const int a = d.srec[8], kind = d.srec[0];
+  d.E[0][0] = d.srec[1]; d.E[0][1] = d.srec[2]; d.E[0][2] = d.srec[3];
+  d.inst[0] = 1;
+  for (int l = 1; l < 3; ++l) {
+    d.E[l][0] = d.E[0][0]; d.E[l][1] = d.E[0][1]; d.E[l][2] = d.E[0][2];
+    d.inst[l] = 1;
+  }
+  d.inl_inst = 1;
+  d.lvl_ok[0] = alive; d.lvl_ok[1] = 0; d.lvl_ok[2] = 0; d.lvl_ok[3] = 0;
+  d.a_tp = d.a_nt = d.a_cat = d.a_perm = 0;
+  bool anchored = (a >= 0 && a < stage && ast[15] == 1);
+  d.anchored = anchored;
+  if (anchored) {
+    uint32_t fa[3] = {(uint32_t)ast[0], (uint32_t)ast[1], (uint32_t)ast[2]};
+    uint32_t Ea[3] = {(uint32_t)ast[8], (uint32_t)ast[9], (uint32_t)ast[10]};
+    uint32_t Oa[3] = {(uint32_t)ast[12], (uint32_t)ast[13], (uint32_t)ast[14]};
+    uint32_t inst_a = ast[11];
+    int d0 = sp.perm[ast[3]][0];
+    uint32_t box[3] = {Ea[0], Ea[1], Ea[2]};
+    box[d0] = fa[d0];
+    needed(d.srec, arec, box, d.E[1]);
+    d.inst[1] = smul(inst_a, Oa[d0]);
+    needed(d.srec, arec, fa, d.E[2]);
+    uint32_t tiles_a = smul(smul(Oa[0], Oa[1]), Oa[2]);
+    d.inst[2] = smul(inst_a, tiles_a);
+    uint32_t pp = 1;
+    for (int k = 0; k < 3; ++k) pp = smul(smul(pp, Oa[k]), fa[k]);
+    uint32_t Ra = smul(smul((uint32_t)arec[4], (uint32_t)arec[5]), (uint32_t)arec[6]);
+    d.inl_inst = smul(smul(inst_a, pp), Ra);
+    bool single = (d.srec[9] == 1) && alive;
+    bool loops = (ast[6] != VF_INLINE);
+    d.lvl_ok[1] = single && loops && Oa[d0] > 1u;
+    d.lvl_ok[2] = single && loops && tiles_a > 1u;
+    d.lvl_ok[3] = single && (kind == VF_POINTWISE || kind == VF_ADD);
+    d.a_tp = acf[packed ? 0 : 42]; d.a_nt = acf[packed ? 1 : 54]; d.a_cat = acf[packed ? 2 : 32]; d.a_perm = acf[packed ? 3 : 23];
+  }
+  d.pm = pm;
+  d.pb = pb;
+  d.sm = sm;
+  d.spt = spt;
+}
+
+// Cooperative set-up of the decision context for problem b, stage `stage`, in three steps with
+// a workgroup barrier between them: every word that comes from memory is fetched by a thread of
+// its own, in two rounds (the anchor's rows need the stage record first), and one thread then
+// works on LDS only.  Rows of stage `fresh` are left out of the fetches: dec_finish takes them
+// from fr (a caller that has just decided that stage can run the two fetch rounds before it
+// knows the winner).
+struct DecScratch {
+  int32_t sc[8];  // alive, prefix sums (2), suffix sums (2)
+  int32_t ast[16], arec[16], acf[4];
+};
+
+__device__ void dec_fetch_rows(Dec &d, vf_space &sp, DecScratch &ds, const Tables &t, int b, int stage, int fresh) {
+  const int tid = threadIdx.x, nt = blockDim.x, S = t.S;
+  const size_t row = (size_t)b * S;
+  for (int i = tid; i < (int)(sizeof(vf_space) / 4); i += nt) ((int32_t *)&sp)[i] = t.space[i];
+  if (tid < 16) {
+    d.srec[tid] = t.stages[(row + stage) * 16 + tid];
+    d.intr[tid] = t.intr[(row + stage) * 16 + tid];
+  }
+  for (int i = tid; i < 192; i += nt) {
+    int32_t v = 0;
+    if (i < 144) {
+      int k = i / 48 + 1, f = i % 48;
+      if (stage - k >= 0 && stage - k != fresh) v = t.cf[(row + stage - k) * 64 + f];
+    } else {
+      int k = (i - 144) / 16 + 1, f = (i - 144) % 16;
+      if (stage + k < S) v = t.intr[(row + stage + k) * 16 + f];
+    }
+    d.nb[i] = v;
+  }
+  // (the last five threads of the first wave: the first ones have the most to fetch above)
+  if (tid == 59) ds.sc[0] = fresh >= 0 ? 0 : t.alive[b];
+  if (tid == 60 || tid == 61) ds.sc[tid - 59] = fresh >= 0 ? 0 : t.prefix[((size_t)b * (S + 1) + stage) * 2 + (tid - 60)];
+  if (tid == 62 || tid == 63) ds.sc[tid - 59] = t.suffix[(row + stage) * 2 + (tid - 62)];
+}
+
+__device__ void dec_fetch_anchor(const Dec &d, DecScratch &ds, const Tables &t, int b, int stage, int fresh) {
+  const int tid = threadIdx.x, S = t.S;
+  const size_t row = (size_t)b * S;
+  const int a = d.srec[8];
+  const bool fetch = a >= 0 && a < stage && a != fresh;
+  if (tid < 16) ds.ast[tid] = fetch ? t.states[(row + a) * 16 + tid] : 0;
+  else if (tid < 32) ds.arec[tid - 16] = (a >= 0 && a < stage) ? t.stages[(row + a) * 16 + tid - 16] : 0;
+  else if (tid < 36) {
+    const int f = tid == 32 ? 42 : tid == 33 ? 54 : tid == 34 ? 32 : 23;
+    ds.acf[tid - 32] = fetch ? t.cf[(row + a) * 64 + f] : 0;
+  }
+}
+
+__device__ void dec_finish(Dec &d, const vf_space &sp, DecScratch &ds, int stage, const FreshRows &fr) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  if (fr.stage >= 0) {
+    // the rows of the stage decided last, from the caller
+    const int k = stage - fr.stage;
+    if (k >= 1 && k <= 3)
+      for (int f = tid; f < 48; f += nt) d.nb[(k - 1) * 48 + f] = fr.cf[f];
+    if (d.srec[8] == fr.stage) {
+      if (tid < 16) ds.ast[tid] = fr.st[tid];
+      else if (tid >= 32 && tid < 36) ds.acf[tid - 32] = fr.cf[tid == 32 ? 42 : tid == 33 ? 54 : tid == 34 ? 32 : 23];
+    }
+    if (tid == 59) { ds.sc[0] = fr.alive; ds.sc[1] = fr.pm; ds.sc[2] = fr.pb; }
+    __syncthreads();
+  }
+  if (tid == 0) dec_derive(d, sp, stage, ds.sc[0], ds.ast, ds.arec, ds.acf, true, ds.sc[1], ds.sc[2], ds.sc[3], ds.sc[4]);
+  __syncthreads();
+}
+
+__device__ void build_dec_from(Dec &d, vf_space &sp, const Tables &t, int b, int stage, const FreshRows &fr) {
+  __shared__ DecScratch ds;
+  dec_fetch_rows(d, sp, ds, t, b, stage, fr.stage);
+  __syncthreads();
+  dec_fetch_anchor(d, ds, t, b, stage, fr.stage);
+  __syncthreads();
+  dec_finish(d, sp, ds, stage, fr);
+}
+
+// The same context with one round of fetches and the rest read by the one thread that derives
+// (a chain of three dependent fetches, but no per-thread addresses that a long kernel would
+// have to keep or spill): the form the whole-schedule kernel uses.
 __device__ void build_dec(Dec &d, vf_space &sp, const Tables &t, int b, int stage) {
   const int tid = threadIdx.x, nt = blockDim.x, S = t.S;
   const size_t row = (size_t)b * S;
@@ -106,50 +245,11 @@ __device__ void build_dec(Dec &d, vf_space &sp, const Tables &t, int b, int stag
   }
   __syncthreads();
   if (tid == 0) {
-    const int alive = t.alive[b];
-    const int a = d.srec[8], kind = d.srec[0];
-    d.E[0][0] = d.srec[1]; d.E[0][1] = d.srec[2]; d.E[0][2] = d.srec[3];
-    d.inst[0] = 1;
-    for (int l = 1; l < 3; ++l) {
-      d.E[l][0] = d.E[0][0]; d.E[l][1] = d.E[0][1]; d.E[l][2] = d.E[0][2];
-      d.inst[l] = 1;
-    }
-    d.inl_inst = 1;
-    d.lvl_ok[0] = alive; d.lvl_ok[1] = 0; d.lvl_ok[2] = 0; d.lvl_ok[3] = 0;
-    d.a_tp = d.a_nt = d.a_cat = d.a_perm = 0;
-    bool anchored = (a >= 0 && a < stage && t.states[(row + a) * 16 + 15] == 1);
-    d.anchored = anchored;
-    if (anchored) {
-      const int32_t *ast = t.states + (row + a) * 16;
-      const int32_t *arec = t.stages + (row + a) * 16;
-      const int32_t *acf = t.cf + (row + a) * 64;
-      uint32_t fa[3] = {(uint32_t)ast[0], (uint32_t)ast[1], (uint32_t)ast[2]};
-      uint32_t Ea[3] = {(uint32_t)ast[8], (uint32_t)ast[9], (uint32_t)ast[10]};
-      uint32_t Oa[3] = {(uint32_t)ast[12], (uint32_t)ast[13], (uint32_t)ast[14]};
-      uint32_t inst_a = ast[11];
-      int d0 = sp.perm[ast[3]][0];
-      uint32_t box[3] = {Ea[0], Ea[1], Ea[2]};
-      box[d0] = fa[d0];
-      needed(d.srec, arec, box, d.E[1]);
-      d.inst[1] = smul(inst_a, Oa[d0]);
-      needed(d.srec, arec, fa, d.E[2]);
-      uint32_t tiles_a = smul(smul(Oa[0], Oa[1]), Oa[2]);
-      d.inst[2] = smul(inst_a, tiles_a);
-      uint32_t pp = 1;
-      for (int k = 0; k < 3; ++k) pp = smul(smul(pp, Oa[k]), fa[k]);
-      uint32_t Ra = smul(smul((uint32_t)arec[4], (uint32_t)arec[5]), (uint32_t)arec[6]);
-      d.inl_inst = smul(smul(inst_a, pp), Ra);
-      bool single = (d.srec[9] == 1) && alive;
-      bool loops = (ast[6] != VF_INLINE);
-      d.lvl_ok[1] = single && loops && Oa[d0] > 1u;
-      d.lvl_ok[2] = single && loops && tiles_a > 1u;
-      d.lvl_ok[3] = single && (kind == VF_POINTWISE || kind == VF_ADD);
-      d.a_tp = acf[42]; d.a_nt = acf[54]; d.a_cat = acf[32]; d.a_perm = acf[23];
-    }
-    d.pm = t.prefix[((size_t)b * (S + 1) + stage) * 2 + 0];
-    d.pb = t.prefix[((size_t)b * (S + 1) + stage) * 2 + 1];
-    d.sm = t.suffix[(row + stage) * 2 + 0];
-    d.spt = t.suffix[(row + stage) * 2 + 1];
+    const int a = d.srec[8];
+    const size_t arow = row + (a >= 0 && a < stage ? a : 0);
+    dec_derive(d, sp, stage, t.alive[b], t.states + arow * 16, t.stages + arow * 16, t.cf + arow * 64, false,
+               t.prefix[((size_t)b * (S + 1) + stage) * 2 + 0], t.prefix[((size_t)b * (S + 1) + stage) * 2 + 1],
+               t.suffix[(row + stage) * 2 + 0], t.suffix[(row + stage) * 2 + 1]);
   }
   __syncthreads();
 }
@@ -468,7 +568,9 @@ __device__ __forceinline__ uint32_t stat_word(const Dec &d, int q) {
 
 // Builds the pack for (problem b, stage) in LDS (every thread of the block takes part).
 [[maybe_unused]] __device__ void fill_decpack(DecPack &pk, const Tables &t, int b, int stage) {
-  build_dec(pk.d, pk.sp, t, b, stage);
+  FreshRows none;
+  none.stage = -1; none.cf = nullptr; none.st = nullptr; none.pm = none.pb = none.alive = 0;
+  build_dec_from(pk.d, pk.sp, t, b, stage, none);  // (two rounds of fetches instead of three)
   for (int q = threadIdx.x; q < VF_STAT_WORDS; q += blockDim.x) pk.stat[q] = stat_word(pk.d, q);
   __syncthreads();
 }
@@ -515,6 +617,59 @@ __device__ __forceinline__ uint32_t stat_word(const Dec &d, int q) {
     t.vals[row] = v;
     pre[2] = sadd((uint32_t)pre_m, (uint32_t)core[40]);
     pre[3] = sadd((uint32_t)pre_b, (uint32_t)core[50]);
+  }
+}
+
+// commit_winner for a caller that goes on to the next decision by itself: the winner's rows are
+// left in LDS (cf64, st16, and the values of a FreshRows record) for build_dec_from, and reach
+// the tables only if `store` - every workgroup of a launch works them out, one of them writes.
+// The running sums of the decision's own stage are taken from its context (d.pm, d.pb).
+[[maybe_unused]] __device__ __forceinline__ void commit_winner_fresh(const Tables &t, const Dec &d, const vf_space &sp, int b,
+                                                                   int stage, int32_t c, float v, uint32_t M,
+                                                                   const EvalTabs &tb, bool store, int32_t *cf64,
+                                                                   int32_t *st16, int32_t *sums3) {
+  const int S = t.S;
+  const size_t row = (size_t)b * S + stage;
+  int32_t *pre = t.prefix + ((size_t)b * (S + 1) + stage) * 2;
+  const int32_t pre_m = d.pm, pre_b = d.pb;
+  int32_t core[64];
+  bool ok = false;
+  if (c >= 0 && (uint32_t)c < M) ok = eval_digits<true>(d, sp, digits_small(sp, (uint32_t)c), &tb, core);
+  if (!ok) {
+#pragma unroll
+    for (int k = 0; k < 64; ++k) cf64[k] = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) st16[k] = 0;
+    sums3[0] = pre_m; sums3[1] = pre_b; sums3[2] = 0;
+    if (store) {
+      t.alive[b] = 0;
+      t.cids[row] = -1;
+      t.vals[row] = __builtin_inff();
+      pre[2] = pre_m; pre[3] = pre_b;
+    }
+  } else {
+    int32_t st[16];
+    st[0] = core[17]; st[1] = core[18]; st[2] = core[19];
+    st[3] = core[23]; st[4] = core[26]; st[5] = core[29]; st[6] = core[32]; st[7] = core[33];
+    st[8] = core[34]; st[9] = core[35]; st[10] = core[36];
+    st[11] = core[37];
+    st[12] = core[20]; st[13] = core[21]; st[14] = core[22];
+    st[15] = 1;
+    const int32_t pm = (int32_t)sadd((uint32_t)pre_m, (uint32_t)core[40]), pb = (int32_t)sadd((uint32_t)pre_b, (uint32_t)core[50]);
+#pragma unroll
+    for (int k = 0; k < 64; ++k) cf64[k] = core[k];
+#pragma unroll
+    for (int k = 0; k < 16; ++k) st16[k] = st[k];
+    sums3[0] = pm; sums3[1] = pb; sums3[2] = d.lvl_ok[0];
+    if (store) {
+#pragma unroll
+      for (int k = 0; k < 64; ++k) t.cf[row * 64 + k] = core[k];
+#pragma unroll
+      for (int k = 0; k < 16; ++k) t.states[row * 16 + k] = st[k];
+      t.cids[row] = c;
+      t.vals[row] = v;
+      pre[2] = pm; pre[3] = pb;
+    }
   }
 }
 

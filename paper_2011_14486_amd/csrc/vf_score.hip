@@ -400,10 +400,22 @@ __global__ __launch_bounds__(256) void k_pack_stream(const float *blob, vf_fast_
 struct GenArgs {
   const uint32_t *decpack;  // [problem][VF_DECPACK_DWORDS], built for the stage being decided
   unsigned long long *stat; // nullable: [0] += ids pushed through the network, [1] += valid ones
+  // Chained layers (prev_stage >= 0): the launch for stage i first takes the decision of stage
+  // i - 1 itself.  decpack is then the context of stage i - 1, pval_prev / pidx_prev its partial
+  // minima [problem][nparts]; every workgroup reduces them, evaluates the winner and builds the
+  // context of stage i from the tables and the winner's rows (Algorithm 1's s_{i-1} := s and the
+  // next CandidateActions in one place); the workgroup that has a problem's first tile also
+  // writes the winner to the tables and the new context to decpack_out, for the launch after.
+  int prev_stage;
+  const float *pval_prev;
+  const int32_t *pidx_prev;
+  uint32_t *decpack_out;
+  Tables t;
 };
 
 // ONE (with GEN): the network has a single hidden layer.
-template <int NC, int RT, int PD, bool GEN, bool ONE = false>
+// CHAIN (with GEN): the launch can also take the decision of the stage before (GenArgs::prev_stage).
+template <int NC, int RT, int PD, bool GEN, bool ONE = false, bool CHAIN = false>
 __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob_stride, int64_t M, int64_t ld,
                                                   int use_valid_row, vf_fast_dev md, int ks, float *scores,
                                                   int64_t ld_scores, float *pval, int32_t *pidx, int nparts,
@@ -419,6 +431,12 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
   float *b1s = auxs + ((md.naux + 3) & ~3);                             // [dims[1]] folded first-layer bias (GEN)
   __shared__ DecPack pk;
   int b1_p = -1;
+  // (chained layers only)
+  __shared__ DecPack pk_next;
+  __shared__ DecScratch dscr;
+  __shared__ EvalTabs tabs;
+  __shared__ int32_t fresh_cf[64], fresh_st[16], fresh_sums[3], win_c;
+  __shared__ float win_v;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -457,6 +475,52 @@ __global__ __launch_bounds__(512) void k_mlp_fast(const int32_t *x, int64_t prob
     if (tid < VF_DECPACK_DWORDS)
       reinterpret_cast<uint32_t *>(&pk)[tid] = ga.decpack[(size_t)p * VF_DECPACK_DWORDS + tid];
     cur_p = p;
+    if (CHAIN && ga.prev_stage >= 0) {
+      // ---- the decision of the stage before, then this stage's context
+      float v = __builtin_inff();
+      int32_t c = -1;
+      if (w == 1) {  // (wave 1: wave 0 has the larger share of the context's fetch in front of it)
+        for (int q = lane; q < nparts; q += 64) {
+          const float pv = ga.pval_prev[(size_t)p * nparts + q];
+          const int32_t pi = ga.pidx_prev[(size_t)p * nparts + q];
+          if (pi >= 0 && (pv < v || (pv == v && (c < 0 || pi < c)))) { v = pv; c = pi; }
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+          const float ov = __shfl_down(v, off);
+          const int32_t oc = __shfl_down(c, off);
+          if (oc >= 0 && (ov < v || (ov == v && (c < 0 || oc < c)))) { v = ov; c = oc; }
+        }
+        if (lane == 0) { win_v = v; win_c = c; }
+      }
+      // what this stage's context takes from memory does not depend on the winner (the rows of
+      // the stage before are left out): both rounds of fetches are under way while one thread
+      // evaluates the winner
+      dec_fetch_rows(pk_next.d, pk_next.sp, dscr, ga.t, p, ga.prev_stage + 1, ga.prev_stage);
+      __syncthreads();  // the context of the stage before has arrived
+      fill_evaltabs(tabs, pk.d, pk.sp, 64);
+      dec_fetch_anchor(pk_next.d, dscr, ga.t, p, ga.prev_stage + 1, ga.prev_stage);
+      __syncthreads();
+      const bool writes = (int)((int64_t)p * nparts) >= t_begin;  // this workgroup has the problem's first tile
+      if (tid == 0)
+        commit_winner_fresh(ga.t, pk.d, pk.sp, p, ga.prev_stage, win_c, win_v, (uint32_t)M, tabs, writes, fresh_cf, fresh_st,
+                            fresh_sums);
+      __syncthreads();
+      FreshRows fr;
+      fr.stage = ga.prev_stage; fr.cf = fresh_cf; fr.st = fresh_st;
+      fr.pm = fresh_sums[0]; fr.pb = fresh_sums[1]; fr.alive = fresh_sums[2];
+      dec_finish(pk_next.d, pk_next.sp, dscr, ga.prev_stage + 1, fr);
+      for (int q = tid; q < VF_STAT_WORDS; q += 512) pk_next.stat[q] = stat_word(pk_next.d, q);
+      __syncthreads();
+      {
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(&pk_next);
+        const int used = (int)((sizeof(Dec) + sizeof(vf_space)) / 4 + VF_STAT_WORDS);
+        if (tid < VF_DECPACK_DWORDS) {
+          const uint32_t wv = tid < used ? src[tid] : 0u;
+          reinterpret_cast<uint32_t *>(&pk)[tid] = wv;
+          if (writes) ga.decpack_out[(size_t)p * VF_DECPACK_DWORDS + tid] = wv;
+        }
+      }
+    }
   }
   __syncthreads();
 
@@ -1092,6 +1156,37 @@ int vfk_step_fused(vf_ctx *c, int stage, int *nparts_out) {
   return score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, nparts_out, stage, stage);
 }
 
+// (the condition under which score_mlp takes tiles of 64 candidates for a generated step)
+static bool narrow_step(const vf_ctx *c) {
+  int maxw = 0, ncu = 256;
+  for (int l = 0; l < c->model.n_layers; ++l) if (c->model.dims[l] > maxw) maxw = c->model.dims[l];
+  (void)hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, c->device);
+  return maxw <= 512 && c->pm.fast_rt && ((c->M + 127) / 128) * c->B * 2 <= ncu;
+}
+
+bool vfk_can_chain(const vf_ctx *c) { return vfk_can_fuse_step(c) && c->M > 0 && narrow_step(c); }
+
+int vfk_greedy_chain(vf_ctx *c, int first, int last) {
+  if (!vfk_can_chain(c) || first > last) return VF_ESTATE;
+  c->chain_on = true;
+  c->chain_prev = -1;
+  c->chain_par = 0;  // the first launch reads the context that vfk_prepare leaves in the first buffer
+  int nparts = 0, rc = VF_OK;
+  for (int i = first; i <= last && rc == VF_OK; ++i) {
+    rc = score_mlp(c, nullptr, 0, c->B, c->M, c->Mpad, 1, nullptr, 0, &nparts, i, i);
+    c->chain_prev = i;
+    c->chain_par ^= 1;
+  }
+  c->chain_on = false;
+  c->dec_stage = -1;  // the first buffer holds whatever stage wrote it last
+  if (rc != VF_OK) return rc;
+  // the last layer's decision: its partial minima and its context are in the set / buffer written last
+  const int par = c->chain_par ^ 1;
+  const size_t nset = (size_t)nparts * c->B;
+  return vfk_commit_from(c, last, nparts, c->d_pval + (size_t)par * nset, c->d_pidx + (size_t)par * nset,
+                         par ? c->d_decpack2 : c->d_decpack);
+}
+
 namespace {
 // masks the scores of invalid candidates (validity row of the feature matrix) and of
 // the padding columns with +inf
@@ -1230,18 +1325,22 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
   // A decision of a few pipelines has fewer tiles of 128 candidates than half the compute
   // units: then tiles of 64 spread the same work over twice as many of them, and the
   // contraction of a tile - most of the time a layer takes - is half as long.
-  const bool narrow = !wide && gen_stage >= 0 && c->pm.fast_rt && ((M + 127) / 128) * nprob * 2 <= ncu;
+  const bool narrow = !wide && gen_stage >= 0 && c->pm.fast_rt && ((M + 127) / 128) * nprob * 2 <= ncu;  // (see narrow_step)
   const int NC = (wide || narrow) ? 64 : 128;
   const int nparts = (int)((M + NC - 1) / NC);
   float *pval = nullptr;
   int32_t *pidx = nullptr;
+  const bool chained = c->chain_on && narrow && !parts && nparts > 0;
+  const size_t nset = (size_t)(nparts > 0 ? nparts : 1) * nprob;
   if (parts) {
-    if ((size_t)(nparts > 0 ? nparts : 1) * nprob > parts->cap) return VF_EINVAL;
+    if (nset > parts->cap) return VF_EINVAL;
     pval = parts->val; pidx = parts->idx;
   } else {
-    int rc = vfk_ensure_parts(c, (size_t)(nparts > 0 ? nparts : 1) * nprob);
+    // (chained layers: two sets, the one being written and the one of the stage before)
+    int rc = vfk_ensure_parts(c, chained ? 2 * nset : nset);
     if (rc != VF_OK) return rc;
-    pval = c->d_pval; pidx = c->d_pidx;
+    pval = c->d_pval + (chained ? (size_t)c->chain_par * nset : 0);
+    pidx = c->d_pidx + (chained ? (size_t)c->chain_par * nset : 0);
   }
   const size_t smem = (size_t)NC * ks * 2 + (size_t)8 * NC * 4 + (size_t)NC * 4;
   if (nparts > 0 && c->pm.fast_rt) {
@@ -1258,13 +1357,28 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     GenArgs ga;
     ga.decpack = c->d_decpack;
     ga.stat = c->profiling ? c->d_stat : nullptr;
+    ga.prev_stage = -1;
+    ga.pval_prev = nullptr;
+    ga.pidx_prev = nullptr;
+    ga.decpack_out = nullptr;
+    ga.t = tables_of(c);
+    if (chained && c->chain_prev >= 0) {
+      uint32_t *const buf[2] = {c->d_decpack, c->d_decpack2};
+      ga.prev_stage = c->chain_prev;
+      ga.pval_prev = c->d_pval + (size_t)(c->chain_par ^ 1) * nset;
+      ga.pidx_prev = c->d_pidx + (size_t)(c->chain_par ^ 1) * nset;
+      ga.decpack = buf[c->chain_par ^ 1];
+      ga.decpack_out = buf[c->chain_par];
+    }
     if (gen_stage >= 0) {
-      int rc2 = vfk_prepare(c, gen_stage);
-      if (rc2 != VF_OK) return rc2;
+      if (ga.prev_stage < 0) {
+        int rc2 = vfk_prepare(c, gen_stage);
+        if (rc2 != VF_OK) return rc2;
+      }
       if (L == 2)
-        kern = wide ? k_mlp_fast<64, 4, 2, true, true> : narrow ? k_mlp_fast<64, 2, 4, true, true> : k_mlp_fast<128, 2, 4, true, true>;
+        kern = wide ? k_mlp_fast<64, 4, 2, true, true> : narrow ? k_mlp_fast<64, 2, 4, true, true, true> : k_mlp_fast<128, 2, 4, true, true>;
       else
-        kern = wide ? k_mlp_fast<64, 4, 2, true> : narrow ? k_mlp_fast<64, 2, 4, true> : k_mlp_fast<128, 2, 4, true>;
+        kern = wide ? k_mlp_fast<64, 4, 2, true> : narrow ? k_mlp_fast<64, 2, 4, true, false, true> : k_mlp_fast<128, 2, 4, true>;
     } else {
       kern = wide ? k_mlp_fast<64, 4, 4, false> : k_mlp_fast<128, 2, 4, false>;
     }

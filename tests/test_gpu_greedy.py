@@ -274,6 +274,52 @@ def test_profile_counts_are_the_candidates_of_algorithm_1(vf, ovf):
     vf.vf_destroy(ctx)
 
 
+@pytest.mark.parametrize("B", [1, 3])
+def test_chained_layers_equal_layer_by_layer(vf, ovf, B):
+    """With a few problems vf_greedy_schedule launches once per layer and every launch also takes
+    the decision of the layer before it; vf_argmin_step scores and commits in two launches.  Both
+    must give bit-identical tables: plain, with exploration noise, in two pieces from a committed
+    prefix, and when one problem's schedule ends early; problem 0 is followed by the checker."""
+    pipes = I.resnet18_batch(B, seed=9)
+    if B > 1:
+        pipes[1, 2, 3] = 2      # problem 1: the convolution at stage 2 has 2 channels ...
+    sp = I.make_space([1, 2, 4], [1, 4], [4, 8], [(0, 1, 2), (2, 1, 0)], 2, 2,
+                      [I.ROOT, I.L1, I.L2, I.INLINE], 2, 256)   # ... and every channel factor is larger
+    dims = [256, 512, 512, 1]
+    w = I.mlp_weights(dims, 3)
+    model = I.model_record(I.MLP, dims, I.BF16)
+    S = pipes.shape[1]
+    ctx = vf.vf_create(0)
+    vf.vf_set_space(ctx, sp); vf.vf_set_pipeline(ctx, pipes); vf.vf_set_model(ctx, model, w)
+    for eps in (0.0, 0.05):
+        vf.vf_set_noise(ctx, eps, seed=11, first_rollout=2)
+        vf.vf_reset_state(ctx)
+        chain = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx)]
+        vf.vf_reset_state(ctx)
+        for i in range(S):
+            vf.vf_argmin_step(ctx, i, True)
+        steps = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=S)]
+        for a, b in zip(chain, steps):
+            assert np.array_equal(a, b)
+        if B > 1:
+            assert chain[1][1, 1] >= 0 and (chain[1][1, 2:] == -1).all() and (chain[1][0] >= 0).all()
+        # two pieces from a committed prefix, the second one a single layer long at its start
+        vf.vf_set_state(ctx, chain[1][:, :2])
+        vf.vf_greedy_schedule(ctx, first=2, last=9)
+        vf.vf_greedy_schedule(ctx, first=10, last=10)
+        pieces = [t.cpu().numpy() for t in vf.vf_greedy_schedule(ctx, first=11)]
+        assert np.array_equal(chain[0], pieces[0]) and np.array_equal(chain[1], pieces[1])
+        assert np.array_equal(chain[2][:, 2:], pieces[2][:, 2:])   # a forced decision carries no value
+        # and a step by hand behind a chained piece sees the context that piece left
+        vf.vf_set_state(ctx, chain[1][:, :2])
+        vf.vf_greedy_schedule(ctx, first=2, last=5)
+        bc, bv = vf.vf_argmin_step(ctx, 6, commit=True)
+        assert np.array_equal(bc.cpu().numpy(), chain[1][:, 6]) and np.array_equal(bv.cpu().numpy(), chain[2][:, 6])
+        if eps == 0.0:
+            compare_schedule(ovf, pipes[0], sp, model, w, chain[1][0], chain[2][0], chain[0][0], TOL[1])
+    vf.vf_destroy(ctx)
+
+
 def test_whole_schedule_launch_equals_layer_by_layer(vf, ovf):
     """With about one problem per compute unit vf_greedy_schedule runs each problem's whole
     schedule inside one workgroup; vf_argmin_step launches layer by layer.  Both must give
