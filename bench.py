@@ -247,7 +247,7 @@ def main():
             e["candidates_per_s"] = ref1["n_evals"] / (ms1 * 1e-3)
         workloads["tiny_conv_relu_fp32"] = e
 
-    # ---- single pipelines: the latency half of the metric (two launches per layer)
+    # ---- single pipelines: the latency half of the metric (one launch per layer)
     if wanted("single"):
         ms2, nv2 = greedy_ms(space, pipes[0], model, w, reps=20)
         workloads["resnet18_single_pipeline"] = {
