@@ -1179,7 +1179,12 @@ int vfk_greedy_chain(vf_ctx *c, int first, int last) {
   }
   c->chain_on = false;
   c->dec_stage = -1;  // the first buffer holds whatever stage wrote it last
-  if (rc != VF_OK) return rc;
+  if (rc != VF_OK) {
+    // a launch could not be made: the tables hold some of the layers' decisions but not the
+    // last one's - back to the state the call started from
+    (void)vfk_rewind(c, first);
+    return rc;
+  }
   // the last layer's decision: its partial minima and its context are in the set / buffer written last
   const int par = c->chain_par ^ 1;
   const size_t nset = (size_t)nparts * c->B;
