@@ -27,6 +27,7 @@ struct vf_partbuf {
 struct vf_packed_model {
   // fp32 path: the caller's blob copied as is
   float *w_f32 = nullptr;
+  float *w_f32t = nullptr;  // fp32 MLPs: every layer's matrix transposed, [k][N rounded up to 16] (zeros in the padding)
   size_t n_floats = 0;
   // bf16 path: matrices repacked into MFMA A-fragment order, biases and the last
   // layer's vector as fp32

@@ -38,11 +38,21 @@ namespace {
 
 // --------------------------------------------------------------- fp32 MLP
 
+// Wt[k][o] = W[o][k] for o < N, zero up to Npad
+__global__ __launch_bounds__(256) void k_transpose_f32(const float *W, int K, int N, int Npad, float *Wt) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (size_t)K * Npad) return;
+  const int k = (int)(i / Npad), o = (int)(i % Npad);
+  Wt[i] = o < N ? W[(size_t)o * K + k] : 0.0f;
+}
+
 // out[o][n] = act(b[o] + sum_k W[o][k] * in[k][n]); one thread per candidate, 16
-// outputs per thread; W and b are uniform across the wave.
+// outputs per thread; the weights come transposed (Wt[k][Npad]), so that the 16 a thread needs
+// for one k are one uniform 64-byte read, and four rows of the input are fetched at a time;
+// every accumulator adds its products in the order k = 0, 1, 2, ...
 template <bool FIRST>
 __global__ __launch_bounds__(256) void k_mlp_f32_layer(const void *in_, int64_t in_stride, int64_t ld_in,
-                                                       const float *W, const float *bias, float *out,
+                                                       const float *__restrict__ Wt, int Npad, const float *bias, float *out,
                                                        int64_t out_stride, int64_t ld_out, int K, int N,
                                                        int64_t M, int relu) {
   const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -54,11 +64,12 @@ __global__ __launch_bounds__(256) void k_mlp_f32_layer(const void *in_, int64_t 
   for (int j = 0; j < 16; ++j) acc[j] = 0.0f;
   const int32_t *xi = (const int32_t *)in_ + (size_t)p * in_stride;
   const float *xf = (const float *)in_ + (size_t)p * in_stride;
+#pragma unroll 4
   for (int k = 0; k < K; ++k) {
     float a = FIRST ? plog2_dev(xi[(size_t)k * ld_in + n]) : xf[(size_t)k * ld_in + n];
+    const float *wrow = Wt + (size_t)k * Npad + o0;
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
-      if (o0 + j < N) acc[j] = fmaf(W[(size_t)(o0 + j) * K + k], a, acc[j]);
+    for (int j = 0; j < 16; ++j) acc[j] = fmaf(wrow[j], a, acc[j]);  // (padding: zero weights, never stored)
   }
 #pragma unroll
   for (int j = 0; j < 16; ++j)
@@ -1023,6 +1034,7 @@ int vfk_ensure_parts(vf_ctx *c, size_t n) {
 void vfk_free_model(vf_ctx *c) {
   vfk_seq_free(c);
   if (c->pm.w_f32) (void)hipFree(c->pm.w_f32);
+  if (c->pm.w_f32t) (void)hipFree(c->pm.w_f32t);
   if (c->pm.w_pack) (void)hipFree(c->pm.w_pack);
   if (c->pm.w_stream) (void)hipFree(c->pm.w_stream);
   if (c->pm.w_stream_fold) (void)hipFree(c->pm.w_stream_fold);
@@ -1043,6 +1055,18 @@ int vfk_pack_model(vf_ctx *c, const float *wdev) {
     pm.n_floats = n;
     hipLaunchKernelGGL(k_copy_f32, blocks(n), dim3(256), 0, st, wdev, pm.w_f32, n, 0);
     VF_HIP(c, hipGetLastError());
+    size_t nt = 0;
+    for (int l = 0; l < m.n_layers; ++l) nt += (size_t)m.dims[l] * ((m.dims[l + 1] + 15) / 16 * 16);
+    VF_HIP(c, hipMalloc((void **)&pm.w_f32t, nt * sizeof(float)));
+    const float *src = wdev;
+    float *dst = pm.w_f32t;
+    for (int l = 0; l < m.n_layers; ++l) {
+      const int K = m.dims[l], N = m.dims[l + 1], Npad = (N + 15) / 16 * 16;
+      hipLaunchKernelGGL(k_transpose_f32, blocks((size_t)K * Npad), dim3(256), 0, st, src, K, N, Npad, dst);
+      VF_HIP(c, hipGetLastError());
+      src += (size_t)K * N + N;
+      dst += (size_t)K * Npad;
+    }
     return VF_OK;
   }
   if (m.kind == VF_MLP) {
@@ -1281,13 +1305,14 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
     rc = vfk_ensure_parts(c, (size_t)nparts * nprob);
     if (rc != VF_OK) return rc;
     const float *wp = c->pm.w_f32;
+    const float *wt = c->pm.w_f32t;
     const void *in = x;
     int64_t in_stride = prob_stride, ld_in = ld;
     const float *final_scores = nullptr;
     int64_t final_stride = 0;
     for (int l = 0; l < L; ++l) {
-      const int K = m.dims[l], N = m.dims[l + 1];
-      const float *W = wp, *b = wp + (size_t)K * N;
+      const int K = m.dims[l], N = m.dims[l + 1], Npad = (N + 15) / 16 * 16;
+      const float *b = wp + (size_t)K * N;
       float *out = c->d_act[l & 1];
       int64_t out_stride = (int64_t)per_prob, ld_out = ld;
       if (l == L - 1) {
@@ -1297,15 +1322,16 @@ static int score_mlp(vf_ctx *c, const int32_t *x, int64_t prob_stride, int nprob
       dim3 grid((unsigned)((M + 255) / 256), (unsigned)((N + 15) / 16), (unsigned)nprob);
       if (M > 0) {
         if (l == 0)
-          hipLaunchKernelGGL(k_mlp_f32_layer<true>, grid, dim3(256), 0, st, in, in_stride, ld_in, W, b, out,
+          hipLaunchKernelGGL(k_mlp_f32_layer<true>, grid, dim3(256), 0, st, in, in_stride, ld_in, wt, Npad, b, out,
                              out_stride, ld_out, K, N, M, (int)(l < L - 1));
         else
-          hipLaunchKernelGGL(k_mlp_f32_layer<false>, grid, dim3(256), 0, st, in, in_stride, ld_in, W, b, out,
+          hipLaunchKernelGGL(k_mlp_f32_layer<false>, grid, dim3(256), 0, st, in, in_stride, ld_in, wt, Npad, b, out,
                              out_stride, ld_out, K, N, M, (int)(l < L - 1));
         VF_HIP(c, hipGetLastError());
       }
       in = out; in_stride = out_stride; ld_in = ld_out;
       wp = b + N;
+      wt += (size_t)K * Npad;
     }
     if (nparts > 0) {
       hipLaunchKernelGGL(k_argmin_parts, dim3((unsigned)nparts, (unsigned)nprob), dim3(VF_PART), 0, st,
