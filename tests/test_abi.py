@@ -47,3 +47,19 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "one GPU" in (r.stdout + r.stderr)
+
+
+def test_bench_takes_traffic_only_from_a_summary_of_the_same_sources(tmp_path, monkeypatch):
+    """bench.py reports HBM traffic only when the committed counter summary names the hash of the
+    kernel sources being timed and the batch; otherwise the field is null."""
+    import bench
+    sha = bench.kernel_sources_sha256()
+    f = tmp_path / "counters.txt"
+    monkeypatch.setattr(bench, "HBM_PROFILE", str(f))
+    assert bench.measured_traffic("k_whole", 256) is None                     # no summary at all
+    f.write_text(f"# csrc_sha256: {sha}\n# batch: 256\n# traffic_bytes_per_launch k_whole: 12345\n")
+    assert bench.measured_traffic("k_whole", 256) == 12345
+    assert bench.measured_traffic("k_whole", 128) is None                     # another batch
+    assert bench.measured_traffic("k_featurize", 256) is None                 # a kernel the summary does not cover
+    f.write_text(f"# csrc_sha256: {'0' * 64}\n# batch: 256\n# traffic_bytes_per_launch k_whole: 12345\n")
+    assert bench.measured_traffic("k_whole", 256) is None                     # other kernel sources
